@@ -1,0 +1,81 @@
+"""Index-set and mask logic of the oracle (test infrastructure).
+
+Alg. 1: active set (the line defining A_t and L_t), UpdateMASK, locking
+candidates Z_t, the optional confidence gate and the lock rule F_t.
+Plain Python / NumPy loops; integer results are exact.
+"""
+import math
+
+import numpy as np
+
+
+def compact_active(lock):
+    """A_t = {i : lock_i = 0} for a batch.  lock: [B, N] (0/1).
+
+    Returns (active_idx, cu_active): active_idx lists the flat row ids b*N+i of
+    the unlocked positions, sequences in order and positions ascending inside
+    each sequence; cu_active[b] is the number of active rows before sequence b
+    (exclusive prefix sum), cu_active[B] the total M.
+    """
+    lock = np.asarray(lock)
+    B, N = lock.shape
+    idx, cu = [], [0]
+    for b in range(B):
+        for i in range(N):
+            if not lock[b, i]:
+                idx.append(b * N + i)
+        cu.append(len(idx))
+    return np.asarray(idx, dtype=np.int64), np.asarray(cu, dtype=np.int64)
+
+
+def update_mask(masked, tokens, pos, conf, argmax_id, block_lo, block_hi, k):
+    """UpdateMASK for one sequence (confidence-ordered unmasking, temperature 0).
+
+    Among the still-masked positions inside the current semi-autoregressive
+    block [block_lo, block_hi), take the k with the highest posterior maximum
+    ``conf`` (ties: lowest position first), write the argmax token there and
+    clear the masked flag.  pos / conf / argmax_id are parallel arrays over the
+    active rows of this sequence (every masked position is active, because only
+    unmasked positions can ever lock).  masked and tokens are updated in place.
+    Returns the list of positions unmasked, in selection order.
+    """
+    cand = [(-float(conf[r]), int(pos[r]), r) for r in range(len(pos))
+            if masked[pos[r]] and block_lo <= pos[r] < block_hi]
+    cand.sort()
+    chosen = []
+    for _, p, r in cand[:k]:
+        tokens[p] = int(argmax_id[r])
+        masked[p] = 0
+        chosen.append(p)
+    return chosen
+
+
+def percentile_nearest_rank(values, m):
+    """The m-th percentile by nearest rank: the ceil(m/100 * n)-th smallest value
+    (at least the 1st).  The paper leaves the interpolation open; this is the
+    reading taken."""
+    v = sorted(float(x) for x in values)
+    if not v:
+        return -math.inf
+    rank = max(1, math.ceil(m * len(v) / 100.0))
+    return v[rank - 1]
+
+
+def lock_rule(lock, masked_for_candidates, pos, D, u, eps, first_step, gate_m=None):
+    """Z_t = active and unmasked; F_t = {i in Z_t : u_i <= theta_m and D_i <= eps}.
+
+    pos / D / u are parallel arrays over the active rows of one sequence.
+    ``masked_for_candidates`` is the masked flag array the candidate set is
+    built from (Alg. 1 places UpdateMASK before the candidate line, so the
+    literal reading passes the post-update flags).  At the first step D is
+    +inf, so nothing locks.  gate_m=None disables the optional confidence gate.
+    Returns the sorted list of positions to lock (F_t); lock is not modified.
+    """
+    Z = [r for r in range(len(pos)) if not lock[pos[r]] and not masked_for_candidates[pos[r]]]
+    if first_step:
+        return []
+    theta = math.inf
+    if gate_m is not None:
+        theta = percentile_nearest_rank([u[r] for r in Z], gate_m)
+    F = [int(pos[r]) for r in Z if u[r] <= theta and D[r] <= eps]
+    return sorted(F)

@@ -1,0 +1,139 @@
+"""Algorithm 1 (SureLock) and the plain sampler, one sequence at a time
+(test infrastructure; a batch is an independent loop over sequences).
+
+State follows the 'State' lines of Alg. 1: lock, the per-layer K/V caches,
+the previous posteriors, the masked set and the frozen block input x_hat.
+Decisions that a floating-point value takes (ranking by confidence, D <= eps)
+are taken on the value rounded to fp32, the precision the GPU kernels decide in.
+"""
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import control, model, posterior
+
+
+@dataclass
+class State:
+    tokens: np.ndarray            # [N] int64, mask_id on still-masked slots
+    masked: np.ndarray            # [N] uint8, 1 = prediction target (M_t)
+    lock: np.ndarray              # [N] uint8, monotone
+    Kc: list                      # L x [N, H, d_h]
+    Vc: list
+    prev_lp: np.ndarray           # [N, V] log p_{t-1}; rows of locked slots keep log p_{t*}
+    x_hat: np.ndarray             # [N, d] frozen block input (bookkeeping only)
+    lock_step: np.ndarray         # [N] int64, step at which the slot locked (0 = never)
+    t: int = 0
+
+
+@dataclass
+class StepRecord:
+    t: int
+    active_pos: np.ndarray        # A_t, ascending
+    logits: np.ndarray            # [M, V] in active order
+    kl: np.ndarray                # [M] D_t (inf at t = 1)
+    u: np.ndarray                 # [M] 1 - max p
+    conf: np.ndarray              # [M] max p
+    argmax: np.ndarray            # [M]
+    unmasked: list                # positions unmasked at this step, selection order
+    F: list                       # positions the KL rule locks at this step
+    forced: list = field(default_factory=list)   # positions locked by a forced schedule
+
+
+def init_state(cfg, weights, prompt_tokens, n_gen):
+    """Alg. 1 state initialisation: nothing locked, caches empty, no previous
+    posterior, the n_gen generation slots masked, x_hat = prompt embeddings."""
+    n_p = len(prompt_tokens)
+    N = n_p + n_gen
+    tokens = np.concatenate([np.asarray(prompt_tokens, dtype=np.int64),
+                             np.full(n_gen, cfg.mask_id, dtype=np.int64)])
+    masked = np.zeros(N, dtype=np.uint8)
+    masked[n_p:] = 1
+    shape = (N, cfg.n_heads, cfg.d_head)
+    x_hat = np.zeros((N, cfg.d_model))
+    x_hat[:n_p] = weights["emb"][tokens[:n_p]]
+    return State(tokens=tokens, masked=masked, lock=np.zeros(N, dtype=np.uint8),
+                 Kc=[np.full(shape, np.nan) for _ in range(cfg.n_layers)],
+                 Vc=[np.full(shape, np.nan) for _ in range(cfg.n_layers)],
+                 prev_lp=np.full((N, cfg.vocab), np.nan), x_hat=x_hat,
+                 lock_step=np.zeros(N, dtype=np.int64))
+
+
+def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
+                  gate_m=None, candidates_pre_update=False, forced_lock=None,
+                  kl_drives_lock=True):
+    """One iteration of the loop of Alg. 1, in the paper's order.
+
+    eps < 0 can never be met by a KL (>= 0), which turns locking off.
+    forced_lock(st, record) -> list of positions, if given, is a workload hook
+    (not part of the method) that locks further positions after the rule ran;
+    with kl_drives_lock=False the rule's F_t is recorded but not applied.
+    """
+    st.t += 1
+    t = st.t
+    # active / locked sets
+    A = np.flatnonzero(st.lock == 0)
+    tokens_in = st.tokens.copy()
+    # restricted forward on the active rows; live K/V overwrite their cache rows
+    z = model.forward_active(cfg, weights, st.tokens, A, st.Kc, st.Vc)
+    lp = posterior.log_softmax(z)
+    conf = posterior.max_prob(lp)
+    amax = posterior.argmax_lowest(z)
+    # unmasking
+    masked_before = st.masked.copy()
+    unmasked = control.update_mask(st.masked, st.tokens, A,
+                                   conf.astype(np.float32), amax, block_lo, block_hi, k)
+    # score
+    u = posterior.uncertainty(lp)
+    if t > 1:
+        D = posterior.kl_rows(lp, st.prev_lp[A])
+    else:
+        D = np.full(len(A), np.inf)
+    # candidates and lock rule
+    m_for_Z = masked_before if candidates_pre_update else st.masked
+    F = control.lock_rule(st.lock, m_for_Z, A, D.astype(np.float32), u.astype(np.float32),
+                          np.float32(eps), first_step=(t == 1), gate_m=gate_m)
+    rec = StepRecord(t=t, active_pos=A, logits=z, kl=D, u=u, conf=conf, argmax=amax,
+                     unmasked=unmasked, F=F)
+    # posteriors of the active rows become p_{t-1}; locked rows keep p_{t*}
+    st.prev_lp[A] = lp
+    to_lock = list(F) if kl_drives_lock else []
+    if forced_lock is not None:
+        rec.forced = [int(p) for p in forced_lock(st, rec)]
+        to_lock = sorted(set(to_lock) | set(rec.forced))
+    for p in to_lock:
+        # K/V of p were written into Kc/Vc by this step's forward and are never
+        # written again: that is the cache commit of the lock line.
+        st.lock[p] = 1
+        st.lock_step[p] = t
+        st.x_hat[p] = weights["emb"][tokens_in[p]]
+    return rec
+
+
+def baseline_step(cfg, weights, tokens, masked, block_lo, block_hi, k):
+    """One step of the same sampler without locking: full recompute of all N
+    positions, then UpdateMASK.  Returns (logits [N, V], K list, V list, unmasked)."""
+    z, Ks, Vs = model.forward_full(cfg, weights, tokens)
+    lp = posterior.log_softmax(z)
+    conf = posterior.max_prob(lp).astype(np.float32)
+    amax = posterior.argmax_lowest(z)
+    unmasked = control.update_mask(masked, tokens, np.arange(len(tokens)), conf, amax,
+                                   block_lo, block_hi, k)
+    return z, Ks, Vs, unmasked
+
+
+def block_schedule(n_prompt, n_gen, block_len, T):
+    """Semi-autoregressive schedule: the generation region is cut into blocks of
+    block_len slots, each block gets T / n_blocks consecutive steps and
+    block_len / steps_per_block tokens are unmasked per step.
+    Returns a list over steps of (block_lo, block_hi, k)."""
+    n_blocks = n_gen // block_len
+    assert n_blocks * block_len == n_gen and T % n_blocks == 0
+    spb = T // n_blocks
+    assert block_len % spb == 0
+    k = block_len // spb
+    out = []
+    for t in range(T):
+        b = t // spb
+        out.append((n_prompt + b * block_len, n_prompt + (b + 1) * block_len, k))
+    return out
