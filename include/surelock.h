@@ -1,0 +1,202 @@
+/*
+ * libsurelock: the per-step hot path of SureLock (Oba et al., "Stopping
+ * Computation for Converged Tokens in Masked Diffusion-LM Decoding") as HIP
+ * kernels for gfx950 (MI355X), behind a plain C ABI.
+ *
+ * One diffusion step (Algorithm 1, body of the loop over t) restricted to the
+ * M unlocked ("active") positions of B sequences of N slots each:
+ *   active-set compaction -> embedding gather -> L x [ RMSNorm, Q/K/V projection,
+ *   RoPE, K/V write into the frozen-plus-live cache, bidirectional M x N
+ *   attention over all N cached slots, Out projection, SwiGLU FFN ] -> final
+ *   RMSNorm + LM head -> posterior scoring (step-wise KL, confidence, argmax)
+ *   -> UpdateMASK -> candidates and the lock rule.
+ *
+ * Conventions for every entry point
+ *  - All tensor arguments are DEVICE pointers unless the comment says "host".
+ *    The library never allocates or frees device memory: the caller owns every
+ *    buffer (weights, caches, workspace, outputs) and passes raw pointers.
+ *  - `stream` is a hipStream_t passed as void*; calls only enqueue work on it
+ *    and return without synchronising.  Buffers must stay valid until the
+ *    stream has drained.
+ *  - Return value: 0 (SL_OK) or a negative sl_status.  Arguments are validated
+ *    on the host before anything is launched, so SL_EINVAL / SL_ENOSPC never
+ *    leave partial work behind.  Nothing throws or aborts.
+ *  - Row ids: a position i of sequence b has the flat row id g = b*N + i.
+ *    "Packed" arrays have one entry per active row, in the order of active_idx.
+ *  - Storage type T is bf16 (SL_BF16) or fp32 (SL_F32); all arithmetic
+ *    accumulates in fp32.  Tensors that live in memory between operators are
+ *    rounded to T (nearest-even) at: RMSNorm output; q and k after RoPE, v;
+ *    attention output; the residual stream after each add; silu(gate)*up; logits.
+ */
+#ifndef SURELOCK_H
+#define SURELOCK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sl_status {
+  SL_OK = 0,
+  SL_EINVAL = -1,   /* null pointer, bad shape, bad dtype, misaligned pointer      */
+  SL_ENOSPC = -2,   /* a caller-provided buffer (workspace, cache, store) too small */
+  SL_EHIP = -3,     /* a HIP call failed; see sl_last_hip_error()                   */
+  SL_ESTATE = -4    /* call order violated (e.g. step before the cache is bound)    */
+} sl_status;
+
+enum { SL_F32 = 0, SL_BF16 = 1 };
+
+/* Model shape.  The block is the pre-RMSNorm / RoPE / SwiGLU block with multi-head
+ * attention (H_kv = H), the one whose GEMMs the paper's algorithmic-FLOP count
+ * lists (Sec. 2.4): Q, K, V, Out projections and a three-matrix FFN. */
+typedef struct sl_config {
+  int32_t n_layers, d_model, n_heads, d_head, d_ff, vocab;
+  int32_t dtype;        /* SL_F32 or SL_BF16: storage type T of weights and activations */
+  int32_t mask_id;      /* token id of [MASK] (only used for validation)                */
+  float rms_eps;
+  float rope_theta;
+} sl_config;
+
+/* Plain weights, caller-owned device memory of type T, `[out_features, in_features]`
+ * row-major (y = x W^T).  Norm gains are vectors of d_model. */
+typedef struct sl_layer_weights {
+  const void *attn_norm;            /* [d]        */
+  const void *wq, *wk, *wv;         /* [H*d_h, d] */
+  const void *wo;                   /* [d, H*d_h] */
+  const void *ffn_norm;             /* [d]        */
+  const void *w_gate, *w_up;        /* [d_ff, d]  */
+  const void *w_down;               /* [d, d_ff]  */
+} sl_layer_weights;
+
+typedef struct sl_weights {
+  const void *emb;                  /* [vocab, d] */
+  const void *final_norm;           /* [d]        */
+  const void *lm_head;              /* [vocab, d] */
+  const sl_layer_weights *layers;   /* HOST array of n_layers entries */
+} sl_weights;
+
+typedef struct sl_ctx sl_ctx;       /* host-side descriptors only */
+
+/* ---- lifetime ------------------------------------------------------------------ */
+
+/* Create a context for one model shape.  Allocates host memory only. */
+int sl_init(const sl_config *cfg, sl_ctx **out);
+int sl_destroy(sl_ctx *ctx);
+const char *sl_strerror(int status);
+/* hipError_t value of the most recent failed HIP call on this thread (0 if none). */
+int sl_last_hip_error(void);
+
+/* Size of, and conversion into, the library's private weight layout.  For bf16
+ * models whose dimensions are multiples of the MFMA tile the projection matrices
+ * are re-tiled so that each wavefront's MFMA operand fragment is one contiguous,
+ * fully coalesced 1 KiB read (Q/K/V fused into one matrix, gate/up fused into
+ * one); other models reference the plain matrices and need 0 extra bytes.  The
+ * plain weights (at least emb and the norm gains) must outlive the context.
+ * Enqueues the re-tiling kernels on `stream`. */
+int sl_packed_weights_bytes(const sl_ctx *ctx, size_t *out);
+int sl_bind_weights(sl_ctx *ctx, void *stream, const sl_weights *plain /* host struct */,
+                    void *packed, size_t packed_bytes);
+
+/* ---- state: Alg. 1 'State' lines ---------------------------------------------------
+ * K/V cache (the caches C for (k, v), all layers): "frozen plus live".  Every active
+ * row overwrites its own cache row at every step (the 'assemble' line); a locked row
+ * is simply never written again, which is the cache commit of the lock line.
+ * Layout (T elements), n_pad = N rounded up to 64:
+ *   K: [L][B][H][n_pad][d_h]            post-RoPE keys, one 2*d_h-byte row per slot
+ *   V: [L][B][H][n_pad/8][d_h][8]       values, 8 consecutive slots interleaved so the
+ *                                       P.V MFMA operand is a contiguous 16-byte read
+ * sl_kv_cache_bind zero-fills the buffer (enqueued on `stream`). */
+int sl_kv_cache_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
+int sl_kv_cache_bind(sl_ctx *ctx, void *stream, void *kv, size_t bytes, int32_t batch, int32_t n_seq);
+/* Copy layer `layer`'s K and V out in the plain layout [B, N, H, d_h] (type T). */
+int sl_kv_cache_read(const sl_ctx *ctx, void *stream, int32_t layer, void *k_out, void *v_out);
+
+/* Previous posteriors p_{t-1} (Alg. 1 state; Sec. 2.1: a locked row keeps p_{t*}).
+ * Stored in factored form as the rows' logits (type T): log p = z - logsumexp(z) is
+ * recomputed on the fly by the KL pass, which needs both rows anyway.  Two buffers
+ * [2][B*N][vocab] alternate: step t writes the logits of its active rows into buffer
+ * t & 1 (rows by flat id) and reads p_{t-1} from buffer (t-1) & 1. */
+int sl_posterior_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
+int sl_posterior_bind(sl_ctx *ctx, void *store, size_t bytes);
+/* Device pointer to the [B*N, vocab] logits buffer that step t writes (host out). */
+int sl_logits_ptr(const sl_ctx *ctx, int32_t t, void **out);
+
+int sl_workspace_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
+
+/* ---- the step ---------------------------------------------------------------------
+ * One iteration of the loop of Alg. 1 for all B sequences.
+ *   tokens  [B*N] i32  in/out  current token ids; UpdateMASK writes argmax ids
+ *   masked  [B*N] u8   in/out  1 = still [MASK] (the set M_t); UpdateMASK clears
+ *   lock    [B*N] u8   in      lock mask at the start of the step
+ *   eps     [B]   f32  in      per-sequence KL threshold (lock iff D <= eps)
+ *   t                  host    1-based step index; at t = 1 D = +inf and nothing locks
+ *   block_lo/hi, k     host    UpdateMASK unmasks the k most confident still-masked
+ *                              positions with block_lo <= i < block_hi in each sequence
+ *   m_upper            host    an upper bound on the number of active rows (B*N is
+ *                              always valid); launches are sized by it, rows beyond
+ *                              the true M exit early
+ *   active_idx [>=m_upper] i32 out  flat ids of active rows, ascending
+ *   cu_active  [B+1]   i32 out  exclusive prefix sums of per-sequence counts; [B] = M
+ *   kl, conf [>=m_upper] f32 out  D_t and max_v p_t per active row (u = 1 - conf)
+ *   argmax   [>=m_upper] i32 out  argmax_v p_t (lowest id on ties)
+ *   new_lock [B*N] u8  out     lock | F_t   (may alias lock)
+ * Logits of the active rows land in the posterior store (sl_logits_ptr(t)). */
+int sl_surelock_step(sl_ctx *ctx, void *stream, int32_t *tokens, uint8_t *masked,
+                     const uint8_t *lock, const float *eps, int32_t t,
+                     int32_t block_lo, int32_t block_hi, int32_t k, int32_t m_upper,
+                     int32_t *active_idx, int32_t *cu_active, float *kl, float *conf,
+                     int32_t *argmax, uint8_t *new_lock, void *workspace, size_t workspace_bytes);
+
+/* The restricted forward alone (Alg. 1, 'Compute on active positions'), layers
+ * [layer_lo, layer_hi) on given block inputs: x_in [m_upper, d] (type T, packed in
+ * active order) -> x_out [m_upper, d].  Writes the active rows' K/V into the cache.
+ * m_dev points to the device int holding the true M (e.g. cu_active + B). */
+int sl_forward_layers(sl_ctx *ctx, void *stream, const void *x_in, void *x_out,
+                      const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
+                      int32_t layer_lo, int32_t layer_hi, void *workspace, size_t workspace_bytes);
+
+/* ---- the controller pieces, callable on given logits ---------------------------- */
+
+/* Alg. 1 'A_t <- {i | lock_i = 0}': stable compaction of the unlocked flat ids. */
+int sl_compact_active(void *stream, const uint8_t *lock, int32_t batch, int32_t n_seq,
+                      int32_t *active_idx, int32_t *cu_active);
+
+/* Alg. 1 'Score on active positions' (+ argmax): for each active row r with flat id
+ * g = active_idx[r]:  D = KL(softmax(cur row) || softmax(prev row)) in nats, conf =
+ * max softmax(cur row), argmax.  cur row = logits_cur + (cur_packed ? r : g)*vocab,
+ * prev row = logits_prev + g*vocab; dtype SL_F32 / SL_BF16; vocab % 8 == 0.
+ * first_step != 0: logits_prev is not read and D = +inf. */
+int sl_score_posteriors(void *stream, const void *logits_cur, int32_t cur_packed,
+                        const void *logits_prev, int32_t dtype, int32_t vocab,
+                        const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
+                        int32_t first_step, float *kl, float *conf, int32_t *argmax);
+
+/* UpdateMASK (confidence-ordered unmasking at temperature 0): per sequence, the k
+ * still-masked positions inside [block_lo, block_hi) with the highest conf (ties:
+ * lowest position) get tokens[g] = argmax[r], masked[g] = 0. */
+int sl_unmask_topk(void *stream, int32_t *tokens, uint8_t *masked, const int32_t *active_idx,
+                   const int32_t *cu_active, const float *conf, const int32_t *argmax,
+                   int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi, int32_t k);
+
+/* Candidates Z_t = active and unmasked; F_t = {i in Z_t : D_i <= eps_b}; new_lock =
+ * lock | F_t (gate disabled).  first_step != 0 locks nothing. */
+int sl_lock_rule(void *stream, const uint8_t *lock, const uint8_t *masked,
+                 const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
+                 const float *kl, const float *eps, int32_t batch, int32_t n_seq,
+                 int32_t first_step, uint8_t *new_lock);
+
+/* lock_test(eps): Alg. 1 from 'Unmasking' to 'Lock' on given logits = score ->
+ * UpdateMASK -> candidates -> lock rule, in that order. */
+int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const void *logits_prev,
+                 int32_t dtype, int32_t vocab, int32_t *tokens, uint8_t *masked, const uint8_t *lock,
+                 const int32_t *active_idx, const int32_t *cu_active, int32_t m_upper,
+                 const float *eps, int32_t batch, int32_t n_seq, int32_t first_step,
+                 int32_t block_lo, int32_t block_hi, int32_t k,
+                 float *kl, float *conf, int32_t *argmax, uint8_t *new_lock);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SURELOCK_H */

@@ -1,0 +1,280 @@
+"""ctypes binding of libsurelock.so: the same entry points as include/surelock.h, taking
+torch tensors (device memory) and Python ints.  Argument marshalling only: every step of the
+path runs in the HIP kernels.  There is no fallback: a missing library raises."""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsurelock.so")
+
+SL_F32, SL_BF16 = 0, 1
+SL_OK, SL_EINVAL, SL_ENOSPC, SL_EHIP, SL_ESTATE = 0, -1, -2, -3, -4
+
+
+class sl_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("d_head", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
+                ("dtype", C.c_int32), ("mask_id", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+
+
+class sl_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm",
+                                          "w_gate", "w_up", "w_down")]
+
+
+class sl_weights(C.Structure):
+    _fields_ = [("emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p),
+                ("layers", C.POINTER(sl_layer_weights))]
+
+
+_P, _I, _Z = C.c_void_p, C.c_int32, C.c_size_t
+_SIGS = {
+    "sl_init": [C.POINTER(sl_config), C.POINTER(_P)],
+    "sl_destroy": [_P],
+    "sl_last_hip_error": [],
+    "sl_packed_weights_bytes": [_P, C.POINTER(_Z)],
+    "sl_bind_weights": [_P, _P, C.POINTER(sl_weights), _P, _Z],
+    "sl_kv_cache_bytes": [_P, _I, _I, C.POINTER(_Z)],
+    "sl_kv_cache_bind": [_P, _P, _P, _Z, _I, _I],
+    "sl_kv_cache_read": [_P, _P, _I, _P, _P],
+    "sl_posterior_bytes": [_P, _I, _I, C.POINTER(_Z)],
+    "sl_posterior_bind": [_P, _P, _Z],
+    "sl_logits_ptr": [_P, _I, C.POINTER(_P)],
+    "sl_workspace_bytes": [_P, _I, _I, C.POINTER(_Z)],
+    "sl_surelock_step": [_P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
+    "sl_forward_layers": [_P, _P, _P, _P, _P, _P, _I, _I, _I, _P, _Z],
+    "sl_compact_active": [_P, _P, _I, _I, _P, _P],
+    "sl_score_posteriors": [_P, _P, _I, _P, _I, _I, _P, _P, _I, _I, _P, _P, _P],
+    "sl_unmask_topk": [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I],
+    "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
+    "sl_lock_test": [_P, _P, _I, _P, _I, _I, _P, _P, _P, _P, _P, _I, _P, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P],
+}
+EXPORTS = sorted(list(_SIGS) + ["sl_strerror"])
+
+_lib = None
+
+
+def lib():
+    """The loaded C-ABI library (opened on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2602_06412_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, args in _SIGS.items():
+            fn = getattr(l, name)
+            fn.argtypes = args
+            fn.restype = C.c_int
+        l.sl_strerror.argtypes = [C.c_int]
+        l.sl_strerror.restype = C.c_char_p
+        _lib = l
+    return _lib
+
+
+class SureLockError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        msg = lib().sl_strerror(status).decode()
+        if status == SL_EHIP:
+            msg += f" [hipError {lib().sl_last_hip_error()}]"
+        super().__init__(f"{fn}: {msg} ({status})")
+
+
+def _check(fn, status):
+    if status != SL_OK:
+        raise SureLockError(fn, status)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def dtype_code(dt):
+    return {torch.float32: SL_F32, torch.bfloat16: SL_BF16}[dt]
+
+
+def make_config(shape):
+    return sl_config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab,
+                     {"fp32": SL_F32, "bf16": SL_BF16}[shape.storage], shape.mask_id, shape.rms_eps,
+                     shape.rope_theta)
+
+
+# ---- entry points, same names as the header -------------------------------------------------
+def sl_init(cfg):
+    h = _P()
+    _check("sl_init", lib().sl_init(C.byref(cfg), C.byref(h)))
+    return h
+
+
+def sl_destroy(ctx):
+    _check("sl_destroy", lib().sl_destroy(ctx))
+
+
+def _size_query(name, ctx, *args):
+    out = _Z()
+    _check(name, getattr(lib(), name)(ctx, *args, C.byref(out)))
+    return out.value
+
+
+def sl_packed_weights_bytes(ctx):
+    return _size_query("sl_packed_weights_bytes", ctx)
+
+
+def sl_kv_cache_bytes(ctx, batch, n_seq):
+    return _size_query("sl_kv_cache_bytes", ctx, batch, n_seq)
+
+
+def sl_posterior_bytes(ctx, batch, n_seq):
+    return _size_query("sl_posterior_bytes", ctx, batch, n_seq)
+
+
+def sl_workspace_bytes(ctx, batch, n_seq):
+    return _size_query("sl_workspace_bytes", ctx, batch, n_seq)
+
+
+def sl_bind_weights(ctx, weights, packed):
+    """weights: dict as made by workloads.make_weights (device tensors); packed: uint8 buffer."""
+    n = len(weights["layers"])
+    arr = (sl_layer_weights * n)()
+    for i, l in enumerate(weights["layers"]):
+        for f, _ in sl_layer_weights._fields_:
+            setattr(arr[i], f, l[f].data_ptr())
+    w = sl_weights(weights["emb"].data_ptr(), weights["final_norm"].data_ptr(), weights["lm_head"].data_ptr(), arr)
+    _check("sl_bind_weights", lib().sl_bind_weights(ctx, _stream(), C.byref(w), _ptr(packed),
+                                                    packed.numel() if packed is not None else 0))
+
+
+def sl_kv_cache_bind(ctx, kv, batch, n_seq):
+    _check("sl_kv_cache_bind", lib().sl_kv_cache_bind(ctx, _stream(), _ptr(kv), kv.numel(), batch, n_seq))
+
+
+def sl_kv_cache_read(ctx, layer, k_out, v_out):
+    _check("sl_kv_cache_read", lib().sl_kv_cache_read(ctx, _stream(), layer, _ptr(k_out), _ptr(v_out)))
+
+
+def sl_posterior_bind(ctx, store):
+    _check("sl_posterior_bind", lib().sl_posterior_bind(ctx, _ptr(store), store.numel()))
+
+
+def sl_logits_ptr(ctx, t):
+    out = _P()
+    _check("sl_logits_ptr", lib().sl_logits_ptr(ctx, t, C.byref(out)))
+    return out.value
+
+
+def sl_surelock_step(ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, active_idx, cu_active,
+                     kl, conf, argmax, new_lock, workspace):
+    _check("sl_surelock_step", lib().sl_surelock_step(
+        ctx, _stream(), _ptr(tokens), _ptr(masked), _ptr(lock), _ptr(eps), t, block_lo, block_hi, k, m_upper,
+        _ptr(active_idx), _ptr(cu_active), _ptr(kl), _ptr(conf), _ptr(argmax), _ptr(new_lock), _ptr(workspace),
+        workspace.numel()))
+
+
+def sl_forward_layers(ctx, x_in, x_out, active_idx, m_dev, m_upper, layer_lo, layer_hi, workspace):
+    _check("sl_forward_layers", lib().sl_forward_layers(
+        ctx, _stream(), _ptr(x_in), _ptr(x_out), _ptr(active_idx), _ptr(m_dev), m_upper, layer_lo, layer_hi,
+        _ptr(workspace), workspace.numel()))
+
+
+def sl_compact_active(lock, batch, n_seq, active_idx, cu_active):
+    _check("sl_compact_active", lib().sl_compact_active(_stream(), _ptr(lock), batch, n_seq, _ptr(active_idx),
+                                                        _ptr(cu_active)))
+
+
+def sl_score_posteriors(logits_cur, cur_packed, logits_prev, dtype, vocab, active_idx, m_dev, m_upper, first_step,
+                        kl, conf, argmax):
+    _check("sl_score_posteriors", lib().sl_score_posteriors(
+        _stream(), _ptr(logits_cur), int(cur_packed), _ptr(logits_prev), dtype, vocab, _ptr(active_idx), _ptr(m_dev),
+        m_upper, int(first_step), _ptr(kl), _ptr(conf), _ptr(argmax)))
+
+
+def sl_unmask_topk(tokens, masked, active_idx, cu_active, conf, argmax, batch, n_seq, block_lo, block_hi, k):
+    _check("sl_unmask_topk", lib().sl_unmask_topk(_stream(), _ptr(tokens), _ptr(masked), _ptr(active_idx),
+                                                  _ptr(cu_active), _ptr(conf), _ptr(argmax), batch, n_seq, block_lo,
+                                                  block_hi, k))
+
+
+def sl_lock_rule(lock, masked, active_idx, m_dev, m_upper, kl, eps, batch, n_seq, first_step, new_lock):
+    _check("sl_lock_rule", lib().sl_lock_rule(_stream(), _ptr(lock), _ptr(masked), _ptr(active_idx), _ptr(m_dev),
+                                              m_upper, _ptr(kl), _ptr(eps), batch, n_seq, int(first_step),
+                                              _ptr(new_lock)))
+
+
+def sl_lock_test(logits_cur, cur_packed, logits_prev, dtype, vocab, tokens, masked, lock, active_idx, cu_active,
+                 m_upper, eps, batch, n_seq, first_step, block_lo, block_hi, k, kl, conf, argmax, new_lock):
+    _check("sl_lock_test", lib().sl_lock_test(
+        _stream(), _ptr(logits_cur), int(cur_packed), _ptr(logits_prev), dtype, vocab, _ptr(tokens), _ptr(masked),
+        _ptr(lock), _ptr(active_idx), _ptr(cu_active), m_upper, _ptr(eps), batch, n_seq, int(first_step), block_lo,
+        block_hi, k, _ptr(kl), _ptr(conf), _ptr(argmax), _ptr(new_lock)))
+
+
+# ---- device-memory plumbing for one model + one batch geometry ---------------------------------
+class Session:
+    """Owns the torch buffers a context needs (packed weights, K/V cache, posterior store,
+    workspace, per-step outputs) and forwards to the entry points above."""
+
+    def __init__(self, shape, weights, batch, n_seq, device="cuda:0"):
+        self.shape, self.B, self.N, self.device = shape, batch, n_seq, torch.device(device)
+        self.weights = weights
+        self.T = {"fp32": torch.float32, "bf16": torch.bfloat16}[shape.storage]
+        self.ctx = sl_init(make_config(shape))
+        dev = self.device
+        u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
+        self.packed = u8(sl_packed_weights_bytes(self.ctx))
+        sl_bind_weights(self.ctx, weights, self.packed)
+        self.kv = u8(sl_kv_cache_bytes(self.ctx, batch, n_seq))
+        sl_kv_cache_bind(self.ctx, self.kv, batch, n_seq)
+        self.post = u8(sl_posterior_bytes(self.ctx, batch, n_seq))
+        sl_posterior_bind(self.ctx, self.post)
+        self.workspace = u8(sl_workspace_bytes(self.ctx, batch, n_seq))
+        R = batch * n_seq
+        self.active_idx = torch.zeros(R, dtype=torch.int32, device=dev)
+        self.cu_active = torch.zeros(batch + 1, dtype=torch.int32, device=dev)
+        self.kl = torch.zeros(R, dtype=torch.float32, device=dev)
+        self.conf = torch.zeros(R, dtype=torch.float32, device=dev)
+        self.argmax = torch.zeros(R, dtype=torch.int32, device=dev)
+
+    def close(self):
+        if self.ctx is not None:
+            torch.cuda.synchronize()
+            sl_destroy(self.ctx)
+            self.ctx = None
+
+    def step(self, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper=None, new_lock=None):
+        m_upper = self.B * self.N if m_upper is None else m_upper
+        new_lock = lock if new_lock is None else new_lock
+        sl_surelock_step(self.ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, self.active_idx,
+                         self.cu_active, self.kl, self.conf, self.argmax, new_lock, self.workspace)
+        return new_lock
+
+    def logits_view(self, t):
+        """[B*N, V] tensor view of the posterior buffer step t writes (rows by flat id)."""
+        buf = self.post.view(self.T)
+        per = buf.numel() // 2
+        R, V = self.B * self.N, self.shape.vocab
+        return buf[(t & 1) * per:(t & 1) * per + R * V].view(R, V)
+
+    def forward_layers(self, x_in, active_idx, m_dev, m_upper, layer_lo=0, layer_hi=None):
+        layer_hi = self.shape.n_layers if layer_hi is None else layer_hi
+        x_out = torch.empty_like(x_in)
+        sl_forward_layers(self.ctx, x_in, x_out, active_idx, m_dev, m_upper, layer_lo, layer_hi, self.workspace)
+        return x_out
+
+    def kv_read(self, layer):
+        s = self.shape
+        k = torch.empty(self.B, self.N, s.n_heads, s.d_head, dtype=self.T, device=self.device)
+        v = torch.empty_like(k)
+        sl_kv_cache_read(self.ctx, layer, k, v)
+        return k, v

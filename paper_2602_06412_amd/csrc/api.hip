@@ -1,0 +1,352 @@
+// C-ABI of libsurelock: argument validation, buffer carving and the launch sequence of one
+// SureLock step.  Everything here runs on the host; no device memory is allocated.
+#include "sl_common.h"
+#include <new>
+#include <string.h>
+
+thread_local int g_sl_last_hip_error = 0;
+
+extern "C" int sl_last_hip_error(void) { return g_sl_last_hip_error; }
+
+extern "C" const char* sl_strerror(int status) {
+  switch (status) {
+    case SL_OK: return "ok";
+    case SL_EINVAL: return "invalid argument (null pointer, shape, dtype or alignment)";
+    case SL_ENOSPC: return "caller-provided buffer too small";
+    case SL_EHIP: return "HIP runtime error (see sl_last_hip_error)";
+    case SL_ESTATE: return "call order violated (weights, K/V cache or posterior store not bound)";
+    default: return "unknown status";
+  }
+}
+
+static bool cfg_ok(const sl_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->d_head < 2 || c->d_ff < 8 || c->vocab < 8) return false;
+  if (c->dtype != SL_F32 && c->dtype != SL_BF16) return false;
+  if (!(c->d_head == 32 || c->d_head == 64 || c->d_head == 128 || c->d_head == 256)) return false;
+  if (c->vocab % 8 || c->d_model % 8 || c->d_ff % 8) return false;
+  if (c->mask_id < 0 || c->mask_id >= c->vocab) return false;
+  if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return false;
+  return true;
+}
+
+extern "C" int sl_init(const sl_config* cfg, sl_ctx** out) {
+  if (!out) return SL_EINVAL;
+  *out = nullptr;
+  if (!cfg_ok(cfg)) return SL_EINVAL;
+  sl_ctx* c = new (std::nothrow) sl_ctx();
+  if (!c) return SL_ENOSPC;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  c->layers = new (std::nothrow) sl_layer_weights[cfg->n_layers];
+  c->packed = new (std::nothrow) sl_packed_layer[cfg->n_layers];
+  if (!c->layers || !c->packed) { delete[] c->layers; delete[] c->packed; delete c; return SL_ENOSPC; }
+  memset(c->packed, 0, sizeof(sl_packed_layer) * cfg->n_layers);
+  c->use_mfma = sl_mfma_supported(cfg);
+  *out = c;
+  return SL_OK;
+}
+
+extern "C" int sl_destroy(sl_ctx* ctx) {
+  if (!ctx) return SL_EINVAL;
+  delete[] ctx->layers;
+  delete[] ctx->packed;
+  delete ctx;
+  return SL_OK;
+}
+
+// ---- weights -----------------------------------------------------------------------------------
+extern "C" int sl_packed_weights_bytes(const sl_ctx* ctx, size_t* out) {
+  if (!ctx || !out) return SL_EINVAL;
+  *out = ctx->use_mfma ? sl_mfma_packed_bytes(&ctx->cfg) : 0;
+  return SL_OK;
+}
+
+extern "C" int sl_bind_weights(sl_ctx* ctx, void* stream, const sl_weights* w, void* packed, size_t packed_bytes) {
+  if (!ctx || !w || !w->emb || !w->final_norm || !w->lm_head || !w->layers) return SL_EINVAL;
+  for (int l = 0; l < ctx->cfg.n_layers; ++l) {
+    const sl_layer_weights& L = w->layers[l];
+    if (!L.attn_norm || !L.wq || !L.wk || !L.wv || !L.wo || !L.ffn_norm || !L.w_gate || !L.w_up || !L.w_down)
+      return SL_EINVAL;
+  }
+  if (ctx->use_mfma) {
+    if (!packed) return SL_EINVAL;
+    if (packed_bytes < sl_mfma_packed_bytes(&ctx->cfg)) return SL_ENOSPC;
+    if ((uintptr_t)packed % 256) return SL_EINVAL;
+  }
+  ctx->plain = *w;
+  memcpy(ctx->layers, w->layers, sizeof(sl_layer_weights) * ctx->cfg.n_layers);
+  ctx->plain.layers = ctx->layers;
+  if (ctx->use_mfma) {
+    const int rc = sl_mfma_pack_all(ctx, (hipStream_t)stream, packed);
+    if (rc != SL_OK) return rc;
+  }
+  ctx->weights_bound = true;
+  return SL_OK;
+}
+
+// ---- K/V cache ---------------------------------------------------------------------------------
+static size_t rope_tab_bytes(const sl_config& c, int n_pad) {
+  return sl_align_up((size_t)n_pad * (c.d_head / 2) * sizeof(float2), 256);
+}
+
+extern "C" int sl_kv_cache_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
+  if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
+  const sl_config& c = ctx->cfg;
+  const int n_pad = (int)sl_align_up(n_seq, 64);
+  const size_t layer = (size_t)batch * c.n_heads * n_pad * c.d_head;
+  *out = rope_tab_bytes(c, n_pad) + 2 * (size_t)c.n_layers * layer * sl_tsize(c.dtype);
+  return SL_OK;
+}
+
+extern "C" int sl_kv_cache_bind(sl_ctx* ctx, void* stream, void* kv, size_t bytes, int32_t batch, int32_t n_seq) {
+  size_t need = 0;
+  const int rc = sl_kv_cache_bytes(ctx, batch, n_seq, &need);
+  if (rc != SL_OK) return rc;
+  if (!kv || (uintptr_t)kv % 256) return SL_EINVAL;
+  if (bytes < need) return SL_ENOSPC;
+  if ((size_t)batch * n_seq > (size_t)1 << 30) return SL_EINVAL;
+  const sl_config& c = ctx->cfg;
+  ctx->kv = kv;
+  ctx->batch = batch;
+  ctx->n_seq = n_seq;
+  ctx->n_pad = (int)sl_align_up(n_seq, 64);
+  ctx->kv_layer_elems = (size_t)batch * c.n_heads * ctx->n_pad * c.d_head;
+  int r2 = slk_fill_zero((hipStream_t)stream, kv, need);
+  if (r2 != SL_OK) return r2;
+  return slk_rope_table((hipStream_t)stream, kv, ctx->n_pad, c.d_head, c.rope_theta);
+}
+
+static inline char* kv_k_layer(const sl_ctx* ctx, int l) {
+  const size_t ts = sl_tsize(ctx->cfg.dtype);
+  return (char*)ctx->kv + rope_tab_bytes(ctx->cfg, ctx->n_pad) + (size_t)l * ctx->kv_layer_elems * ts;
+}
+static inline char* kv_v_layer(const sl_ctx* ctx, int l) {
+  const size_t ts = sl_tsize(ctx->cfg.dtype);
+  return kv_k_layer(ctx, ctx->cfg.n_layers) + (size_t)l * ctx->kv_layer_elems * ts;
+}
+
+extern "C" int sl_kv_cache_read(const sl_ctx* ctx, void* stream, int32_t layer, void* k_out, void* v_out) {
+  if (!ctx || !k_out || !v_out) return SL_EINVAL;
+  if (!ctx->kv) return SL_ESTATE;
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return SL_EINVAL;
+  return slk_kv_read((hipStream_t)stream, ctx->cfg.dtype, kv_k_layer(ctx, layer), kv_v_layer(ctx, layer), ctx->batch,
+                     ctx->cfg.n_heads, ctx->n_seq, ctx->n_pad, ctx->cfg.d_head, k_out, v_out);
+}
+
+// ---- posterior store -----------------------------------------------------------------------------
+extern "C" int sl_posterior_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
+  if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
+  *out = 2 * sl_align_up((size_t)batch * n_seq * ctx->cfg.vocab * sl_tsize(ctx->cfg.dtype), 256);
+  return SL_OK;
+}
+
+extern "C" int sl_posterior_bind(sl_ctx* ctx, void* store, size_t bytes) {
+  if (!ctx || !store || (uintptr_t)store % 256) return SL_EINVAL;
+  if (!ctx->kv) return SL_ESTATE;          // batch / n_seq come from the cache binding
+  size_t need = 0;
+  sl_posterior_bytes(ctx, ctx->batch, ctx->n_seq, &need);
+  if (bytes < need) return SL_ENOSPC;
+  ctx->post = store;
+  ctx->post_buf_elems = need / 2 / sl_tsize(ctx->cfg.dtype);
+  return SL_OK;
+}
+
+extern "C" int sl_logits_ptr(const sl_ctx* ctx, int32_t t, void** out) {
+  if (!ctx || !out || t < 0) return SL_EINVAL;
+  if (!ctx->post) return SL_ESTATE;
+  *out = (char*)ctx->post + (size_t)(t & 1) * ctx->post_buf_elems * sl_tsize(ctx->cfg.dtype);
+  return SL_OK;
+}
+
+// ---- workspace -----------------------------------------------------------------------------------
+struct Workspace {
+  char *x, *h, *q, *o, *a;
+  float* f32;
+  size_t bytes;
+};
+
+static Workspace carve(const sl_ctx* ctx, void* base, int rows) {
+  const sl_config& c = ctx->cfg;
+  const size_t ts = sl_tsize(c.dtype);
+  const size_t hd = (size_t)c.n_heads * c.d_head;
+  size_t f32_cols = 3 * hd;
+  if ((size_t)2 * c.d_ff > f32_cols) f32_cols = (size_t)2 * c.d_ff;
+  if ((size_t)c.d_model > f32_cols) f32_cols = c.d_model;
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t n) { char* p = (char*)base + off; off += sl_align_up(n, 256); return p; };
+  w.x = take((size_t)rows * c.d_model * ts);
+  w.h = take((size_t)rows * c.d_model * ts);
+  w.q = take((size_t)rows * hd * ts);
+  w.o = take((size_t)rows * hd * ts);
+  w.a = take((size_t)rows * c.d_ff * ts);
+  w.f32 = (float*)take((size_t)rows * f32_cols * sizeof(float));
+  w.bytes = off;
+  return w;
+}
+
+extern "C" int sl_workspace_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
+  if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
+  *out = carve(ctx, nullptr, batch * n_seq).bytes;
+  return SL_OK;
+}
+
+// ---- the restricted forward ------------------------------------------------------------------------
+#define SL_TRY(expr) do { const int rc_ = (expr); if (rc_ != SL_OK) return rc_; } while (0)
+
+// Layers [lo, hi) on the rows held in ws.x, with ws.h = RMSNorm(ws.x) by layer lo's attention
+// gain on entry.  On exit ws.x is the block output and ws.h its RMSNorm by the next gain
+// (layer hi's attention gain, or the final gain after the last layer).
+static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int32_t* active_idx,
+                      const int32_t* m_dev, int mu, int lo, int hi) {
+  const sl_config& c = ctx->cfg;
+  const int dt = c.dtype, d = c.d_model, H = c.n_heads, dh = c.d_head, hd = H * dh, dff = c.d_ff;
+  const void* rope_tab = ctx->kv;
+  for (int l = lo; l < hi; ++l) {
+    const sl_layer_weights& L = ctx->layers[l];
+    const void* next_gain = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->plain.final_norm;
+    if (ctx->use_mfma) {
+      SL_TRY(sl_mfma_layer(ctx, s, l, ws.x, ws.h, ws.q, ws.o, ws.a, ws.f32, active_idx, m_dev, mu, next_gain));
+      continue;
+    }
+    // Q, K, V projections of the active rows (fp32 results side by side)
+    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wq, m_dev, mu, hd, d, ws.f32, nullptr, nullptr, 3 * (size_t)hd));
+    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wk, m_dev, mu, hd, d, ws.f32 + hd, nullptr, nullptr, 3 * (size_t)hd));
+    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wv, m_dev, mu, hd, d, ws.f32 + 2 * hd, nullptr, nullptr, 3 * (size_t)hd));
+    // RoPE; live K/V overwrite the rows' own cache slots (locked slots are never touched)
+    SL_TRY(slk_rope_kv_write(s, dt, ws.f32, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
+                             kv_k_layer(ctx, l), kv_v_layer(ctx, l)));
+    SL_TRY(slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
+                                 ctx->n_seq, ctx->n_pad, ws.o));
+    SL_TRY(slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
+    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
+    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
+    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
+    SL_TRY(slk_swiglu(s, dt, ws.f32, m_dev, mu, dff, ws.a));
+    SL_TRY(slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
+    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
+  }
+  return SL_OK;
+}
+
+static int check_ready(const sl_ctx* ctx, bool need_post) {
+  if (!ctx) return SL_EINVAL;
+  if (!ctx->weights_bound || !ctx->kv) return SL_ESTATE;
+  if (need_post && !ctx->post) return SL_ESTATE;
+  return SL_OK;
+}
+
+extern "C" int sl_forward_layers(sl_ctx* ctx, void* stream, const void* x_in, void* x_out, const int32_t* active_idx,
+                                 const int32_t* m_dev, int32_t m_upper, int32_t layer_lo, int32_t layer_hi,
+                                 void* workspace, size_t workspace_bytes) {
+  SL_TRY(check_ready(ctx, false));
+  if (!x_in || !x_out || !active_idx || !m_dev || !workspace) return SL_EINVAL;
+  if (m_upper < 0 || m_upper > ctx->batch * ctx->n_seq) return SL_EINVAL;
+  if (layer_lo < 0 || layer_hi > ctx->cfg.n_layers || layer_lo >= layer_hi) return SL_EINVAL;
+  if ((uintptr_t)workspace % 256) return SL_EINVAL;
+  if (m_upper == 0) return SL_OK;
+  const Workspace ws = carve(ctx, workspace, m_upper);
+  if (workspace_bytes < ws.bytes) return SL_ENOSPC;
+  hipStream_t s = (hipStream_t)stream;
+  const sl_config& c = ctx->cfg;
+  SL_TRY(slk_copy_rows(s, c.dtype, x_in, ws.x, m_dev, m_upper, c.d_model));
+  SL_TRY(slk_rmsnorm(s, c.dtype, ws.x, m_dev, m_upper, c.d_model, ctx->layers[layer_lo].attn_norm, c.rms_eps, ws.h));
+  SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, layer_lo, layer_hi));
+  return slk_copy_rows(s, c.dtype, ws.x, x_out, m_dev, m_upper, c.d_model);
+}
+
+// ---- controller pieces -----------------------------------------------------------------------------
+extern "C" int sl_compact_active(void* stream, const uint8_t* lock, int32_t batch, int32_t n_seq,
+                                 int32_t* active_idx, int32_t* cu_active) {
+  if (!lock || !active_idx || !cu_active || batch < 1 || n_seq < 1) return SL_EINVAL;
+  if ((size_t)batch * n_seq > (size_t)1 << 30) return SL_EINVAL;
+  return slk_compact_active((hipStream_t)stream, lock, batch, n_seq, active_idx, cu_active);
+}
+
+extern "C" int sl_score_posteriors(void* stream, const void* logits_cur, int32_t cur_packed, const void* logits_prev,
+                                   int32_t dtype, int32_t vocab, const int32_t* active_idx, const int32_t* m_dev,
+                                   int32_t m_upper, int32_t first_step, float* kl, float* conf, int32_t* argmax) {
+  if (!logits_cur || !active_idx || !m_dev || !kl || !conf || !argmax) return SL_EINVAL;
+  if (!first_step && !logits_prev) return SL_EINVAL;
+  if (dtype != SL_F32 && dtype != SL_BF16) return SL_EINVAL;
+  if (vocab < 8 || vocab % 8 || m_upper < 0) return SL_EINVAL;
+  if ((uintptr_t)logits_cur % 16 || (uintptr_t)logits_prev % 16) return SL_EINVAL;
+  return slk_score((hipStream_t)stream, logits_cur, cur_packed, logits_prev, dtype, vocab, active_idx, m_dev, m_upper,
+                   first_step, kl, conf, argmax);
+}
+
+extern "C" int sl_unmask_topk(void* stream, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
+                              const int32_t* cu_active, const float* conf, const int32_t* argmax, int32_t batch,
+                              int32_t n_seq, int32_t block_lo, int32_t block_hi, int32_t k) {
+  if (!tokens || !masked || !active_idx || !cu_active || !conf || !argmax) return SL_EINVAL;
+  if (batch < 1 || n_seq < 1 || block_lo < 0 || block_hi > n_seq || block_lo > block_hi || k < 0) return SL_EINVAL;
+  if ((size_t)(block_hi - block_lo) * 8 > 60 * 1024) return SL_EINVAL;
+  return slk_unmask_topk((hipStream_t)stream, tokens, masked, active_idx, cu_active, conf, argmax, batch, n_seq,
+                         block_lo, block_hi, k);
+}
+
+extern "C" int sl_lock_rule(void* stream, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                            const int32_t* m_dev, int32_t m_upper, const float* kl, const float* eps, int32_t batch,
+                            int32_t n_seq, int32_t first_step, uint8_t* new_lock) {
+  if (!lock || !masked || !active_idx || !m_dev || !kl || !eps || !new_lock) return SL_EINVAL;
+  if (batch < 1 || n_seq < 1 || m_upper < 0) return SL_EINVAL;
+  return slk_lock_rule((hipStream_t)stream, lock, masked, active_idx, m_dev, m_upper, kl, eps, batch, n_seq,
+                       first_step, new_lock);
+}
+
+extern "C" int sl_lock_test(void* stream, const void* logits_cur, int32_t cur_packed, const void* logits_prev,
+                            int32_t dtype, int32_t vocab, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
+                            const int32_t* active_idx, const int32_t* cu_active, int32_t m_upper, const float* eps,
+                            int32_t batch, int32_t n_seq, int32_t first_step, int32_t block_lo, int32_t block_hi,
+                            int32_t k, float* kl, float* conf, int32_t* argmax, uint8_t* new_lock) {
+  if (!cu_active || batch < 1) return SL_EINVAL;
+  if (!tokens || !masked || !lock || !eps || !new_lock) return SL_EINVAL;
+  if (n_seq < 1 || block_lo < 0 || block_hi > n_seq || block_lo > block_hi || k < 0) return SL_EINVAL;
+  const int32_t* m_dev = cu_active + batch;
+  SL_TRY(sl_score_posteriors(stream, logits_cur, cur_packed, logits_prev, dtype, vocab, active_idx, m_dev, m_upper,
+                             first_step, kl, conf, argmax));
+  SL_TRY(sl_unmask_topk(stream, tokens, masked, active_idx, cu_active, conf, argmax, batch, n_seq, block_lo, block_hi,
+                        k));
+  return sl_lock_rule(stream, lock, masked, active_idx, m_dev, m_upper, kl, eps, batch, n_seq, first_step, new_lock);
+}
+
+// ---- the step --------------------------------------------------------------------------------------
+extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
+                                const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,
+                                int32_t m_upper, int32_t* active_idx, int32_t* cu_active, float* kl, float* conf,
+                                int32_t* argmax, uint8_t* new_lock, void* workspace, size_t workspace_bytes) {
+  SL_TRY(check_ready(ctx, true));
+  if (!tokens || !masked || !lock || !eps || !active_idx || !cu_active || !kl || !conf || !argmax || !new_lock ||
+      !workspace)
+    return SL_EINVAL;
+  const int B = ctx->batch, N = ctx->n_seq;
+  if (t < 1 || m_upper < 1 || m_upper > B * N) return SL_EINVAL;
+  if (block_lo < 0 || block_hi > N || block_lo > block_hi || k < 0) return SL_EINVAL;
+  if ((size_t)(block_hi - block_lo) * 8 > 60 * 1024) return SL_EINVAL;
+  if ((uintptr_t)workspace % 256) return SL_EINVAL;
+  const Workspace ws = carve(ctx, workspace, m_upper);
+  if (workspace_bytes < ws.bytes) return SL_ENOSPC;
+  hipStream_t s = (hipStream_t)stream;
+  const sl_config& c = ctx->cfg;
+  const int32_t* m_dev = cu_active + B;
+  // A_t
+  SL_TRY(slk_compact_active(s, lock, B, N, active_idx, cu_active));
+  // block input of the active rows + first LN
+  SL_TRY(slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model,
+                           ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h));
+  SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, 0, c.n_layers));
+  // logits of the active rows, written to their rows of this step's posterior buffer
+  void *cur = nullptr, *prev = nullptr;
+  sl_logits_ptr(ctx, t, &cur);
+  sl_logits_ptr(ctx, t - 1, &prev);
+  if (ctx->use_mfma)
+    SL_TRY(sl_mfma_lm_head(ctx, s, ws.h, active_idx, m_dev, m_upper, cur));
+  else
+    SL_TRY(slk_gemm_generic(s, c.dtype, ws.h, ctx->plain.lm_head, m_dev, m_upper, c.vocab, c.d_model, nullptr, cur,
+                            active_idx, c.vocab));
+  // score -> UpdateMASK -> candidates -> lock
+  SL_TRY(slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax));
+  SL_TRY(slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
+  return slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock);
+}

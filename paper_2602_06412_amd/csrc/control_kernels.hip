@@ -1,0 +1,135 @@
+// Index-set and mask kernels of the SureLock controller (Alg. 1: the active-set
+// line, UpdateMASK, the candidate line and the lock rule).  All integer work; these
+// launches move a few KB and are latency-bound, so each is a single small kernel.
+#include "sl_common.h"
+
+// ---- A_t = {i | lock_i = 0}: stable stream compaction over the flat [B*N] mask -------
+// One 1024-thread block walks the mask in chunks of 1024: wave ballot + popcount gives
+// the rank inside a wave, an LDS scan over the 16 wave totals gives the rank inside the
+// chunk, a running base carries across chunks.  cu_active[b] is the rank of flat id b*N.
+__global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __restrict__ lock, int B, int N,
+                                                              int32_t* __restrict__ active_idx,
+                                                              int32_t* __restrict__ cu_active) {
+  __shared__ int wave_tot[16];
+  __shared__ int base_sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int total = B * N;
+  if (tid == 0) base_sh = 0;
+  __syncthreads();
+  for (int start = 0; start < total; start += 1024) {
+    const int g = start + tid;
+    const bool act = (g < total) && (lock[g] == 0);
+    const unsigned long long bal = __ballot(act);
+    const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int before = 0, chunk_tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+      const int c = wave_tot[w];
+      before += (w < wave) ? c : 0;
+      chunk_tot += c;
+    }
+    const int base = base_sh;
+    const int rank = base + before + in_wave;
+    if (g < total) {
+      if (act) active_idx[rank] = g;
+      if (g % N == 0) cu_active[g / N] = rank;
+    }
+    __syncthreads();
+    if (tid == 0) base_sh = base + chunk_tot;
+    __syncthreads();
+  }
+  if (tid == 0) cu_active[B] = base_sh;
+}
+
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, s, lock, B, N, active_idx, cu_active);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// ---- UpdateMASK: top-k by confidence inside the current block, one workgroup per sequence --
+// Eligible rows are appended to an LDS list; each entry's rank is the number of entries
+// that beat it (higher conf, or equal conf and lower position); rank < k is selected.
+// Comparisons are on the fp32 conf values; rows are in position order, so comparing row
+// ids compares positions.
+__global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ tokens, uint8_t* __restrict__ masked,
+                                                          const int32_t* __restrict__ active_idx,
+                                                          const int32_t* __restrict__ cu_active,
+                                                          const float* __restrict__ conf,
+                                                          const int32_t* __restrict__ argmax, int N, int lo, int hi,
+                                                          int k) {
+  extern __shared__ unsigned char smem_raw[];
+  float* e_conf = reinterpret_cast<float*>(smem_raw);
+  int* e_row = reinterpret_cast<int*>(smem_raw) + (hi - lo);
+  __shared__ int count;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int r0 = cu_active[b], r1 = cu_active[b + 1];
+  if (tid == 0) count = 0;
+  __syncthreads();
+  for (int r = r0 + tid; r < r1; r += 256) {
+    const int g = active_idx[r];
+    const int i = g - b * N;
+    if (i >= lo && i < hi && masked[g]) {
+      const int slot = atomicAdd(&count, 1);
+      e_conf[slot] = conf[r];
+      e_row[slot] = r;
+    }
+  }
+  __syncthreads();
+  const int n = count;
+  for (int e = tid; e < n; e += 256) {
+    const float c = e_conf[e];
+    const int r = e_row[e];
+    int rank = 0;
+    for (int f = 0; f < n; ++f) {
+      const float cf = e_conf[f];
+      rank += (cf > c || (cf == c && e_row[f] < r)) ? 1 : 0;
+    }
+    if (rank < k) {
+      const int g = active_idx[r];
+      tokens[g] = argmax[r];
+      masked[g] = 0;
+    }
+  }
+}
+
+int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
+                    const int32_t* cu_active, const float* conf, const int32_t* argmax, int B, int N, int lo, int hi,
+                    int k) {
+  if (hi <= lo || k <= 0) return SL_OK;
+  const size_t sh = (size_t)(hi - lo) * 8;
+  hipLaunchKernelGGL(unmask_topk_kernel, dim3(B), dim3(256), sh, s, tokens, masked, active_idx, cu_active, conf,
+                     argmax, N, lo, hi, k);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// ---- candidates and lock rule: Z_t = active & unmasked, F_t = {i in Z_t : D_i <= eps_b} ------
+// Thread p < B*N carries an already-locked position over; thread r < M decides row r.
+// The two roles write disjoint positions, so new_lock may alias lock.
+__global__ void lock_rule_kernel(const uint8_t* lock, const uint8_t* __restrict__ masked,
+                                 const int32_t* __restrict__ active_idx, const int32_t* __restrict__ m_dev,
+                                 int m_upper, const float* __restrict__ kl, const float* __restrict__ eps, int total,
+                                 int N, int first_step, uint8_t* new_lock) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int M = min(*m_dev, m_upper);
+  if (t < total && lock[t]) new_lock[t] = 1;
+  if (t < M) {
+    const int g = active_idx[t];
+    const bool F = !first_step && masked[g] == 0 && kl[t] <= eps[g / N];
+    new_lock[g] = F ? 1 : 0;
+  }
+}
+
+int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                  const int32_t* m_dev, int m_upper, const float* kl, const float* eps, int B, int N, int first_step,
+                  uint8_t* new_lock) {
+  const int total = B * N;
+  const int n = total > m_upper ? total : m_upper;
+  hipLaunchKernelGGL(lock_rule_kernel, dim3(sl_cdiv(n, 256)), dim3(256), 0, s, lock, masked, active_idx, m_dev,
+                     m_upper, kl, eps, total, N, first_step, new_lock);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}

@@ -1,0 +1,144 @@
+// Posterior scoring (Alg. 1 'Score on active positions'; Sec. 2.2): one streaming pass
+// over the current and the previous logits row of every active position gives
+//   D    = KL(p_t || p_{t-1})           (nats)
+//   conf = max_v p_t(v)                  (u = 1 - conf)
+//   argmax_v p_t(v)                      (lowest id on ties)
+// HBM-bound: each row pair is read exactly once with 16-byte loads, nothing is written
+// but three scalars per row.
+//
+// Arithmetic.  With a = z_t(v), b = z_{t-1}(v) and any common shift m,
+//   S  = sum e^{a-m},   dS = sum (e^{b-m} - e^{a-m}),   W = sum e^{a-m} (a - b)
+//   KL = sum p_t (log p_t - log p_{t-1}) = W/S + log(1 + dS/S).
+// a - b is exact in fp32 for bf16 inputs, and both dS and W are sums of terms that vanish
+// with a - b, so the result keeps its relative accuracy when successive posteriors are
+// close (the regime the lock test works in) instead of cancelling two O(1) logsumexps.
+// The shift m is a running maximum over both rows, raised chunk by chunk (online
+// rescaling), so one pass suffices for any vocabulary size.
+#include "sl_common.h"
+
+struct ScoreAcc {
+  float m, S, dS, W, bestv;
+  int besti;
+};
+
+__device__ inline void acc_merge(ScoreAcc& x, const ScoreAcc& y) {
+  const float m = fmaxf(x.m, y.m);
+  const float fx = (x.m == m) ? 1.f : __expf(x.m - m);
+  const float fy = (y.m == m) ? 1.f : __expf(y.m - m);
+  x.S = x.S * fx + y.S * fy;
+  x.dS = x.dS * fx + y.dS * fy;
+  x.W = x.W * fx + y.W * fy;
+  x.m = m;
+  if (y.bestv > x.bestv || (y.bestv == x.bestv && y.besti < x.besti)) {
+    x.bestv = y.bestv;
+    x.besti = y.besti;
+  }
+}
+
+template <typename T> struct chunk_io;
+template <> struct chunk_io<bf16_t> {
+  __device__ static inline void load(const bf16_t* p, float (&v)[8]) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+  }
+};
+template <> struct chunk_io<float> {
+  __device__ static inline void load(const float* p, float (&v)[4]) {
+    const float4 u = *reinterpret_cast<const float4*>(p);
+    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+  }
+};
+
+constexpr int kScoreThreads = 256;
+
+template <typename T, bool FIRST>
+__global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restrict__ cur, int cur_packed,
+                                                               const T* __restrict__ prev, int V,
+                                                               const int32_t* __restrict__ active_idx,
+                                                               const int32_t* __restrict__ m_dev, int m_upper,
+                                                               float* __restrict__ kl, float* __restrict__ conf,
+                                                               int32_t* __restrict__ argmax) {
+  constexpr int E = st<T>::kVec;
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.x;
+  if (r >= M) return;
+  const int g = active_idx[r];
+  const T* a_row = cur + (size_t)(cur_packed ? r : g) * V;
+  const T* b_row = prev + (size_t)g * V;
+  ScoreAcc acc{-INFINITY, 0.f, 0.f, 0.f, -INFINITY, 0x7fffffff};
+  const int n_chunks = V / E;
+  for (int c = threadIdx.x; c < n_chunks; c += kScoreThreads) {
+    float a[E], b[E];
+    chunk_io<T>::load(a_row + (size_t)c * E, a);
+    if (!FIRST) chunk_io<T>::load(b_row + (size_t)c * E, b);
+    float cm = a[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) cm = fmaxf(cm, a[j]);
+    if (!FIRST) {
+#pragma unroll
+      for (int j = 0; j < E; ++j) cm = fmaxf(cm, b[j]);
+    }
+    if (cm > acc.m) {
+      const float f = __expf(acc.m - cm);      // 0 on the first chunk (acc.m = -inf)
+      acc.S *= f; acc.dS *= f; acc.W *= f;
+      acc.m = cm;
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const float ea = __expf(a[j] - acc.m);
+      acc.S += ea;
+      if (!FIRST) {
+        const float eb = __expf(b[j] - acc.m);
+        acc.dS += eb - ea;
+        acc.W = fmaf(ea, a[j] - b[j], acc.W);
+      }
+      if (a[j] > acc.bestv) { acc.bestv = a[j]; acc.besti = c * E + j; }
+    }
+  }
+  // wave reduction, then across the block's waves through LDS
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    ScoreAcc y;
+    y.m = __shfl_xor(acc.m, o, 64); y.S = __shfl_xor(acc.S, o, 64); y.dS = __shfl_xor(acc.dS, o, 64);
+    y.W = __shfl_xor(acc.W, o, 64); y.bestv = __shfl_xor(acc.bestv, o, 64); y.besti = __shfl_xor(acc.besti, o, 64);
+    acc_merge(acc, y);
+  }
+  __shared__ ScoreAcc sh[kScoreThreads / 64];
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ScoreAcc t = sh[0];
+#pragma unroll
+    for (int w = 1; w < kScoreThreads / 64; ++w) acc_merge(t, sh[w]);
+    conf[r] = __expf(t.bestv - t.m) / t.S;
+    argmax[r] = t.besti;
+    kl[r] = FIRST ? INFINITY : fmaxf(0.f, t.W / t.S + log1pf(t.dS / t.S));
+  }
+}
+
+template <typename T>
+static int launch_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int V,
+                        const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl,
+                        float* conf, int32_t* argmax) {
+  if (m_upper <= 0) return SL_OK;
+  dim3 grid(m_upper), block(kScoreThreads);
+  if (first_step)
+    hipLaunchKernelGGL((score_kernel<T, true>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)cur, V,
+                       active_idx, m_dev, m_upper, kl, conf, argmax);
+  else
+    hipLaunchKernelGGL((score_kernel<T, false>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)prev, V,
+                       active_idx, m_dev, m_upper, kl, conf, argmax);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int dtype, int V,
+              const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl, float* conf,
+              int32_t* argmax) {
+  if (dtype == SL_BF16)
+    return launch_score<bf16_t>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
+  return launch_score<float>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
+}

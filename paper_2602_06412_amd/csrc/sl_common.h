@@ -1,0 +1,143 @@
+// Shared host/device declarations of libsurelock (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/surelock.h"
+
+typedef __bf16 bf16_t;
+
+// ---- storage-type traits: load to fp32, round-to-nearest-even store -------------
+template <typename T> struct st;
+template <> struct st<float> {
+  static constexpr int kDtype = SL_F32;
+  static constexpr int kVec = 4;                       // elements per 16-byte access
+  __device__ static inline float ld(const float* p) { return *p; }
+  __device__ static inline void stv(float* p, float v) { *p = v; }
+  __device__ static inline float rnd(float v) { return v; }
+};
+template <> struct st<bf16_t> {
+  static constexpr int kDtype = SL_BF16;
+  static constexpr int kVec = 8;
+  __device__ static inline float ld(const bf16_t* p) { return (float)*p; }
+  __device__ static inline void stv(bf16_t* p, float v) { *p = (bf16_t)v; }
+  __device__ static inline float rnd(float v) { return (float)(bf16_t)v; }
+};
+
+__device__ inline float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
+
+// ---- wave / block reductions (wave = 64 lanes) ------------------------------------
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sum over a block of NT threads; every thread gets the result.  `sh` has NT/64 floats.
+template <int NT>
+__device__ inline float block_sum(float v, float* sh) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+  __syncthreads();
+  if (l == 0) sh[w] = v;
+  __syncthreads();
+  float r = 0.f;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) r += sh[i];
+  return r;
+}
+template <int NT>
+__device__ inline float block_max(float v, float* sh) {
+  v = wave_max(v);
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+  __syncthreads();
+  if (l == 0) sh[w] = v;
+  __syncthreads();
+  float r = sh[0];
+#pragma unroll
+  for (int i = 1; i < NT / 64; ++i) r = fmaxf(r, sh[i]);
+  return r;
+}
+
+// ---- host side -------------------------------------------------------------------------
+extern thread_local int g_sl_last_hip_error;
+#define SL_HIP(call)                                   \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) {                            \
+      g_sl_last_hip_error = (int)e_;                   \
+      return SL_EHIP;                                  \
+    }                                                  \
+  } while (0)
+#define SL_LAUNCH_CHECK() SL_HIP(hipGetLastError())
+#define SL_REQUIRE(cond) do { if (!(cond)) return SL_EINVAL; } while (0)
+
+static inline size_t sl_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int sl_cdiv(int a, int b) { return (a + b - 1) / b; }
+static inline size_t sl_tsize(int dtype) { return dtype == SL_BF16 ? 2 : 4; }
+
+struct sl_packed_layer {            // device pointers into the caller's packed buffer (MFMA path)
+  const void *wqkv, *wo, *wgu, *wdown;
+};
+
+struct sl_ctx {
+  sl_config cfg;
+  bool weights_bound, use_mfma;
+  sl_weights plain;                 // copy of the caller's struct (layers -> own host array)
+  sl_layer_weights* layers;         // host array, n_layers
+  sl_packed_layer* packed;          // host array, n_layers (use_mfma only)
+  const void* packed_lm_head;
+  // K/V cache
+  void* kv; int32_t batch, n_seq, n_pad; size_t kv_layer_elems;   // elements of T per layer per K (= per V)
+  // posterior store
+  void* post; size_t post_buf_elems;
+};
+
+// ---- kernel launchers (one translation unit each) ------------------------------------------
+// control_kernels.hip
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active);
+int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
+                    const int32_t* cu_active, const float* conf, const int32_t* argmax,
+                    int B, int N, int lo, int hi, int k);
+int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                  const int32_t* m_dev, int m_upper, const float* kl, const float* eps, int B, int N,
+                  int first_step, uint8_t* new_lock);
+// score_kernel.hip
+int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int dtype, int V,
+              const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step,
+              float* kl, float* conf, int32_t* argmax);
+// rowwise_kernels.hip
+int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
+                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h);
+int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, const int32_t* m_dev, int m_upper,
+                    int d, const void* gain, float eps, void* h);
+int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d,
+                const void* gain, float eps, void* h);
+int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta);
+int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, const int32_t* active_idx, const int32_t* m_dev,
+                      int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
+int slk_swiglu(hipStream_t s, int dtype, const float* gu, const int32_t* m_dev, int m_upper, int dff, void* a);
+int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
+                void* k_out, void* v_out);
+int slk_fill_zero(hipStream_t s, void* p, size_t bytes);
+int slk_copy_rows(hipStream_t s, int dtype, const void* src, void* dst, const int32_t* m_dev, int m_upper, int d);
+// gemm_generic.hip:  C[m, n] (fp32, ldc) = A[m, k] (T) . W[n, k]^T (T); optional row map for the output
+int slk_gemm_generic(hipStream_t s, int dtype, const void* A, const void* W, const int32_t* m_dev, int m_upper,
+                     int n, int k, float* C_f32, void* C_T, const int32_t* out_row_map, size_t ldc);
+// attention_generic.hip
+int slk_attention_generic(hipStream_t s, int dtype, const void* q, const void* kc, const void* vc,
+                          const int32_t* active_idx, const int32_t* m_dev, int m_upper,
+                          int H, int dh, int N, int n_pad, void* o);
+
+// mfma path (gemm_mfma.hip / attention_mfma.hip / mfma_layer.hip)
+bool sl_mfma_supported(const sl_config* cfg);
+size_t sl_mfma_packed_bytes(const sl_config* cfg);
+int sl_mfma_pack_all(sl_ctx* ctx, hipStream_t s, void* packed);
+int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int layer, void* x, void* h, void* q, void* o, void* a, float* f32,
+                  const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain);
+int sl_mfma_lm_head(sl_ctx* ctx, hipStream_t s, const void* h, const int32_t* active_idx, const int32_t* m_dev, int mu,
+                    void* logits_buf);

@@ -1,0 +1,88 @@
+"""Oracle trajectories for the teacher-forced GPU parity tests (not collected by pytest).
+
+run_oracle() drives oracle.sampler for B independent sequences and records, per step, the
+state BEFORE the step (tokens, masked, lock) and everything the step produced, batched the
+way the C ABI sees it (flat row ids b*N + i, sequences concatenated)."""
+from dataclasses import dataclass
+
+import numpy as np
+
+from oracle import sampler
+from paper_2602_06412_amd import workloads as wl
+
+
+@dataclass
+class BatchStep:
+    t: int
+    tokens_in: np.ndarray      # [B, N]
+    masked_in: np.ndarray      # [B, N]
+    lock_in: np.ndarray        # [B, N]
+    block: tuple               # (lo, hi, k)
+    active_idx: np.ndarray     # [M] flat ids
+    cu_active: np.ndarray      # [B+1]
+    logits: np.ndarray         # [M, V]
+    kl: np.ndarray
+    conf: np.ndarray
+    argmax: np.ndarray
+    tokens_out: np.ndarray
+    masked_out: np.ndarray
+    lock_rule_out: np.ndarray  # lock_in | F_t  (what the KL rule alone gives)
+    lock_out: np.ndarray       # lock mask carried to the next step (rule and/or forced)
+
+
+def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, seed=0, keep_states=False):
+    """prompts: list of B int arrays (same length); eps: list of B thresholds.
+    forced_M_end: None -> the KL rule drives the mask; else a list of per-sequence final
+    active counts: a seeded priority force-locks eligible rows so M falls linearly, and the
+    rule's F_t is recorded only."""
+    Bn = len(prompts)
+    n_p = len(prompts[0])
+    N = n_p + n_gen
+    sched = sampler.block_schedule(n_p, n_gen, block_len, T)
+    states = [sampler.init_state(cfg, w64, p, n_gen) for p in prompts]
+    hooks = [None] * Bn
+    if forced_M_end is not None:
+        for b in range(Bn):
+            pri = np.random.default_rng(seed * 1000 + b).permutation(N)
+            target = wl.linear_m_schedule(N, forced_M_end[b], T)
+
+            def hook(st, rec, pri=pri, target=target):
+                nxt = target[st.t] if st.t < len(target) else target[-1]
+                return wl.forced_lock_positions(pri, st.lock, st.masked, int((st.lock == 0).sum()) - nxt)
+            hooks[b] = hook
+    steps = []
+    for t in range(T):
+        lo, hi, k = sched[t]
+        pre = [(s.tokens.copy(), s.masked.copy(), s.lock.copy()) for s in states]
+        recs = [sampler.surelock_step(cfg, w64, states[b], eps[b], lo, hi, k, forced_lock=hooks[b],
+                                      kl_drives_lock=forced_M_end is None) for b in range(Bn)]
+        idx = np.concatenate([r.active_pos + b * N for b, r in enumerate(recs)])
+        cu = np.concatenate([[0], np.cumsum([len(r.active_pos) for r in recs])])
+        rule = np.stack([p[2].copy() for p in pre])
+        for b, r in enumerate(recs):
+            rule[b, r.F] = 1
+        steps.append(BatchStep(
+            t=t + 1, tokens_in=np.stack([p[0] for p in pre]), masked_in=np.stack([p[1] for p in pre]),
+            lock_in=np.stack([p[2] for p in pre]), block=(lo, hi, k), active_idx=idx, cu_active=cu,
+            logits=np.concatenate([r.logits for r in recs]), kl=np.concatenate([r.kl for r in recs]),
+            conf=np.concatenate([r.conf for r in recs]), argmax=np.concatenate([r.argmax for r in recs]),
+            tokens_out=np.stack([s.tokens.copy() for s in states]),
+            masked_out=np.stack([s.masked.copy() for s in states]),
+            lock_rule_out=rule, lock_out=np.stack([s.lock.copy() for s in states])))
+    return (steps, states) if keep_states else steps
+
+
+def near_tie_in_topk(step, N, rel=1e-5):
+    """True if, in some sequence, the k-th and (k+1)-th most confident eligible rows are
+    closer than `rel` relative: then either choice is valid and the step is skipped by the
+    exact-token comparison."""
+    lo, hi, k = step.block
+    Bn = step.tokens_in.shape[0]
+    for b in range(Bn):
+        r0, r1 = step.cu_active[b], step.cu_active[b + 1]
+        pos = step.active_idx[r0:r1] - b * N
+        c = sorted((float(step.conf[r0 + j]) for j in range(r1 - r0)
+                    if step.masked_in[b, pos[j]] and lo <= pos[j] < hi), reverse=True)
+        if k < len(c) and k > 0 and abs(c[k - 1] - c[k]) <= rel * c[k - 1]:
+            return True
+    return False
