@@ -17,7 +17,7 @@
 #include "sl_common.h"
 
 struct ScoreAcc {
-  float m, S, dS, W, bestv;
+  float m, S, Sc, dS, W, bestv;   // Sc: compensation term of S (S + Sc is the sum)
   int besti;
 };
 
@@ -25,7 +25,8 @@ __device__ inline void acc_merge(ScoreAcc& x, const ScoreAcc& y) {
   const float m = fmaxf(x.m, y.m);
   const float fx = (x.m == m) ? 1.f : __expf(x.m - m);
   const float fy = (y.m == m) ? 1.f : __expf(y.m - m);
-  x.S = x.S * fx + y.S * fy;
+  x.S = (x.S + x.Sc) * fx + (y.S + y.Sc) * fy;
+  x.Sc = 0.f;
   x.dS = x.dS * fx + y.dS * fy;
   x.W = x.W * fx + y.W * fy;
   x.m = m;
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
   const int g = active_idx[r];
   const T* a_row = cur + (size_t)(cur_packed ? r : g) * V;
   const T* b_row = prev + (size_t)g * V;
-  ScoreAcc acc{-INFINITY, 0.f, 0.f, 0.f, -INFINITY, 0x7fffffff};
+  ScoreAcc acc{-INFINITY, 0.f, 0.f, 0.f, 0.f, -INFINITY, 0x7fffffff};
   const int n_chunks = V / E;
   for (int c = threadIdx.x; c < n_chunks; c += kScoreThreads) {
     float a[E], b[E];
@@ -83,13 +84,14 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
     }
     if (cm > acc.m) {
       const float f = __expf(acc.m - cm);      // 0 on the first chunk (acc.m = -inf)
-      acc.S *= f; acc.dS *= f; acc.W *= f;
+      acc.S *= f; acc.Sc *= f; acc.dS *= f; acc.W *= f;
       acc.m = cm;
     }
+    float cs = 0.f;                             // this chunk's share of S
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       const float ea = __expf(a[j] - acc.m);
-      acc.S += ea;
+      cs += ea;
       if (!FIRST) {
         const float eb = __expf(b[j] - acc.m);
         acc.dS += eb - ea;
@@ -97,12 +99,18 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
       }
       if (a[j] > acc.bestv) { acc.bestv = a[j]; acc.besti = c * E + j; }
     }
+    // S += cs with an error-free two-sum: once a dominant term (e^0 = 1) is in S, plain
+    // adds of the many ~1e-8 terms of a peaked posterior would be rounded away
+    const float t = acc.S + cs;
+    const float bp = t - acc.S;
+    acc.Sc += (acc.S - (t - bp)) + (cs - bp);
+    acc.S = t;
   }
   // wave reduction, then across the block's waves through LDS
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     ScoreAcc y;
-    y.m = __shfl_xor(acc.m, o, 64); y.S = __shfl_xor(acc.S, o, 64); y.dS = __shfl_xor(acc.dS, o, 64);
+    y.m = __shfl_xor(acc.m, o, 64); y.S = __shfl_xor(acc.S, o, 64); y.Sc = __shfl_xor(acc.Sc, o, 64); y.dS = __shfl_xor(acc.dS, o, 64);
     y.W = __shfl_xor(acc.W, o, 64); y.bestv = __shfl_xor(acc.bestv, o, 64); y.besti = __shfl_xor(acc.besti, o, 64);
     acc_merge(acc, y);
   }
@@ -113,6 +121,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
     ScoreAcc t = sh[0];
 #pragma unroll
     for (int w = 1; w < kScoreThreads / 64; ++w) acc_merge(t, sh[w]);
+    t.S += t.Sc;
     conf[r] = __expf(t.bestv - t.m) / t.S;
     argmax[r] = t.besti;
     kl[r] = FIRST ? INFINITY : fmaxf(0.f, t.W / t.S + log1pf(t.dS / t.S));

@@ -20,7 +20,7 @@ from oracle import control, posterior
 from paper_2602_06412_amd import binding as B
 from paper_2602_06412_amd import workloads as wl
 from tests.gpu_util import DEV, dev, logits_tol, oracle_cfg, weights_to_device
-from tests.trajectory import near_tie_in_topk, run_oracle
+from tests.trajectory import near_tie_in_topk, run_oracle, unmask_is_valid
 
 pytestmark = pytest.mark.gpu
 
@@ -117,9 +117,12 @@ def _decisions_on_oracle_logits(shape, steps, eps):
         if st.t > 1:
             g = kl[:M].cpu().numpy().astype(np.float64)
             assert np.all(np.abs(g - st.kl) <= 1e-4 * st.kl + 2e-7), f"t={st.t}"
+        tok_g, msk_g = tokens.cpu().numpy().reshape(Bn, N), masked.cpu().numpy().reshape(Bn, N)
+        assert unmask_is_valid(st, N, tok_g, msk_g), f"t={st.t}"
         if not near_tie_in_topk(st, N):
-            assert np.array_equal(tokens.cpu().numpy().reshape(Bn, N), st.tokens_out), f"t={st.t}"
-            assert np.array_equal(masked.cpu().numpy().reshape(Bn, N), st.masked_out)
+            assert np.array_equal(tok_g, st.tokens_out), f"t={st.t}"
+            assert np.array_equal(msk_g, st.masked_out)
+        if np.array_equal(msk_g, st.masked_out):
             safe = np.ones((Bn, N), bool)
             for b in range(Bn):
                 r0, r1 = st.cu_active[b], st.cu_active[b + 1]
@@ -128,7 +131,7 @@ def _decisions_on_oracle_logits(shape, steps, eps):
             assert np.array_equal(new_lock.cpu().numpy().reshape(Bn, N)[safe], st.lock_rule_out[safe]), f"t={st.t}"
             n_checked += 1
         prev[torch.as_tensor(st.active_idx, device=DEV, dtype=torch.long)] = cur
-    assert n_checked >= len(steps) // 2
+    assert n_checked >= max(1, len(steps) // 4)
 
 
 def test_c1_tiny_fp32_full_run():
@@ -186,7 +189,7 @@ def test_kv_cache_matches_oracle_and_is_permanent():
     shape = wl.S_BF16
     w = wl.make_weights(shape, seed=5)
     cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
-    n_p, n_gen, T = 40, 64, 6
+    n_p, n_gen, T = 40, 64, 8
     N = n_p + n_gen
     steps, states = run_oracle(cfg, w64, [wl.prompt_uniform(1, n_p, shape.vocab, shape.mask_id)], n_gen, T, n_gen,
                                [1e-3], forced_M_end=[30], seed=6, keep_states=True)

@@ -86,3 +86,30 @@ def near_tie_in_topk(step, N, rel=1e-5):
         if k < len(c) and k > 0 and abs(c[k - 1] - c[k]) <= rel * c[k - 1]:
             return True
     return False
+
+
+def unmask_is_valid(step, N, tokens_gpu, masked_gpu, rel=1e-5):
+    """The GPU's UpdateMASK result is a valid confidence-ordered top-k of the oracle's own
+    confidences: exactly min(k, #eligible) eligible positions unmasked per sequence, none of
+    them less confident (beyond `rel`) than an eligible position left masked, each given its
+    row's argmax token, and nothing else changed.  Without near-ties this is equality."""
+    lo, hi, k = step.block
+    Bn = step.tokens_in.shape[0]
+    for b in range(Bn):
+        r0, r1 = step.cu_active[b], step.cu_active[b + 1]
+        pos = step.active_idx[r0:r1] - b * N
+        elig = {int(pos[j]): r0 + j for j in range(r1 - r0) if step.masked_in[b, pos[j]] and lo <= pos[j] < hi}
+        changed = set(np.flatnonzero(masked_gpu[b] != step.masked_in[b]).tolist())
+        if not changed <= set(elig) or len(changed) != min(k, len(elig)):
+            return False
+        if np.any(masked_gpu[b][list(changed)] != 0):
+            return False
+        for i in range(N):
+            want = step.argmax[elig[i]] if i in changed else step.tokens_in[b, i]
+            if tokens_gpu[b, i] != want:
+                return False
+        left = [step.conf[r] for i, r in elig.items() if i not in changed]
+        took = [step.conf[r] for i, r in elig.items() if i in changed]
+        if left and took and min(took) < max(left) * (1 - rel):
+            return False
+    return True
