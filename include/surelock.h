@@ -104,9 +104,13 @@ int sl_bind_weights(sl_ctx *ctx, void *stream, const sl_weights *plain /* host s
  * row overwrites its own cache row at every step (the 'assemble' line); a locked row
  * is simply never written again, which is the cache commit of the lock line.
  * Layout (T elements), n_pad = N rounded up to 64:
- *   K: [L][B][H][n_pad][d_h]            post-RoPE keys, one 2*d_h-byte row per slot
- *   V: [L][B][H][n_pad/8][d_h][8]       values, 8 consecutive slots interleaved so the
- *                                       P.V MFMA operand is a contiguous 16-byte read
+ *   K: [L][B][H][n_pad/32][d_h/8][32][8]  post-RoPE keys; 32 slots x 8 dims interleaved so a
+ *                                         32-key MFMA operand fragment of QK^T is contiguous
+ *   V: [L][B][H][n_pad/16][2][d_h][8]     values; the 8 slots {8a+4h+i} of a 16-slot block are
+ *                                         stored together at [h][dim][4a+i], the key order in
+ *                                         which one lane holds the K Q^T accumulator, so P.V
+ *                                         needs no transpose
+ * (sl_kv_cache_read returns the plain layout.)
  * sl_kv_cache_bind zero-fills the buffer (enqueued on `stream`). */
 int sl_kv_cache_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
 int sl_kv_cache_bind(sl_ctx *ctx, void *stream, void *kv, size_t bytes, int32_t batch, int32_t n_seq);

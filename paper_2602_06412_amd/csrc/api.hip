@@ -181,7 +181,12 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows) {
   w.q = take((size_t)rows * hd * ts);
   w.o = take((size_t)rows * hd * ts);
   w.a = take((size_t)rows * c.d_ff * ts);
-  w.f32 = (float*)take((size_t)rows * f32_cols * sizeof(float));
+  size_t f32_elems = (size_t)rows * f32_cols;
+  if (ctx->use_mfma) {
+    const size_t e = sl_mfma_f32_elems(&c, rows);
+    if (e > f32_elems) f32_elems = e;
+  }
+  w.f32 = (float*)take(f32_elems * sizeof(float));
   w.bytes = off;
   return w;
 }
@@ -215,17 +220,17 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wk, m_dev, mu, hd, d, ws.f32 + hd, nullptr, nullptr, 3 * (size_t)hd));
     SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wv, m_dev, mu, hd, d, ws.f32 + 2 * hd, nullptr, nullptr, 3 * (size_t)hd));
     // RoPE; live K/V overwrite the rows' own cache slots (locked slots are never touched)
-    SL_TRY(slk_rope_kv_write(s, dt, ws.f32, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
+    SL_TRY(slk_rope_kv_write(s, dt, ws.f32, 1, 0, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
                              kv_k_layer(ctx, l), kv_v_layer(ctx, l)));
     SL_TRY(slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
                                  ctx->n_seq, ctx->n_pad, ws.o));
     SL_TRY(slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
-    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
+    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
     SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
-    SL_TRY(slk_swiglu(s, dt, ws.f32, m_dev, mu, dff, ws.a));
+    SL_TRY(slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a));
     SL_TRY(slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
-    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
+    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
   }
   return SL_OK;
 }

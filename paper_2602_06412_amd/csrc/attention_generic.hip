@@ -27,9 +27,8 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(const T* __restr
   __syncthreads();
   float lmax = -INFINITY;
   for (int n = tid; n < N; n += 256) {
-    const T* krow = kc + head_base + (size_t)n * dh;
     float s = 0.f;
-    for (int c = 0; c < dh; ++c) s = fmaf(qs[c], st<T>::ld(krow + c), s);
+    for (int c = 0; c < dh; ++c) s = fmaf(qs[c], st<T>::ld(kc + head_base + kc_index(n, c, dh)), s);
     s *= scale;
     sc[n] = s;
     lmax = fmaxf(lmax, s);
@@ -46,12 +45,7 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(const T* __restr
   const int grp = tid / dh, c = tid - grp * dh;
   float acc = 0.f;
   if (grp < G) {
-    for (int nb = grp; nb * 8 < N; nb += G) {
-      const T* vb = vc + head_base + ((size_t)nb * dh + c) * 8;
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (nb * 8 + j < N) acc = fmaf(sc[nb * 8 + j], st<T>::ld(vb + j), acc);
-    }
+    for (int n = grp; n < N; n += G) acc = fmaf(sc[n], st<T>::ld(vc + head_base + vc_index(n, c, dh)), acc);
   }
   part[tid] = acc;
   __syncthreads();

@@ -1,0 +1,189 @@
+// Bidirectional M x N attention of the active rows on the MFMA units (bf16, d_h = 128):
+//   o[r, h] = softmax(q[r, h] . K[b, h, 0..N)^T / sqrt(d_h)) V[b, h, 0..N)
+// for the packed active rows r of each sequence b against ALL N cached slots of that
+// sequence, no mask (Alg. 1 'attention' line; Sec. 2.1: locked slots are served from the
+// cache, live slots were just overwritten by this step's K/V write).
+//
+// Flash-style, computed transposed so that softmax statistics live in one lane:
+//   S^T[key, q] = K Q^T   (MFMA A = K fragment from LDS, B = Q^T fragment kept in registers)
+//   lane l of the accumulator owns query q = l%32 and 16 keys per 32-key block, so the row
+//   max / sum of the online softmax need one cross-lane exchange (lanes l, l^32) only;
+//   O^T[dim, q] += V^T P^T  (A = V^T fragment from LDS, B = P^T = the accumulator registers
+//   of the first product rounded to bf16, used in place: no LDS round trip, no transpose).
+// The K/V cache layouts (kc_index / vc_index) make every fragment of a 64-slot tile a
+// contiguous block, so a tile is a straight 16 KiB + 16 KiB copy into LDS.
+//
+// One workgroup = 4 waves x 32 queries of ONE sequence and one head; packed rows of
+// different sequences never share a tile (the varlen case of a ragged batch).
+#include "sl_common.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+typedef bf16x8 FragA;       // one lane's 16-byte share of an MFMA operand fragment
+
+constexpr int QT = 128;          // queries per workgroup
+constexpr int KT = 64;           // slots per K/V tile
+constexpr int DH = 128;
+constexpr int kMaxBatch = 255;
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ q,
+                                                             const bf16_t* __restrict__ kc,
+                                                             const bf16_t* __restrict__ vc,
+                                                             const int32_t* __restrict__ active_idx,
+                                                             const int32_t* __restrict__ m_dev, int m_upper, int B,
+                                                             int H, int N, int n_pad, bf16_t* __restrict__ o) {
+  __shared__ FragA ldsK[KT * DH / 8];        // 16 KiB
+  __shared__ FragA ldsV[KT * DH / 8];        // 16 KiB
+  __shared__ int cu[kMaxBatch + 2];
+  const int M = min(*m_dev, m_upper);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hh = blockIdx.y;
+  // per-sequence row ranges: cu[b] = first packed row whose flat id >= b*N
+  if (tid <= B) {
+    int lo = 0, hi = M;
+    const long long key = (long long)tid * N;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((long long)active_idx[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    cu[tid] = lo;
+  }
+  __syncthreads();
+  int b = 0, tile = blockIdx.x, row0 = -1, row_end = 0;
+  for (; b < B; ++b) {
+    const int cnt = cu[b + 1] - cu[b];
+    const int nt = (cnt + QT - 1) / QT;
+    if (tile < nt) { row0 = cu[b] + tile * QT; row_end = cu[b + 1]; break; }
+    tile -= nt;
+  }
+  if (row0 < 0) return;                       // uniform across the workgroup
+
+  const size_t head_base = ((size_t)b * H + hh) * n_pad * DH;
+  const FragA* kg = reinterpret_cast<const FragA*>(kc + head_base);
+  const FragA* vg = reinterpret_cast<const FragA*>(vc + head_base);
+
+  // Q^T fragments: lane holds query (lane&31), dims ks*16 + (lane>>5)*8 .. +7
+  const int my_row = row0 + wave * 32 + (lane & 31);
+  const int ld_row = my_row < row_end ? my_row : row_end - 1;
+  FragA qf[8];
+  {
+    const bf16_t* qp = q + ((size_t)ld_row * H + hh) * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const FragA*>(qp + ks * 16);
+  }
+
+  f32x16 acc_o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc_o[i][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(d_h)
+
+  const int n_tiles = n_pad / KT;
+  FragA kreg[4], vreg[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { kreg[i] = kg[tid + 256 * i]; vreg[i] = vg[tid + 256 * i]; }
+
+  for (int kt = 0; kt < n_tiles; ++kt) {
+    __syncthreads();                          // previous tile fully consumed
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { ldsK[tid + 256 * i] = kreg[i]; ldsV[tid + 256 * i] = vreg[i]; }
+    __syncthreads();
+    if (kt + 1 < n_tiles) {
+      const FragA* kn = kg + (size_t)(kt + 1) * (KT * DH / 8);
+      const FragA* vn = vg + (size_t)(kt + 1) * (KT * DH / 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { kreg[i] = kn[tid + 256 * i]; vreg[i] = vn[tid + 256 * i]; }
+    }
+    // S^T = K Q^T : two 32-key blocks
+    f32x16 s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const FragA a = ldsK[(kb * 16 + 2 * ks) * 32 + lane];
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+      }
+    }
+    // accumulator register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
+    if ((kt + 1) * KT > N) {
+      const int kbase = kt * KT + 4 * (lane >> 5);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) s[kb][v] = -INFINITY;
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one real key
+    const float alpha = exp2f((m_run - m_new) * sc);
+    const float mb_ = m_new * sc;
+    float psum = 0.f;
+    FragA pf[4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        p[v] = exp2f(fmaf(s[kb][v], sc, -mb_));
+        psum += p[v];
+      }
+      // step st = 2*kb + j uses registers 8j .. 8j+7: keys 16*st + 8a + 4h + i  <->  e = 4a + i
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pf[2 * kb + j][e] = (__bf16)p[8 * j + e];
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
+    // O^T += V^T P^T
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const FragA a = ldsV[(2 * st + (lane >> 5)) * DH + mb * 32 + (lane & 31)];
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[st], acc_o[mb], 0, 0, 0);
+      }
+    }
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  if (my_row < row_end) {
+    bf16_t* op = o + ((size_t)my_row * H + hh) * DH + 4 * (lane >> 5);
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[mb][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + mb * 32 + 8 * g) = w;
+      }
+  }
+}
+
+int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void* vc, const int32_t* active_idx,
+                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o) {
+  if (m_upper <= 0) return SL_OK;
+  if (B > kMaxBatch || n_pad % KT) return SL_EINVAL;
+  dim3 grid(sl_cdiv(m_upper, QT) + B - 1, H), block(256);
+  hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc,
+                     active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}

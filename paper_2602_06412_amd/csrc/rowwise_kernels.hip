@@ -33,9 +33,11 @@ __global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_kernel(const T* __r
     st<T>::stv(h + (size_t)r * d + c, st<T>::ld(src + c) * rstd * st<T>::ld(gain + c));
 }
 
-// x <- rnd(x + delta) (residual add in fp32), then h = RMSNorm of the STORED x.
+// x <- rnd(x + delta) (residual add in fp32; delta may arrive as S k-split partials),
+// then h = RMSNorm of the STORED x.
 template <typename T, bool ADD>
-__global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const float* __restrict__ delta,
+__global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const float* __restrict__ delta, int S,
+                                                                  size_t sstride,
                                                                   const int32_t* __restrict__ m_dev, int m_upper,
                                                                   int d, const T* __restrict__ gain, float eps,
                                                                   T* __restrict__ h) {
@@ -48,7 +50,9 @@ __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const fl
   for (int c = threadIdx.x; c < d; c += kRowThreads) {
     float v = st<T>::ld(xr + c);
     if (ADD) {
-      v = st<T>::rnd(v + delta[(size_t)r * d + c]);
+      float dl = delta[(size_t)r * d + c];
+      for (int sp = 1; sp < S; ++sp) dl += delta[sp * sstride + (size_t)r * d + c];   // k-split partials, fixed order
+      v = st<T>::rnd(v + dl);
       st<T>::stv(xr + c, v);
     }
     ssq += v * v;
@@ -63,7 +67,7 @@ __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const fl
 // cache slot (the only cache rows this step may touch), q to the packed query buffer.
 // Half-split pairing (j, j + d_h/2); angles come from a table built in fp64 at bind time.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restrict__ qkv,
+__global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, size_t sstride,
                                                             const int32_t* __restrict__ active_idx,
                                                             const int32_t* __restrict__ m_dev, int m_upper, int H,
                                                             int dh, int N, int n_pad,
@@ -80,18 +84,22 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restr
     const int hh = e / half, j = e - hh * half;
     const float2 cs = rope_tab[(size_t)i * half + j];
     const int c0 = hh * dh + j, c1 = c0 + half;
-    const float q0 = row[c0], q1 = row[c1];
-    const float k0 = row[hd + c0], k1 = row[hd + c1];
-    const float v0 = row[2 * hd + c0], v1 = row[2 * hd + c1];
+    float q0 = row[c0], q1 = row[c1];
+    float k0 = row[hd + c0], k1 = row[hd + c1];
+    float v0 = row[2 * hd + c0], v1 = row[2 * hd + c1];
+    for (int sp = 1; sp < S; ++sp) {                     // k-split partials, fixed order
+      const float* pr = row + sp * sstride;
+      q0 += pr[c0]; q1 += pr[c1];
+      k0 += pr[hd + c0]; k1 += pr[hd + c1];
+      v0 += pr[2 * hd + c0]; v1 += pr[2 * hd + c1];
+    }
     st<T>::stv(q + (size_t)r * hd + c0, q0 * cs.x - q1 * cs.y);
     st<T>::stv(q + (size_t)r * hd + c1, q1 * cs.x + q0 * cs.y);
     const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
-    T* krow = kc + head_base + (size_t)i * dh;
-    st<T>::stv(krow + j, k0 * cs.x - k1 * cs.y);
-    st<T>::stv(krow + j + half, k1 * cs.x + k0 * cs.y);
-    T* vblk = vc + head_base + (size_t)(i >> 3) * dh * 8 + (i & 7);
-    st<T>::stv(vblk + (size_t)j * 8, v0);
-    st<T>::stv(vblk + (size_t)(j + half) * 8, v1);
+    st<T>::stv(kc + head_base + kc_index(i, j, dh), k0 * cs.x - k1 * cs.y);
+    st<T>::stv(kc + head_base + kc_index(i, j + half, dh), k1 * cs.x + k0 * cs.y);
+    st<T>::stv(vc + head_base + vc_index(i, j, dh), v0);
+    st<T>::stv(vc + head_base + vc_index(i, j + half, dh), v1);
   }
 }
 
@@ -105,14 +113,19 @@ __global__ void rope_table_kernel(float2* tab, int n_pad, int half, int dh, doub
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, const int32_t* __restrict__ m_dev,
-                                                     int m_upper, int dff, T* __restrict__ a) {
+__global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int S, size_t sstride,
+                                                     const int32_t* __restrict__ m_dev, int m_upper, int dff,
+                                                     T* __restrict__ a) {
   const int M = min(*m_dev, m_upper);
   const int r = blockIdx.y;
   if (r >= M) return;
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= dff) return;
-  const float g = gu[(size_t)r * 2 * dff + c], u = gu[(size_t)r * 2 * dff + dff + c];
+  float g = gu[(size_t)r * 2 * dff + c], u = gu[(size_t)r * 2 * dff + dff + c];
+  for (int sp = 1; sp < S; ++sp) {
+    g += gu[sp * sstride + (size_t)r * 2 * dff + c];
+    u += gu[sp * sstride + (size_t)r * 2 * dff + dff + c];
+  }
   st<T>::stv(a + (size_t)r * dff + c, g / (1.0f + expf(-g)) * u);
 }
 
@@ -127,8 +140,8 @@ __global__ void kv_read_kernel(const T* __restrict__ kc, const T* __restrict__ v
   const int i = (t / ((size_t)dh * H)) % N;
   const int b = t / ((size_t)dh * H * N);
   const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
-  k_out[t] = kc[head_base + (size_t)i * dh + dd];
-  v_out[t] = vc[head_base + (size_t)(i >> 3) * dh * 8 + (size_t)dd * 8 + (i & 7)];
+  k_out[t] = kc[head_base + kc_index(i, dd, dh)];
+  v_out[t] = vc[head_base + vc_index(i, dd, dh)];
 }
 
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
@@ -162,11 +175,11 @@ int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* 
   return SL_OK;
 }
 
-int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, const int32_t* m_dev, int m_upper, int d,
-                    const void* gain, float eps, void* h) {
+int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
+                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h) {
   if (m_upper <= 0) return SL_OK;
   DISPATCH_T(dtype, hipLaunchKernelGGL((add_rmsnorm_kernel<T, true>), dim3(m_upper), dim3(kRowThreads), 0, s, (T*)x,
-                                       delta, m_dev, m_upper, d, (const T*)gain, eps, (T*)h));
+                                       delta, S, sstride, m_dev, m_upper, d, (const T*)gain, eps, (T*)h));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -175,7 +188,7 @@ int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, i
                 float eps, void* h) {
   if (m_upper <= 0) return SL_OK;
   DISPATCH_T(dtype, hipLaunchKernelGGL((add_rmsnorm_kernel<T, false>), dim3(m_upper), dim3(kRowThreads), 0, s,
-                                       (T*)const_cast<void*>(x), (const float*)nullptr, m_dev, m_upper, d,
+                                       (T*)const_cast<void*>(x), (const float*)nullptr, 1, (size_t)0, m_dev, m_upper, d,
                                        (const T*)gain, eps, (T*)h));
   SL_LAUNCH_CHECK();
   return SL_OK;
@@ -189,21 +202,22 @@ int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta) {
   return SL_OK;
 }
 
-int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, const int32_t* active_idx, const int32_t* m_dev,
-                      int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc,
+int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
+                      const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc,
                       void* vc) {
   if (m_upper <= 0) return SL_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_kernel<T>), dim3(m_upper), dim3(256), 0, s, qkv, active_idx,
-                                       m_dev, m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (T*)q, (T*)kc,
+  DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_kernel<T>), dim3(m_upper), dim3(256), 0, s, qkv, S, sstride,
+                                       active_idx, m_dev, m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (T*)q, (T*)kc,
                                        (T*)vc));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
 
-int slk_swiglu(hipStream_t s, int dtype, const float* gu, const int32_t* m_dev, int m_upper, int dff, void* a) {
+int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
+               int dff, void* a) {
   if (m_upper <= 0) return SL_OK;
   DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_kernel<T>), dim3(sl_cdiv(dff, 256), m_upper), dim3(256), 0, s, gu,
-                                       m_dev, m_upper, dff, (T*)a));
+                                       S, sstride, m_dev, m_upper, dff, (T*)a));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

@@ -26,6 +26,20 @@ template <> struct st<bf16_t> {
 
 __device__ inline float bf16_bits_to_f32(uint32_t hi16) { return __uint_as_float(hi16 << 16); }
 
+// ---- K/V cache addressing (elements of T inside one (sequence, head) slab of n_pad slots) ---
+// K: [n_pad/32][d_h/8][32 slots][8]   -> a 32-key x 16-dim MFMA A-operand fragment of QK^T is
+//                                       one contiguous 1 KiB block (lane = slot + 32*(chunk&1))
+// V: [n_pad/16][2][d_h][8]             -> the 8 slots {8a + 4h + i : a<2, i<4} of a 16-slot block
+//                                       sit together at [h][dim][4a + i]: exactly the 8 keys
+//                                       one lane of the S^T = K Q^T accumulator holds, so the
+//                                       P V product needs no transpose or shuffle
+__host__ __device__ inline size_t kc_index(int slot, int dim, int dh) {
+  return (((size_t)(slot >> 5) * (dh >> 3) + (dim >> 3)) * 32 + (slot & 31)) * 8 + (dim & 7);
+}
+__host__ __device__ inline size_t vc_index(int slot, int dim, int dh) {
+  return (((size_t)(slot >> 4) * 2 + ((slot >> 2) & 1)) * dh + dim) * 8 + ((slot >> 3) & 1) * 4 + (slot & 3);
+}
+
 // ---- wave / block reductions (wave = 64 lanes) ------------------------------------
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -113,14 +127,16 @@ int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, 
 // rowwise_kernels.hip
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
                       const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h);
-int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, const int32_t* m_dev, int m_upper,
-                    int d, const void* gain, float eps, void* h);
+// delta / qkv / gu may be S k-split partials, `sstride` floats apart; they are summed in split order
+int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
+                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h);
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d,
                 const void* gain, float eps, void* h);
 int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta);
-int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, const int32_t* active_idx, const int32_t* m_dev,
-                      int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
-int slk_swiglu(hipStream_t s, int dtype, const float* gu, const int32_t* m_dev, int m_upper, int dff, void* a);
+int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
+                      const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
+int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
+               int dff, void* a);
 int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
                 void* k_out, void* v_out);
 int slk_fill_zero(hipStream_t s, void* p, size_t bytes);
@@ -133,7 +149,16 @@ int slk_attention_generic(hipStream_t s, int dtype, const void* q, const void* k
                           const int32_t* active_idx, const int32_t* m_dev, int m_upper,
                           int H, int dh, int N, int n_pad, void* o);
 
-// mfma path (gemm_mfma.hip / attention_mfma.hip / mfma_layer.hip)
+// gemm_mfma.hip
+int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off);
+int slk_gemm_splits(int mu, int n, int k);
+int slk_gemm_mfma(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k, int splits,
+                  float* Cf, void* Cb, const int32_t* row_map, size_t ldc);
+// attention_mfma.hip
+int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void* vc, const int32_t* active_idx,
+                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o);
+// mfma path (mfma_layer.hip)
+size_t sl_mfma_f32_elems(const sl_config* cfg, int mu);
 bool sl_mfma_supported(const sl_config* cfg);
 size_t sl_mfma_packed_bytes(const sl_config* cfg);
 int sl_mfma_pack_all(sl_ctx* ctx, hipStream_t s, void* packed);
