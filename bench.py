@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""SureLock step latency vs unlocked fraction M/N on one MI355X.
+
+Workload (BASELINE config 2): one LLaDA-8B-shaped bf16 layer (d=4096, 32 heads x 128,
+SwiGLU FFN 12288) plus the LLaDA LM head (vocab 126464) so that every step of the hot path
+runs: compaction, gather+RMSNorm, QKV GEMM, RoPE + K/V cache write, M x N attention over
+N=1024 cached slots, Out GEMM, FFN GEMMs, LM head, KL/conf/argmax scoring, UpdateMASK,
+lock rule.  Active sets of M in {1024, 512, 256, 64, 16} positions are drawn uniformly
+without replacement from a seed.  Inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints one JSON line; `value` is the step latency at M = N, `sweep` the latency at each M.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15      # dense bf16 FLOP/s, MI355X
+HBM_PEAK = 8.0e12            # B/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", type=str, default="1024,512,256,64,16")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_06412_amd import binding as B
+    from paper_2602_06412_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    shape, N, Bn = wl.C2, 1024, 1
+    K, W = args.steps, args.warmup
+    sweep = [int(x) for x in args.sweep.split(",")]
+
+    w = wl.make_weights(shape, args.seed, device="cuda", emb_std=1.0)
+    sess = B.Session(shape, w, Bn, N)
+    rng = np.random.default_rng(args.seed)
+    tokens0 = torch.as_tensor(wl.prompt_uniform(args.seed + 1, N, shape.vocab, shape.mask_id), dtype=torch.int32,
+                              device=dev)
+    eps = torch.full((Bn,), 1e-3, dtype=torch.float32, device=dev)
+    zero_mask = torch.zeros(N, dtype=torch.uint8, device=dev)
+    new_lock = torch.zeros(N, dtype=torch.uint8, device=dev)
+
+    # cache + both posterior buffers filled by two M = N passes
+    t = 0
+    for _ in range(2):
+        t += 1
+        sess.step(tokens0.clone(), zero_mask.clone(), zero_mask, eps, t, 0, N, 0, m_upper=N, new_lock=new_lock)
+    torch.cuda.synchronize()
+
+    d, dff, hd, V = shape.d_model, shape.d_ff, shape.n_heads * shape.d_head, shape.vocab
+    layer_gemm_flops = 2 * d * (3 * hd) + 2 * hd * d + 2 * d * (2 * dff) + 2 * dff * d      # per row
+    lm_flops = 2 * d * V
+    attn_flops = 4 * N * hd                                                                 # per row
+    layer_w_bytes = 2 * (d * 3 * hd + hd * d + d * 2 * dff + dff * d)
+    lm_w_bytes = 2 * d * V
+    gemm_slots = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "lm_head"]
+
+    results = []
+    for M in sweep:
+        active = wl.active_positions(args.seed + 100 + M, N, M)
+        lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
+        masked = (1 - lock).clone()                 # every active slot still masked: UpdateMASK has work
+        tokens = tokens0.clone()
+
+        def run(n_steps):
+            nonlocal t
+            for _ in range(n_steps):
+                t += 1
+                sess.step(tokens, masked, lock, eps, t, 0, N, 1, m_upper=M, new_lock=new_lock)
+
+        run(W)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        run(K)
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / K
+        ms = e0.elapsed_time(e1) / K
+        # per-kernel event timing of the same steps (profiling on: separate pass)
+        B.sl_profile_begin(sess.ctx, K * 16)
+        run(K)
+        prof = B.sl_profile_end(sess.ctx)
+        per = {k: v[0] / K for k, v in prof.items()}            # ms per step per kernel slot
+        gemm_ms = sum(per[s] for s in gemm_slots)
+        gemm_flops = M * (layer_gemm_flops + lm_flops)
+        gemm_bytes = layer_w_bytes + lm_w_bytes + 2 * M * (d * 6 + hd * 2 + dff * 2) + 2 * M * V
+        score_bytes = M * V * 4
+        results.append({
+            "M": M, "M_over_N": M / N, "ms": round(ms, 4), "wall_ms": round(wall_ms, 4),
+            "rows_per_s": round(M / (ms * 1e-3), 1),
+            "gemm_ms": round(gemm_ms, 4), "gemm_tflops": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 2),
+            "gemm_mfma_frac": round(gemm_flops / (gemm_ms * 1e-3) / MFMA_BF16_PEAK, 4),
+            "gemm_weight_stream_GBps": round(gemm_bytes / (gemm_ms * 1e-3) / 1e9, 1),
+            "gemm_hbm_frac": round(gemm_bytes / (gemm_ms * 1e-3) / HBM_PEAK, 4),
+            "attention_ms": round(per["attention"], 4),
+            "attention_mfma_frac": round(M * attn_flops / (per["attention"] * 1e-3) / MFMA_BF16_PEAK, 4),
+            "score_ms": round(per["score"], 4),
+            "score_hbm_frac": round(score_bytes / (per["score"] * 1e-3) / HBM_PEAK, 4),
+            "kernels_ms": {k: round(v, 4) for k, v in per.items()},
+        })
+
+    head = results[0]
+    M0 = head["M"]
+    if M0 >= 512:
+        roof = {"kernel": "gemm_mfma_kernel (QKV, Out, gate/up, down, LM head)", "bound": "mfma",
+                "achieved": head["gemm_tflops"], "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                "frac": head["gemm_mfma_frac"], "traffic": None}
+    else:
+        roof = {"kernel": "gemm_mfma_kernel (weight stream)", "bound": "hbm",
+                "achieved": head["gemm_weight_stream_GBps"], "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": head["gemm_hbm_frac"], "traffic": None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(shape, w, tokens0, N)
+
+    out = {
+        "metric": "SureLock step latency (ms) vs unlocked fraction M/N; % bf16 MFMA peak",
+        "value": head["ms"], "unit": "ms", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2: one LLaDA-8B-shaped bf16 layer + LM head (V=126464), N=1024 cached K/V, "
+                               "whole SureLock step at M=%d active rows (value); sweep over M in `sweep`" % M0,
+                   "N": N, "batch": Bn, "M": M0, "d_model": d, "n_heads": shape.n_heads, "d_head": shape.d_head,
+                   "d_ff": dff, "vocab": V, "n_layers": shape.n_layers},
+        "rows_per_s": head["rows_per_s"],
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "sweep": results,
+    }
+    print(json.dumps(out))
+    sess.close()
+
+
+def cpu_baseline(shape, w, tokens0, N):
+    """The oracle, as it stands, on the host cores: one full C2 step at M = N (restricted
+    forward of one layer + LM head + scoring), timed once."""
+    import numpy as np
+    import torch
+    from oracle import model, posterior
+    from oracle.model import Config
+
+    cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab, shape.mask_id,
+                 shape.rms_eps, shape.rope_theta, shape.storage)
+    tok = tokens0.cpu().numpy().astype(np.int64)
+    f64 = lambda t_: t_.detach().to("cpu", torch.float64).numpy()
+    w64 = {"emb": f64(w["emb"][torch.as_tensor(tok, device=w["emb"].device)]),      # only the rows the tokens use
+           "final_norm": f64(w["final_norm"]), "lm_head": f64(w["lm_head"]),
+           "layers": [{k: f64(v) for k, v in l.items()} for l in w["layers"]]}
+    Kc = [np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)]
+    Vc = [np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)]
+    prev = None
+    t0 = time.perf_counter()
+    z = model.forward_active(cfg, w64, np.arange(N), np.arange(N), Kc, Vc)
+    lp = posterior.log_softmax(z)
+    conf = posterior.max_prob(lp)
+    amax = posterior.argmax_lowest(z)
+    D = posterior.kl_rows(lp, lp if prev is None else prev)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except Exception:
+        cores = os.cpu_count()
+    try:
+        import threadpoolctl
+        nthreads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+        cores = min(cores, nthreads) if nthreads else cores
+    except Exception:
+        pass
+    return {"value": round(dt * 1e3, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
+            "sample": "one full step of the same workload at M=N=1024 (1 layer + LM head + KL/conf/argmax), "
+                      "NumPy fp64, timed once", "rows_per_s": round(N / dt, 1),
+            "checksum": float(np.sum(D) + conf[0] + amax[0])}
+
+
+if __name__ == "__main__":
+    main()

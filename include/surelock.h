@@ -200,6 +200,35 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
                  int32_t block_lo, int32_t block_hi, int32_t k,
                  float *kl, float *conf, int32_t *argmax, uint8_t *new_lock);
 
+/* ---- the M-row projection alone ---------------------------------------------------------
+ * y = x W^T for the packed active rows on the MFMA units (the GEMM terms Q, K, V, Out, FFN
+ * of Sec. 2.4), bf16 only; n % 32 == 0, k % 64 == 0.  sl_linear_pack re-tiles W [n, k] into
+ * the fragment layout (same byte count).  sl_linear_forward: x [m_upper, k] bf16; splits = 0
+ * picks the k-split count (query it with sl_linear_splits); exactly one of
+ *   y_f32  [splits][m_upper][n] fp32 partial sums (caller adds the splits), or
+ *   y_bf16 [*, n] bf16 rows, row r written to row row_map[r] (row_map may be null; splits
+ *          must resolve to 1: pass splits = 1)
+ * must be non-null. */
+int sl_linear_pack(void *stream, const void *w, int32_t n, int32_t k, void *packed, size_t packed_bytes);
+int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k);
+int sl_linear_forward(void *stream, const void *x, const void *packed, const int32_t *m_dev, int32_t m_upper,
+                      int32_t n, int32_t k, int32_t splits, float *y_f32, void *y_bf16, const int32_t *row_map);
+
+/* ---- measurement support ------------------------------------------------------------
+ * Per-kernel timing of the step's launches with HIP events on the step's own stream.
+ * Between sl_profile_begin and sl_profile_end every kernel the library launches for this
+ * context is bracketed by an event pair; sl_profile_end synchronises on the last event,
+ * adds the elapsed times up per kernel slot and releases the events.  Host arrays:
+ * ms[SL_PROF_SLOTS], launches[SL_PROF_SLOTS].  Profiling adds host work per launch, so
+ * whole-step latency is measured with profiling off. */
+enum {
+  SL_PROF_COMPACT = 0, SL_PROF_EMBED_NORM, SL_PROF_GEMM_QKV, SL_PROF_ROPE_KV, SL_PROF_ATTENTION,
+  SL_PROF_GEMM_OUT, SL_PROF_ADD_NORM, SL_PROF_GEMM_GATE_UP, SL_PROF_SWIGLU, SL_PROF_GEMM_DOWN,
+  SL_PROF_LM_HEAD, SL_PROF_SCORE, SL_PROF_UNMASK, SL_PROF_LOCK_RULE, SL_PROF_SLOTS
+};
+int sl_profile_begin(sl_ctx *ctx, int32_t max_launches);
+int sl_profile_end(sl_ctx *ctx, float *ms /* host */, int32_t *launches /* host */);
+
 #ifdef __cplusplus
 }
 #endif

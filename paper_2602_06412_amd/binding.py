@@ -50,6 +50,11 @@ _SIGS = {
     "sl_score_posteriors": [_P, _P, _I, _P, _I, _I, _P, _P, _I, _I, _P, _P, _P],
     "sl_unmask_topk": [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I],
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
+    "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
+    "sl_linear_splits": [_I, _I, _I],
+    "sl_linear_forward": [_P, _P, _P, _P, _I, _I, _I, _I, _P, _P, _P],
+    "sl_profile_begin": [_P, _I],
+    "sl_profile_end": [_P, C.POINTER(C.c_float), C.POINTER(_I)],
     "sl_lock_test": [_P, _P, _I, _P, _I, _I, _P, _P, _P, _P, _P, _I, _P, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P],
 }
 EXPORTS = sorted(list(_SIGS) + ["sl_strerror"])
@@ -218,6 +223,40 @@ def sl_lock_test(logits_cur, cur_packed, logits_prev, dtype, vocab, tokens, mask
         _stream(), _ptr(logits_cur), int(cur_packed), _ptr(logits_prev), dtype, vocab, _ptr(tokens), _ptr(masked),
         _ptr(lock), _ptr(active_idx), _ptr(cu_active), m_upper, _ptr(eps), batch, n_seq, int(first_step), block_lo,
         block_hi, k, _ptr(kl), _ptr(conf), _ptr(argmax), _ptr(new_lock)))
+
+
+def sl_linear_pack(w, packed):
+    n, k = w.shape
+    _check("sl_linear_pack", lib().sl_linear_pack(_stream(), _ptr(w), n, k, _ptr(packed),
+                                                  packed.numel() * packed.element_size()))
+
+
+def sl_linear_splits(m_upper, n, k):
+    r = lib().sl_linear_splits(m_upper, n, k)
+    if r < 0:
+        raise SureLockError("sl_linear_splits", r)
+    return r
+
+
+def sl_linear_forward(x, packed, m_dev, m_upper, n, k, splits=0, y_f32=None, y_bf16=None, row_map=None):
+    _check("sl_linear_forward", lib().sl_linear_forward(_stream(), _ptr(x), _ptr(packed), _ptr(m_dev), m_upper, n, k,
+                                                        splits, _ptr(y_f32), _ptr(y_bf16), _ptr(row_map)))
+
+
+PROF_SLOTS = ["compact", "embed_norm", "gemm_qkv", "rope_kv", "attention", "gemm_out", "add_norm", "gemm_gate_up",
+              "swiglu", "gemm_down", "lm_head", "score", "unmask", "lock_rule"]
+
+
+def sl_profile_begin(ctx, max_launches):
+    _check("sl_profile_begin", lib().sl_profile_begin(ctx, max_launches))
+
+
+def sl_profile_end(ctx):
+    """Returns {slot name: (total ms, launches)}."""
+    n = len(PROF_SLOTS)
+    ms, cnt = (C.c_float * n)(), (_I * n)()
+    _check("sl_profile_end", lib().sl_profile_end(ctx, ms, cnt))
+    return {PROF_SLOTS[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 # ---- device-memory plumbing for one model + one batch geometry ---------------------------------

@@ -47,8 +47,57 @@ extern "C" int sl_init(const sl_config* cfg, sl_ctx** out) {
   return SL_OK;
 }
 
+static void prof_free(sl_ctx* ctx) {
+  if (!ctx->prof) return;
+  for (int i = 0; i < 2 * ctx->prof->cap; ++i)
+    if (ctx->prof->ev[i]) (void)hipEventDestroy(ctx->prof->ev[i]);
+  delete[] ctx->prof->ev;
+  delete[] ctx->prof->slot;
+  delete ctx->prof;
+  ctx->prof = nullptr;
+}
+
+extern "C" int sl_profile_begin(sl_ctx* ctx, int32_t max_launches) {
+  if (!ctx || max_launches < 1 || max_launches > (1 << 20)) return SL_EINVAL;
+  prof_free(ctx);
+  sl_prof* p = new (std::nothrow) sl_prof();
+  if (!p) return SL_ENOSPC;
+  p->cap = max_launches;
+  p->n = 0;
+  p->ev = new (std::nothrow) hipEvent_t[2 * (size_t)max_launches]();
+  p->slot = new (std::nothrow) int[max_launches];
+  ctx->prof = p;
+  if (!p->ev || !p->slot) { prof_free(ctx); return SL_ENOSPC; }
+  for (int i = 0; i < 2 * max_launches; ++i) {
+    const hipError_t e = hipEventCreate(&p->ev[i]);
+    if (e != hipSuccess) { g_sl_last_hip_error = (int)e; prof_free(ctx); return SL_EHIP; }
+  }
+  return SL_OK;
+}
+
+extern "C" int sl_profile_end(sl_ctx* ctx, float* ms, int32_t* launches) {
+  if (!ctx || !ms || !launches) return SL_EINVAL;
+  if (!ctx->prof) return SL_ESTATE;
+  for (int i = 0; i < SL_PROF_SLOTS; ++i) { ms[i] = 0.f; launches[i] = 0; }
+  sl_prof* p = ctx->prof;
+  int rc = SL_OK;
+  if (p->n > 0) {
+    hipError_t e = hipEventSynchronize(p->ev[2 * p->n - 1]);
+    for (int i = 0; i < p->n && e == hipSuccess; ++i) {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, p->ev[2 * i], p->ev[2 * i + 1]);
+      ms[p->slot[i]] += t;
+      launches[p->slot[i]] += 1;
+    }
+    if (e != hipSuccess) { g_sl_last_hip_error = (int)e; rc = SL_EHIP; }
+  }
+  prof_free(ctx);
+  return rc;
+}
+
 extern "C" int sl_destroy(sl_ctx* ctx) {
   if (!ctx) return SL_EINVAL;
+  prof_free(ctx);
   delete[] ctx->layers;
   delete[] ctx->packed;
   delete ctx;
@@ -162,11 +211,11 @@ extern "C" int sl_logits_ptr(const sl_ctx* ctx, int32_t t, void** out) {
 // ---- workspace -----------------------------------------------------------------------------------
 struct Workspace {
   char *x, *h, *q, *o, *a;
-  float* f32;
+  float *f32, *attn;
   size_t bytes;
 };
 
-static Workspace carve(const sl_ctx* ctx, void* base, int rows) {
+static Workspace carve(const sl_ctx* ctx, void* base, int rows, int batch, int n_seq) {
   const sl_config& c = ctx->cfg;
   const size_t ts = sl_tsize(c.dtype);
   const size_t hd = (size_t)c.n_heads * c.d_head;
@@ -187,13 +236,18 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows) {
     if (e > f32_elems) f32_elems = e;
   }
   w.f32 = (float*)take(f32_elems * sizeof(float));
+  w.attn = nullptr;
+  if (ctx->use_mfma) {
+    const int n_pad = (int)sl_align_up((size_t)n_seq, 64);
+    w.attn = (float*)take(slk_attention_scratch_elems(rows, batch, c.n_heads, n_pad) * sizeof(float));
+  }
   w.bytes = off;
   return w;
 }
 
 extern "C" int sl_workspace_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
   if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
-  *out = carve(ctx, nullptr, batch * n_seq).bytes;
+  *out = carve(ctx, nullptr, batch * n_seq, batch, n_seq).bytes;
   return SL_OK;
 }
 
@@ -212,25 +266,25 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     const sl_layer_weights& L = ctx->layers[l];
     const void* next_gain = (l + 1 < c.n_layers) ? ctx->layers[l + 1].attn_norm : ctx->plain.final_norm;
     if (ctx->use_mfma) {
-      SL_TRY(sl_mfma_layer(ctx, s, l, ws.x, ws.h, ws.q, ws.o, ws.a, ws.f32, active_idx, m_dev, mu, next_gain));
+      SL_TRY(sl_mfma_layer(ctx, s, l, ws.x, ws.h, ws.q, ws.o, ws.a, ws.f32, ws.attn, active_idx, m_dev, mu, next_gain));
       continue;
     }
     // Q, K, V projections of the active rows (fp32 results side by side)
-    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wq, m_dev, mu, hd, d, ws.f32, nullptr, nullptr, 3 * (size_t)hd));
-    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wk, m_dev, mu, hd, d, ws.f32 + hd, nullptr, nullptr, 3 * (size_t)hd));
-    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.wv, m_dev, mu, hd, d, ws.f32 + 2 * hd, nullptr, nullptr, 3 * (size_t)hd));
+    SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_generic(s, dt, ws.h, L.wq, m_dev, mu, hd, d, ws.f32, nullptr, nullptr, 3 * (size_t)hd));
+    SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_generic(s, dt, ws.h, L.wk, m_dev, mu, hd, d, ws.f32 + hd, nullptr, nullptr, 3 * (size_t)hd));
+    SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_generic(s, dt, ws.h, L.wv, m_dev, mu, hd, d, ws.f32 + 2 * hd, nullptr, nullptr, 3 * (size_t)hd));
     // RoPE; live K/V overwrite the rows' own cache slots (locked slots are never touched)
-    SL_TRY(slk_rope_kv_write(s, dt, ws.f32, 1, 0, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
+    SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, dt, ws.f32, 1, 0, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
                              kv_k_layer(ctx, l), kv_v_layer(ctx, l)));
-    SL_TRY(slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
+    SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
                                  ctx->n_seq, ctx->n_pad, ws.o));
-    SL_TRY(slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
-    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
-    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
-    SL_TRY(slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
-    SL_TRY(slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a));
-    SL_TRY(slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
-    SL_TRY(slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
+    SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
+    SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
+    SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
+    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a));
+    SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
   }
   return SL_OK;
 }
@@ -251,7 +305,7 @@ extern "C" int sl_forward_layers(sl_ctx* ctx, void* stream, const void* x_in, vo
   if (layer_lo < 0 || layer_hi > ctx->cfg.n_layers || layer_lo >= layer_hi) return SL_EINVAL;
   if ((uintptr_t)workspace % 256) return SL_EINVAL;
   if (m_upper == 0) return SL_OK;
-  const Workspace ws = carve(ctx, workspace, m_upper);
+  const Workspace ws = carve(ctx, workspace, m_upper, ctx->batch, ctx->n_seq);
   if (workspace_bytes < ws.bytes) return SL_ENOSPC;
   hipStream_t s = (hipStream_t)stream;
   const sl_config& c = ctx->cfg;
@@ -316,6 +370,30 @@ extern "C" int sl_lock_test(void* stream, const void* logits_cur, int32_t cur_pa
   return sl_lock_rule(stream, lock, masked, active_idx, m_dev, m_upper, kl, eps, batch, n_seq, first_step, new_lock);
 }
 
+// ---- standalone projection ---------------------------------------------------------------------------
+extern "C" int sl_linear_pack(void* stream, const void* w, int32_t n, int32_t k, void* packed, size_t packed_bytes) {
+  if (!w || !packed || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
+  if ((uintptr_t)w % 16 || (uintptr_t)packed % 16) return SL_EINVAL;
+  if (packed_bytes < (size_t)n * k * 2) return SL_ENOSPC;
+  return slk_pack_weight((hipStream_t)stream, w, n, k, packed, 0);
+}
+
+extern "C" int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k) {
+  if (m_upper < 1 || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
+  return slk_gemm_splits(m_upper, n, k);
+}
+
+extern "C" int sl_linear_forward(void* stream, const void* x, const void* packed, const int32_t* m_dev, int32_t m_upper,
+                                 int32_t n, int32_t k, int32_t splits, float* y_f32, void* y_bf16,
+                                 const int32_t* row_map) {
+  if (!x || !packed || !m_dev || m_upper < 0 || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
+  if ((y_f32 == nullptr) == (y_bf16 == nullptr)) return SL_EINVAL;
+  if ((uintptr_t)x % 16 || (uintptr_t)packed % 16) return SL_EINVAL;
+  if (splits == 0) splits = y_f32 ? slk_gemm_splits(m_upper, n, k) : 1;
+  if (splits < 1 || k % (64 * splits) || (y_bf16 && splits != 1)) return SL_EINVAL;
+  return slk_gemm_mfma((hipStream_t)stream, x, packed, m_dev, m_upper, n, k, splits, y_f32, y_bf16, row_map, n);
+}
+
 // ---- the step --------------------------------------------------------------------------------------
 extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
                                 const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,
@@ -330,15 +408,15 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   if (block_lo < 0 || block_hi > N || block_lo > block_hi || k < 0) return SL_EINVAL;
   if ((size_t)(block_hi - block_lo) * 8 > 60 * 1024) return SL_EINVAL;
   if ((uintptr_t)workspace % 256) return SL_EINVAL;
-  const Workspace ws = carve(ctx, workspace, m_upper);
+  const Workspace ws = carve(ctx, workspace, m_upper, ctx->batch, ctx->n_seq);
   if (workspace_bytes < ws.bytes) return SL_ENOSPC;
   hipStream_t s = (hipStream_t)stream;
   const sl_config& c = ctx->cfg;
   const int32_t* m_dev = cu_active + B;
   // A_t
-  SL_TRY(slk_compact_active(s, lock, B, N, active_idx, cu_active));
+  SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, lock, B, N, active_idx, cu_active));
   // block input of the active rows + first LN
-  SL_TRY(slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model,
+  SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model,
                            ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h));
   SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, 0, c.n_layers));
   // logits of the active rows, written to their rows of this step's posterior buffer
@@ -346,12 +424,13 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   sl_logits_ptr(ctx, t, &cur);
   sl_logits_ptr(ctx, t - 1, &prev);
   if (ctx->use_mfma)
-    SL_TRY(sl_mfma_lm_head(ctx, s, ws.h, active_idx, m_dev, m_upper, cur));
+    SL_RUN(ctx, s, SL_PROF_LM_HEAD, sl_mfma_lm_head(ctx, s, ws.h, active_idx, m_dev, m_upper, cur));
   else
-    SL_TRY(slk_gemm_generic(s, c.dtype, ws.h, ctx->plain.lm_head, m_dev, m_upper, c.vocab, c.d_model, nullptr, cur,
+    SL_RUN(ctx, s, SL_PROF_LM_HEAD, slk_gemm_generic(s, c.dtype, ws.h, ctx->plain.lm_head, m_dev, m_upper, c.vocab, c.d_model, nullptr, cur,
                             active_idx, c.vocab));
   // score -> UpdateMASK -> candidates -> lock
-  SL_TRY(slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax));
-  SL_TRY(slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
-  return slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock);
+  SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax));
+  SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
+  SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
+  return SL_OK;
 }

@@ -29,12 +29,18 @@ constexpr int kMaxBatch = 255;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
+// SPLIT: the key tiles are divided over gridDim.z workgroups (thin launches would otherwise
+// leave most CUs idle and walk all N slots serially); each writes its unnormalised O, running
+// max and sum, and attention_merge_kernel combines them.
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ q,
                                                              const bf16_t* __restrict__ kc,
                                                              const bf16_t* __restrict__ vc,
                                                              const int32_t* __restrict__ active_idx,
                                                              const int32_t* __restrict__ m_dev, int m_upper, int B,
-                                                             int H, int N, int n_pad, bf16_t* __restrict__ o) {
+                                                             int H, int N, int n_pad, bf16_t* __restrict__ o,
+                                                             int tiles_per_split, float* __restrict__ part_o,
+                                                             float* __restrict__ part_ml) {
   __shared__ FragA ldsK[KT * DH / 8];        // 16 KiB
   __shared__ FragA ldsV[KT * DH / 8];        // 16 KiB
   __shared__ int cu[kMaxBatch + 2];
@@ -83,12 +89,17 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(d_h)
 
-  const int n_tiles = n_pad / KT;
+  const int kt_lo = SPLIT ? blockIdx.z * tiles_per_split : 0;
+  const int n_tiles = SPLIT ? min(n_pad / KT, kt_lo + tiles_per_split) : n_pad / KT;
   FragA kreg[4], vreg[4];
+  {
+    const FragA* k0 = kg + (size_t)kt_lo * (KT * DH / 8);
+    const FragA* v0 = vg + (size_t)kt_lo * (KT * DH / 8);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { kreg[i] = kg[tid + 256 * i]; vreg[i] = vg[tid + 256 * i]; }
+    for (int i = 0; i < 4; ++i) { kreg[i] = k0[tid + 256 * i]; vreg[i] = v0[tid + 256 * i]; }
+  }
 
-  for (int kt = 0; kt < n_tiles; ++kt) {
+  for (int kt = kt_lo; kt < n_tiles; ++kt) {
     __syncthreads();                          // previous tile fully consumed
 #pragma unroll
     for (int i = 0; i < 4; ++i) { ldsK[tid + 256 * i] = kreg[i]; ldsV[tid + 256 * i] = vreg[i]; }
@@ -162,6 +173,23 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
     }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (SPLIT) {
+    if (my_row < row_end) {
+      const size_t slot = ((size_t)blockIdx.z * m_upper + my_row) * H + hh;
+      float* po = part_o + slot * DH + 4 * (lane >> 5);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(po + mb * 32 + 8 * g) =
+              make_float4(acc_o[mb][4 * g], acc_o[mb][4 * g + 1], acc_o[mb][4 * g + 2], acc_o[mb][4 * g + 3]);
+      if (lane < 32) {
+        part_ml[slot * 2] = m_run * sc;          // running max in the exp2 domain
+        part_ml[slot * 2 + 1] = l_tot;
+      }
+    }
+    return;
+  }
   const float inv = 1.0f / l_tot;
   if (my_row < row_end) {
     bf16_t* op = o + ((size_t)my_row * H + hh) * DH + 4 * (lane >> 5);
@@ -177,13 +205,70 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   }
 }
 
+// o[row, h, :] = sum_z 2^(m_z - m) O_z / sum_z 2^(m_z - m) l_z over the key splits z
+__global__ __launch_bounds__(128) void attention_merge_kernel(const float* __restrict__ part_o,
+                                                              const float* __restrict__ part_ml,
+                                                              const int32_t* __restrict__ m_dev, int m_upper, int H,
+                                                              int Z, bf16_t* __restrict__ o) {
+  const int M = min(*m_dev, m_upper);
+  const int row = blockIdx.x, hh = blockIdx.y, dd = threadIdx.x;
+  if (row >= M) return;
+  float mx = -INFINITY;
+  for (int z = 0; z < Z; ++z) mx = fmaxf(mx, part_ml[(((size_t)z * m_upper + row) * H + hh) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int z = 0; z < Z; ++z) {
+    const size_t slot = ((size_t)z * m_upper + row) * H + hh;
+    const float w = exp2f(part_ml[slot * 2] - mx);
+    num = fmaf(w, part_o[slot * DH + dd], num);
+    den = fmaf(w, part_ml[slot * 2 + 1], den);
+  }
+  o[((size_t)row * H + hh) * DH + dd] = (bf16_t)(num / den);
+}
+
+// Key-split plan for a launch bounded by m_upper rows: split while fewer than ~2 workgroups
+// per CU would run.  Returns Z (1 = no split) and the tiles per split.
+int slk_attention_splits(int m_upper, int B, int H, int n_pad, int* tiles_per_split) {
+  const int n_tiles = n_pad / KT;
+  const int blocks = (sl_cdiv(m_upper, QT) + B - 1) * H;
+  int Z = 1;
+  if (blocks < 256) Z = sl_cdiv(512, blocks);
+  if (Z > n_tiles) Z = n_tiles;
+  const int tps = sl_cdiv(n_tiles, Z);
+  *tiles_per_split = tps;
+  return sl_cdiv(n_tiles, tps);
+}
+
+// fp32 scratch floats the split path may need for any launch of at most m_upper rows
+size_t slk_attention_scratch_elems(int m_upper, int B, int H, int n_pad) {
+  size_t best = 0;
+  for (int mu = 1; mu <= m_upper; ++mu) {
+    int tps;
+    const int Z = slk_attention_splits(mu, B, H, n_pad, &tps);
+    if (Z > 1 && (size_t)Z * mu * H * (DH + 2) > best) best = (size_t)Z * mu * H * (DH + 2);
+  }
+  return best;
+}
+
 int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void* vc, const int32_t* active_idx,
-                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o) {
+                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o, float* scratch) {
   if (m_upper <= 0) return SL_OK;
   if (B > kMaxBatch || n_pad % KT) return SL_EINVAL;
-  dim3 grid(sl_cdiv(m_upper, QT) + B - 1, H), block(256);
-  hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc,
-                     active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o);
+  int tps;
+  const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
+  dim3 grid(sl_cdiv(m_upper, QT) + B - 1, H, Z), block(256);
+  if (Z == 1) {
+    hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc,
+                       (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, 0, nullptr, nullptr);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
+  float* part_o = scratch;
+  float* part_ml = scratch + (size_t)Z * m_upper * H * DH;
+  hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc,
+                     (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, tps, part_o, part_ml);
+  SL_LAUNCH_CHECK();
+  hipLaunchKernelGGL(attention_merge_kernel, dim3(m_upper, H), dim3(DH), 0, s, part_o, part_ml, m_dev, m_upper, H, Z,
+                     (bf16_t*)o);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

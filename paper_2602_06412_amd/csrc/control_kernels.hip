@@ -50,20 +50,22 @@ int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t
 }
 
 // ---- UpdateMASK: top-k by confidence inside the current block, one workgroup per sequence --
-// Eligible rows are appended to an LDS list; each entry's rank is the number of entries
-// that beat it (higher conf, or equal conf and lower position); rank < k is selected.
-// Comparisons are on the fp32 conf values; rows are in position order, so comparing row
-// ids compares positions.
+// Every eligible row gets the 64-bit key (conf bits << 32) | ~row: keys are distinct, a larger
+// key means more confident, and among equal confidences the lower position (= lower packed
+// row) wins.  The k-th largest key is found by an 8-bit-per-pass radix select over LDS
+// histograms; rows whose key reaches it are unmasked.  Confidences are probabilities
+// (non-negative floats), whose bit patterns order like the values.
 __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ tokens, uint8_t* __restrict__ masked,
                                                           const int32_t* __restrict__ active_idx,
                                                           const int32_t* __restrict__ cu_active,
                                                           const float* __restrict__ conf,
                                                           const int32_t* __restrict__ argmax, int N, int lo, int hi,
                                                           int k) {
-  extern __shared__ unsigned char smem_raw[];
-  float* e_conf = reinterpret_cast<float*>(smem_raw);
-  int* e_row = reinterpret_cast<int*>(smem_raw) + (hi - lo);
+  extern __shared__ unsigned long long keys[];     // [hi - lo]
   __shared__ int count;
+  __shared__ int hist[256];
+  __shared__ unsigned long long prefix_sh;
+  __shared__ int want_sh;
   const int b = blockIdx.x, tid = threadIdx.x;
   const int r0 = cu_active[b], r1 = cu_active[b + 1];
   if (tid == 0) count = 0;
@@ -73,21 +75,43 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
     const int i = g - b * N;
     if (i >= lo && i < hi && masked[g]) {
       const int slot = atomicAdd(&count, 1);
-      e_conf[slot] = conf[r];
-      e_row[slot] = r;
+      keys[slot] = ((unsigned long long)__float_as_uint(conf[r]) << 32) | (unsigned)(~(unsigned)r);
     }
   }
   __syncthreads();
   const int n = count;
-  for (int e = tid; e < n; e += 256) {
-    const float c = e_conf[e];
-    const int r = e_row[e];
-    int rank = 0;
-    for (int f = 0; f < n; ++f) {
-      const float cf = e_conf[f];
-      rank += (cf > c || (cf == c && e_row[f] < r)) ? 1 : 0;
+  if (n == 0) return;
+  unsigned long long thresh = 0;                   // k >= n: everything eligible is taken
+  if (k < n) {
+    // radix select of the k-th largest key, most significant byte first
+    if (tid == 0) { prefix_sh = 0; want_sh = k; }
+    for (int shift = 56; shift >= 0; shift -= 8) {
+      hist[tid] = 0;
+      __syncthreads();
+      const unsigned long long prefix = prefix_sh;
+      const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
+      for (int e = tid; e < n; e += 256) {
+        const unsigned long long key = keys[e];
+        if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 0xff)], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int want = want_sh, bin = 255;
+        for (; bin > 0; --bin) {                   // walk down from the largest byte value
+          if (hist[bin] >= want) break;
+          want -= hist[bin];
+        }
+        want_sh = want;
+        prefix_sh = prefix | ((unsigned long long)bin << shift);
+      }
+      __syncthreads();
     }
-    if (rank < k) {
+    thresh = prefix_sh;
+  }
+  for (int e = tid; e < n; e += 256) {
+    const unsigned long long key = keys[e];
+    if (key >= thresh) {
+      const int r = (int)(~(unsigned)(key & 0xffffffffu));
       const int g = active_idx[r];
       tokens[g] = argmax[r];
       masked[g] = 0;

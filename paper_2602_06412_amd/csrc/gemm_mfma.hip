@@ -17,6 +17,7 @@
 //  * Workgroup ids are mapped so that all M-tiles of one weight slab run back to back on
 //    the same XCD (ids are dealt round-robin over the 8 XCDs), i.e. re-reads hit that L2.
 #include "sl_common.h"
+#include <stdlib.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -49,15 +50,18 @@ int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_
 // ---- the kernel ----------------------------------------------------------------------------
 // OUT = 0: fp32 partials Cf[split][row][n] (ldc = n, split stride = m_upper * n)
 // OUT = 1: bf16 rows Cb[row_map ? row_map[row] : row][n] (no split-k)
-template <int BM, int WNB, int OUT>
-__global__ __launch_bounds__(256, (BM <= 64 ? 2 : 1)) void gemm_mfma_kernel(
+template <int BM, int WNB, int OUT, int DBG = 0>
+__global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
     const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
   constexpr int MB = BM / 32;          // 32-row blocks per tile
   constexpr int BN = 128 * WNB;
-  constexpr int NF = MB;               // A fragments each wave stages per k-tile (MB*4 / 4 waves)
-  extern __shared__ Frag lds[];       // [2 stages][MB][4 kb][64 lanes] x 16 B
+  constexpr int NF = MB;               // A fragments each wave fetches per k-tile (MB*4 / 4 waves)
+  // Two LDS stages as separate arrays, so the compiler can tell which stage an in-flight
+  // direct-to-LDS load targets and does not make reads of the other stage wait for it.
+  __shared__ Frag stage0[MB * 4 * 64];
+  __shared__ Frag stage1[MB * 4 * 64];
 
   const int M = min(*m_dev, m_upper);
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
@@ -71,22 +75,27 @@ __global__ __launch_bounds__(256, (BM <= 64 ? 2 : 1)) void gemm_mfma_kernel(
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int K16 = k / 16, NB32 = n / 32;
 
-  const Frag* Bp[WNB];
+  // Per-lane 32-bit offsets from wave-uniform bases keep the address registers few.
+  const Frag* Wf = reinterpret_cast<const Frag*>(Wp) + (size_t)(kbeg / 16) * 64;
+  uint32_t b_off[WNB];
 #pragma unroll
   for (int i = 0; i < WNB; ++i) {
     int nb = n0 / 32 + wave * WNB + i;
     nb = nb < NB32 ? nb : NB32 - 1;                      // column tail: load something valid, never stored
-    Bp[i] = reinterpret_cast<const Frag*>(Wp) + ((size_t)nb * K16 + kbeg / 16) * 64 + lane;
+    b_off[i] = (uint32_t)nb * (uint32_t)K16 * 64u + (uint32_t)lane;
   }
-  const bf16_t* Ap[NF];
-  int a_slot[NF];
+  // Activation fragments go global -> LDS directly (no register staging): the hardware puts
+  // lane L's 16 bytes at (wave-uniform LDS base) + 16*L, which is the fragment order.
+  const bf16_t* Ab = A + kbeg;
+  uint32_t a_off[NF];
+  int a_frag[NF];                                         // fragment index (mb*4 + kb) inside a stage
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const int f = wave + 4 * i, mb = f % MB, kb = f / MB;
     int row = m0 + mb * 32 + (lane & 31);
     row = row < m_upper ? row : m_upper - 1;              // row tail: stay inside the buffer
-    Ap[i] = A + (size_t)row * k + kbeg + kb * 16 + (lane >> 5) * 8;
-    a_slot[i] = (mb * 4 + kb) * 64 + lane;
+    a_off[i] = (uint32_t)row * (uint32_t)k + (uint32_t)(kb * 16 + (lane >> 5) * 8);
+    a_frag[i] = mb * 4 + kb;
   }
 
   f32x16 acc[MB][WNB];
@@ -97,49 +106,68 @@ __global__ __launch_bounds__(256, (BM <= 64 ? 2 : 1)) void gemm_mfma_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  Frag a_reg[NF];
-  Frag b_cur[WNB][4], b_nxt[WNB][4];
-  // prologue: tile 0
+  Frag b0[WNB][4], b1[WNB][4];          // weight fragments of the even / odd k-tile (ping-pong, no copies)
+
+  auto load_a = [&](int kt, Frag* stage) {
+    const bf16_t* base = Ab + kt * BK;
 #pragma unroll
-  for (int i = 0; i < NF; ++i) a_reg[i] = *reinterpret_cast<const Frag*>(Ap[i]);
+    for (int i = 0; i < NF; ++i)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + a_off[i]),
+                                       (__attribute__((address_space(3))) void*)(stage + a_frag[i] * 64), 16, 0, 0);
+  };
+  auto load_b = [&](int kt, Frag (&b)[WNB][4]) {
+    const Frag* base = Wf + kt * 256;
+#pragma unroll
+    for (int i = 0; i < WNB; ++i)
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) b[i][kb] = base[b_off[i] + kb * 64];
+  };
+  // One k-tile: A fragments are read one k-step ahead of the MFMAs that use them.
+  auto compute = [&](const Frag* stage, const Frag (&b)[WNB][4]) {
+    Frag af[2][MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) af[0][mb] = stage[(mb * 4) * 64 + lane];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      if (kb < 3) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) af[(kb + 1) & 1][mb] = stage[(mb * 4 + kb + 1) * 64 + lane];
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < WNB; ++i)
+          acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kb & 1][mb], b[i][kb], acc[mb][i], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  load_b(0, b0);
+  load_a(0, stage0);
 #pragma unroll
   for (int i = 0; i < WNB; ++i)
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) b_cur[i][kb] = Bp[i][kb * 64];
-#pragma unroll
-  for (int i = 0; i < NF; ++i) lds[a_slot[i]] = a_reg[i];
+    for (int kb = 0; kb < 4; ++kb) asm volatile("" : "+v"(b0[i][kb]));   // pin: loads stay above the wait
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load issued so far has landed
   __syncthreads();
 
-  for (int kt = 0; kt < ktiles; ++kt) {
-    const bool more = kt + 1 < ktiles;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < NF; ++i) a_reg[i] = *reinterpret_cast<const Frag*>(Ap[i] + (kt + 1) * BK);
-#pragma unroll
-      for (int i = 0; i < WNB; ++i)
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) b_nxt[i][kb] = Bp[i][((kt + 1) * 4 + kb) * 64];
-    }
-    const Frag* stage = lds + (kt & 1) * (MB * 4 * 64);
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const Frag a = stage[(mb * 4 + kb) * 64 + lane];
-#pragma unroll
-        for (int i = 0; i < WNB; ++i)
-          acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b_cur[i][kb], acc[mb][i], 0, 0, 0);
-      }
-    }
-    if (more) {
-      Frag* nstage = lds + ((kt + 1) & 1) * (MB * 4 * 64);
-#pragma unroll
-      for (int i = 0; i < NF; ++i) nstage[a_slot[i]] = a_reg[i];
-#pragma unroll
-      for (int i = 0; i < WNB; ++i)
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) b_cur[i][kb] = b_nxt[i][kb];
-    }
+  // Two k-tiles per trip (the tile count per split is even).  While tile kt is multiplied out
+  // of one LDS stage and one register set, tile kt+1 is in flight towards the other stage /
+  // set; the last trip re-fetches the final tile instead of branching (never used).  The
+  // direct-to-LDS loads must have landed (vmcnt) before the barrier that publishes them.
+  const int last = ktiles - 1;
+  for (int kt = 0; kt < ktiles; kt += 2) {
+    if (DBG != 1 && DBG != 6) load_b(kt + 1, b1);
+    if (DBG != 1 && DBG != 5) load_a(kt + 1, stage1);
+    compute(stage0, b0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load issued so far has landed
+    __syncthreads();
+    const int nk = kt + 2 < ktiles ? kt + 2 : last;
+    if (DBG != 1 && DBG != 6) load_b(nk, b0);
+    if (DBG != 1 && DBG != 5) load_a(nk, stage0);
+    compute(stage1, b1);
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load issued so far has landed
     __syncthreads();
   }
 
@@ -167,28 +195,31 @@ __global__ __launch_bounds__(256, (BM <= 64 ? 2 : 1)) void gemm_mfma_kernel(
 }
 
 // ---- host side ------------------------------------------------------------------------------
-// Number of k-splits for a launch bounded by mu rows: enough workgroups to cover the chip
-// twice over, capped so that the fp32 partial traffic stays under a quarter of the weight
-// bytes and each split keeps at least two k-tiles.
+// Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
+// measured at least as fast as 256 x 256 at one per CU for every projection shape here.
+static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
+
+// Number of k-splits for a launch bounded by mu rows: enough workgroups for two per CU,
+// capped so that the fp32 partial traffic (written here, read back by the consumer) stays
+// small against the weight stream (thin-M regime: k >= 16*S*mu) or against the MFMA time
+// (thick-M regime: S <= k/2048), and each split keeps an even number (>= 4) of k-tiles.
 int slk_gemm_splits(int mu, int n, int k) {
-  const int bm = mu <= 32 ? 32 : mu <= 64 ? 64 : mu <= 128 ? 128 : 256;
+  const int bm = pick_bm(mu);
   const int tiles = sl_cdiv(mu, bm) * sl_cdiv(n, 256);
-  const int target = bm <= 64 ? 512 : 256;
   int s = 1;
-  while (s < 16 && tiles * s < target && (k % (BK * s * 2) == 0) && (k / (BK * s * 2) >= 2) &&
-         (size_t)(s * 2) * 16 * mu <= (size_t)k)
+  while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
+         ((size_t)(s * 2) * 16 * mu <= (size_t)k || s * 2 <= k / 2048))
     s *= 2;
   return s;
 }
 
-template <int BM, int WNB, int OUT>
+template <int BM, int WNB, int OUT, int DBG = 0>
 static int launch_gemm(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                        int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   constexpr int BN = 128 * WNB;
   const int tiles_m = sl_cdiv(mu, BM), tiles_n = sl_cdiv(n, BN);
-  const size_t sh = (size_t)2 * (BM / 32) * 4 * 64 * 16;
-  auto kern = gemm_mfma_kernel<BM, WNB, OUT>;
-  if (sh > 48 * 1024) SL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+  const size_t sh = 0;
+  auto kern = gemm_mfma_kernel<BM, WNB, OUT, DBG>;
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(256);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
                      (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
@@ -201,14 +232,27 @@ static int launch_gemm(hipStream_t s, const void* A, const void* Wp, const int32
 int slk_gemm_mfma(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k, int splits,
                   float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   if (mu <= 0) return SL_OK;
-  if (n % 32 || k % (BK * splits) || splits < 1) return SL_EINVAL;
+  if (splits < 1 || n % 32 || k % (2 * BK * splits)) return SL_EINVAL;     // even number of k-tiles per split
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;   // 32-bit offsets
   if (!Cf && splits != 1) return SL_EINVAL;
 #define GO(BM)                                                                                             \
   return Cf ? launch_gemm<BM, 2, 0>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
             : launch_gemm<BM, 2, 1>(s, A, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  if (mu <= 32) { GO(32); }
-  if (mu <= 64) { GO(64); }
-  if (mu <= 128) { GO(128); }
-  GO(256);
+  static const int dbg = getenv("SL_GEMM_DBG") ? atoi(getenv("SL_GEMM_DBG")) : 0;
+  if (dbg == 1 && Cf) return launch_gemm<128, 2, 0, 1>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 2 && Cf) return launch_gemm<128, 2, 0, 2>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 5 && Cf) return launch_gemm<128, 2, 0, 5>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 6 && Cf) return launch_gemm<128, 2, 0, 6>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 3 && Cf) return launch_gemm<256, 2, 0, 1>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 4 && Cf) return launch_gemm<256, 2, 0, 2>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  static const int force_bm = getenv("SL_GEMM_BM") ? atoi(getenv("SL_GEMM_BM")) : 0;   // tuning aid
+  if (force_bm == 32) { GO(32); }
+  if (force_bm == 64) { GO(64); }
+  if (force_bm == 128) { GO(128); }
+  if (force_bm == 256) { GO(256); }
+  const int bm = pick_bm(mu);
+  if (bm == 32) { GO(32); }
+  if (bm == 64) { GO(64); }
+  GO(128);
 #undef GO
 }

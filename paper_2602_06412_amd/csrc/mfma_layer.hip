@@ -54,15 +54,17 @@ int sl_mfma_pack_all(sl_ctx* ctx, hipStream_t s, void* packed) {
   return SL_OK;
 }
 
-// fp32 scratch needed by a launch bounded by mu rows: the widest [splits][mu][n] partial block
-size_t sl_mfma_f32_elems(const sl_config* c, int mu) {
+// fp32 scratch needed by any launch bounded by at most `rows` rows: the widest
+// [splits][mu][n] partial block over the four projections
+size_t sl_mfma_f32_elems(const sl_config* c, int rows) {
   const int d = c->d_model, hd = c->n_heads * c->d_head, dff = c->d_ff;
   const int shapes[4][2] = {{3 * hd, d}, {d, hd}, {2 * dff, d}, {d, dff}};
   size_t best = 0;
-  for (auto& sh : shapes) {
-    const size_t e = (size_t)slk_gemm_splits(mu, sh[0], sh[1]) * mu * sh[0];
-    if (e > best) best = e;
-  }
+  for (int mu = 1; mu <= rows; ++mu)
+    for (auto& sh : shapes) {
+      const size_t e = (size_t)slk_gemm_splits(mu, sh[0], sh[1]) * mu * sh[0];
+      if (e > best) best = e;
+    }
   return best;
 }
 
@@ -74,27 +76,27 @@ static inline char* kv_k(const sl_ctx* ctx, int l) {
 static inline char* kv_v(const sl_ctx* ctx, int l) { return kv_k(ctx, ctx->cfg.n_layers) + (size_t)l * ctx->kv_layer_elems * 2; }
 
 int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, void* o, void* a, float* f32,
-                  const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain) {
+                  float* attn_scratch, const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain) {
   const sl_config& c = ctx->cfg;
   const int d = c.d_model, H = c.n_heads, dh = c.d_head, hd = H * dh, dff = c.d_ff;
   const sl_packed_layer& P = ctx->packed[l];
   const sl_layer_weights& L = ctx->layers[l];
   // Q | K | V projections in one launch
   int S = slk_gemm_splits(mu, 3 * hd, d);
-  SL_TRY(slk_gemm_mfma(s, h, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
-  SL_TRY(slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
+  SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
+  SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
                            ctx->kv, q, kv_k(ctx, l), kv_v(ctx, l)));
-  SL_TRY(slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
-                            ctx->n_pad, o));
+  SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
+                            ctx->n_pad, o, attn_scratch));
   S = slk_gemm_splits(mu, d, hd);
-  SL_TRY(slk_gemm_mfma(s, o, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
-  SL_TRY(slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h));
+  SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
+  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h));
   S = slk_gemm_splits(mu, 2 * dff, d);
-  SL_TRY(slk_gemm_mfma(s, h, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
-  SL_TRY(slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a));
+  SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
+  SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a));
   S = slk_gemm_splits(mu, d, dff);
-  SL_TRY(slk_gemm_mfma(s, a, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
-  SL_TRY(slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h));
+  SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
+  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h));
   return SL_OK;
 }
 

@@ -53,10 +53,11 @@ template <> struct chunk_io<float> {
   }
 };
 
-constexpr int kScoreThreads = 256;
 
-template <typename T, bool FIRST>
-__global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restrict__ cur, int cur_packed,
+// NT threads per row: 256 when there are rows enough to fill the chip, 1024 for thin launches
+// (a row is ~0.5 MB of loads; a single small workgroup would be latency-bound on it).
+template <typename T, bool FIRST, int NT>
+__global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, int cur_packed,
                                                                const T* __restrict__ prev, int V,
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ m_dev, int m_upper,
@@ -71,10 +72,7 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
   const T* b_row = prev + (size_t)g * V;
   ScoreAcc acc{-INFINITY, 0.f, 0.f, 0.f, 0.f, -INFINITY, 0x7fffffff};
   const int n_chunks = V / E;
-  for (int c = threadIdx.x; c < n_chunks; c += kScoreThreads) {
-    float a[E], b[E];
-    chunk_io<T>::load(a_row + (size_t)c * E, a);
-    if (!FIRST) chunk_io<T>::load(b_row + (size_t)c * E, b);
+  auto consume = [&](const float (&a)[E], const float (&b)[E], int c) {
     float cm = a[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) cm = fmaxf(cm, a[j]);
@@ -105,6 +103,25 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
     const float bp = t - acc.S;
     acc.Sc += (acc.S - (t - bp)) + (cs - bp);
     acc.S = t;
+  };
+  // two chunks per trip so that four 16-byte loads are in flight per thread
+  int c = threadIdx.x;
+  for (; c + NT < n_chunks; c += 2 * NT) {
+    float a0[E], b0[E], a1[E], b1[E];
+    chunk_io<T>::load(a_row + (size_t)c * E, a0);
+    chunk_io<T>::load(a_row + (size_t)(c + NT) * E, a1);
+    if (!FIRST) {
+      chunk_io<T>::load(b_row + (size_t)c * E, b0);
+      chunk_io<T>::load(b_row + (size_t)(c + NT) * E, b1);
+    }
+    consume(a0, b0, c);
+    consume(a1, b1, c + NT);
+  }
+  if (c < n_chunks) {
+    float a0[E], b0[E];
+    chunk_io<T>::load(a_row + (size_t)c * E, a0);
+    if (!FIRST) chunk_io<T>::load(b_row + (size_t)c * E, b0);
+    consume(a0, b0, c);
   }
   // wave reduction, then across the block's waves through LDS
 #pragma unroll
@@ -114,13 +131,13 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
     y.W = __shfl_xor(acc.W, o, 64); y.bestv = __shfl_xor(acc.bestv, o, 64); y.besti = __shfl_xor(acc.besti, o, 64);
     acc_merge(acc, y);
   }
-  __shared__ ScoreAcc sh[kScoreThreads / 64];
+  __shared__ ScoreAcc sh[NT / 64];
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) {
     ScoreAcc t = sh[0];
 #pragma unroll
-    for (int w = 1; w < kScoreThreads / 64; ++w) acc_merge(t, sh[w]);
+    for (int w = 1; w < NT / 64; ++w) acc_merge(t, sh[w]);
     t.S += t.Sc;
     conf[r] = __expf(t.bestv - t.m) / t.S;
     argmax[r] = t.besti;
@@ -128,20 +145,30 @@ __global__ __launch_bounds__(kScoreThreads) void score_kernel(const T* __restric
   }
 }
 
+template <typename T, int NT>
+static int launch_score_nt(hipStream_t s, const void* cur, int cur_packed, const void* prev, int V,
+                           const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl,
+                           float* conf, int32_t* argmax) {
+  dim3 grid(m_upper), block(NT);
+  if (first_step)
+    hipLaunchKernelGGL((score_kernel<T, true, NT>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)cur, V,
+                       active_idx, m_dev, m_upper, kl, conf, argmax);
+  else
+    hipLaunchKernelGGL((score_kernel<T, false, NT>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)prev, V,
+                       active_idx, m_dev, m_upper, kl, conf, argmax);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
 template <typename T>
 static int launch_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int V,
                         const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl,
                         float* conf, int32_t* argmax) {
   if (m_upper <= 0) return SL_OK;
-  dim3 grid(m_upper), block(kScoreThreads);
-  if (first_step)
-    hipLaunchKernelGGL((score_kernel<T, true>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)cur, V,
-                       active_idx, m_dev, m_upper, kl, conf, argmax);
-  else
-    hipLaunchKernelGGL((score_kernel<T, false>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)prev, V,
-                       active_idx, m_dev, m_upper, kl, conf, argmax);
-  SL_LAUNCH_CHECK();
-  return SL_OK;
+  if (m_upper <= 512 && V >= 16384)
+    return launch_score_nt<T, 1024>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf,
+                                    argmax);
+  return launch_score_nt<T, 256>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
 }
 
 int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int dtype, int V,

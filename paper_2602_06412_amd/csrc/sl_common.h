@@ -98,8 +98,15 @@ struct sl_packed_layer {            // device pointers into the caller's packed 
   const void *wqkv, *wo, *wgu, *wdown;
 };
 
+struct sl_prof {                    // event pairs recorded while profiling is on
+  hipEvent_t* ev;                   // 2 * cap events
+  int* slot;
+  int cap, n;
+};
+
 struct sl_ctx {
   sl_config cfg;
+  sl_prof* prof;
   bool weights_bound, use_mfma;
   sl_weights plain;                 // copy of the caller's struct (layers -> own host array)
   sl_layer_weights* layers;         // host array, n_layers
@@ -110,6 +117,20 @@ struct sl_ctx {
   // posterior store
   void* post; size_t post_buf_elems;
 };
+
+// Run one launcher call, bracketed by an event pair when profiling is on.
+#define SL_RUN(ctx, stream, slot_id, call)                                                   \
+  do {                                                                                       \
+    sl_prof* pf_ = (ctx)->prof;                                                              \
+    const bool on_ = pf_ && pf_->n < pf_->cap;                                               \
+    if (on_) SL_HIP(hipEventRecord(pf_->ev[2 * pf_->n], (stream)));                          \
+    const int rc_ = (call);                                                                  \
+    if (rc_ != SL_OK) return rc_;                                                            \
+    if (on_) {                                                                               \
+      SL_HIP(hipEventRecord(pf_->ev[2 * pf_->n + 1], (stream)));                             \
+      pf_->slot[pf_->n++] = (slot_id);                                                       \
+    }                                                                                        \
+  } while (0)
 
 // ---- kernel launchers (one translation unit each) ------------------------------------------
 // control_kernels.hip
@@ -156,13 +177,14 @@ int slk_gemm_mfma(hipStream_t s, const void* A, const void* Wp, const int32_t* m
                   float* Cf, void* Cb, const int32_t* row_map, size_t ldc);
 // attention_mfma.hip
 int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void* vc, const int32_t* active_idx,
-                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o);
+                       const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o, float* scratch);
+size_t slk_attention_scratch_elems(int m_upper, int B, int H, int n_pad);
 // mfma path (mfma_layer.hip)
 size_t sl_mfma_f32_elems(const sl_config* cfg, int mu);
 bool sl_mfma_supported(const sl_config* cfg);
 size_t sl_mfma_packed_bytes(const sl_config* cfg);
 int sl_mfma_pack_all(sl_ctx* ctx, hipStream_t s, void* packed);
 int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int layer, void* x, void* h, void* q, void* o, void* a, float* f32,
-                  const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain);
+                  float* attn_scratch, const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain);
 int sl_mfma_lm_head(sl_ctx* ctx, hipStream_t s, const void* h, const int32_t* active_idx, const int32_t* m_dev, int mu,
                     void* logits_buf);

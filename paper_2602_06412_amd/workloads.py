@@ -58,10 +58,12 @@ def _normal(gen, shape, std, dtype, device):
     return t.to(dtype)
 
 
-def make_weights(shape, seed, device="cpu", std=0.02, norm_gain_jitter=0.0):
+def make_weights(shape, seed, device="cpu", std=0.02, norm_gain_jitter=0.0, emb_std=None):
     """Every matrix i.i.d. N(0, std^2) drawn in fp32 from the seed, then rounded
     to the storage type; norm gains are 1 (optionally 1 + jitter*N(0,1), which
-    tests use so a dropped gain cannot hide).  Layout: [out_features, in_features]."""
+    tests use so a dropped gain cannot hide).  emb_std overrides the embedding's std
+    (the one-layer microbench feeds block inputs x ~ N(0,1)).
+    Layout: [out_features, in_features]."""
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
     dt = torch_dtype(shape.storage)
@@ -74,7 +76,7 @@ def make_weights(shape, seed, device="cpu", std=0.02, norm_gain_jitter=0.0):
             g = g + norm_gain_jitter * torch.empty(d, device=device).normal_(generator=gen)
         return g.to(dt)
 
-    w = {"emb": _normal(gen, (V, d), std, dt, device), "layers": []}
+    w = {"emb": _normal(gen, (V, d), std if emb_std is None else emb_std, dt, device), "layers": []}
     for _ in range(shape.n_layers):
         w["layers"].append({
             "attn_norm": gain(),

@@ -1,0 +1,71 @@
+"""GPU parity at the benchmark's full size and launch configuration (config 2: one
+LLaDA-8B-shaped bf16 layer + LM head, N = 1024 cached slots).  The oracle runs the layer for
+the active rows (it must: their K/V feed the attention) and the LM head on a sample of rows."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import model, posterior
+from paper_2602_06412_amd import binding as B
+from paper_2602_06412_amd import workloads as wl
+from tests.gpu_util import DEV, check_logits, dev, oracle_cfg
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c2_full_size_sampled_rows():
+    shape, N = wl.C2, 1024
+    w = wl.make_weights(shape, seed=0, device="cuda", emb_std=1.0)
+    sess = B.Session(shape, w, 1, N)
+    try:
+        cfg = oracle_cfg(shape)
+        tokens_np = wl.prompt_uniform(1, N, shape.vocab, shape.mask_id)
+        f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
+        w64 = {"emb": f64(w["emb"][torch.as_tensor(tokens_np, device=DEV)]), "final_norm": f64(w["final_norm"]),
+               "lm_head": None, "layers": [{k: f64(v) for k, v in w["layers"][0].items()}]}
+        lm64 = f64(w["lm_head"])
+        eps = dev(np.array([1e-3], dtype=np.float32))
+        zero = torch.zeros(N, dtype=torch.uint8, device=DEV)
+        Kc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
+        Vc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
+        rng = np.random.default_rng(0)
+        prev_rows = {}
+        active = np.arange(N)
+        for t, M in ((1, 1024), (2, 256), (3, 16)):
+            # the active set only ever shrinks (locks are permanent): nested subsets
+            active = active if M == len(active) else active[wl.active_positions(50 + M, len(active), M)]
+            lock = dev(wl.lock_mask_from_active(N, active))
+            tokens = dev(tokens_np, torch.int32)
+            print(f"C2 full-size step t={t} M={M}", flush=True)
+            sess.step(tokens, zero.clone(), lock, eps, t, 0, N, 0, m_upper=M, new_lock=torch.zeros_like(lock))
+            torch.cuda.synchronize()
+            assert int(sess.cu_active[-1].item()) == M
+            assert np.array_equal(sess.active_idx[:M].cpu().numpy(), active)
+            # oracle: block output of the active rows (tokens index w64['emb'] by position)
+            x = w64["emb"][active]
+            x = model.layer_active(cfg, w64["layers"][0], x, active, Kc[0], Vc[0])
+            sample = np.sort(rng.choice(M, size=min(M, 6), replace=False))
+            hf = cfg.rnd(model.rmsnorm(x[sample], w64["final_norm"], cfg.rms_eps))
+            z = cfg.rnd(hf @ lm64.T)
+            rows = torch.as_tensor(active[sample], device=DEV, dtype=torch.long)
+            z_gpu = sess.logits_view(t)[rows].double().cpu().numpy()
+            check_logits(z_gpu, z, "bf16", f"t={t} M={M}")
+            # scoring in situ on the GPU's own logits for the sampled rows
+            lp = posterior.log_softmax(z_gpu)
+            conf = sess.conf[:M].cpu().numpy()[sample]
+            am = sess.argmax[:M].cpu().numpy()[sample]
+            kl = sess.kl[:M].cpu().numpy().astype(np.float64)[sample]
+            assert np.array_equal(am, posterior.argmax_lowest(z_gpu))
+            assert np.allclose(conf, posterior.max_prob(lp), rtol=2e-6)
+            if t > 1:
+                prev = sess.logits_view(t - 1)[rows].double().cpu().numpy()
+                want = posterior.kl_rows(lp, posterior.log_softmax(prev))
+                assert np.all(np.abs(kl - want) <= 1e-4 * want + 2e-7)
+            # K/V cache rows of this step (sampled) against the oracle's
+            kg, vg = sess.kv_read(0)
+            kg, vg = kg[0, rows].double().cpu().numpy(), vg[0, rows].double().cpu().numpy()
+            for got, wantkv in ((kg, Kc[0][active[sample]]), (vg, Vc[0][active[sample]])):
+                e = np.abs(got - wantkv)
+                assert np.all(e <= np.maximum(2e-2, 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wantkv), 1e-30))) - 7)))
+    finally:
+        sess.close()

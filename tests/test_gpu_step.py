@@ -19,7 +19,7 @@ import torch
 from oracle import control, posterior
 from paper_2602_06412_amd import binding as B
 from paper_2602_06412_amd import workloads as wl
-from tests.gpu_util import DEV, dev, logits_tol, oracle_cfg, weights_to_device
+from tests.gpu_util import DEV, check_logits, dev, oracle_cfg, weights_to_device
 from tests.trajectory import near_tie_in_topk, run_oracle, unmask_is_valid
 
 pytestmark = pytest.mark.gpu
@@ -45,9 +45,7 @@ def _check_traj(shape, steps, sess, eps, strict_decisions):
         assert np.array_equal(idx, st.active_idx)
         # logits
         z_gpu = sess.logits_view(st.t)[torch.as_tensor(idx, device=DEV, dtype=torch.long)].to(torch.float64).cpu().numpy()
-        err = np.abs(z_gpu - st.logits)
-        tol = logits_tol(st.logits, shape.storage)
-        assert np.all(err <= tol), f"t={st.t}: max logit err {err.max():.4g} at |z|={np.abs(st.logits).flat[err.argmax()]:.3g}"
+        check_logits(z_gpu, st.logits, shape.storage, f"t={st.t}")
         # scoring, in situ on the GPU's logits
         kl = sess.kl[:M].cpu().numpy().astype(np.float64)
         conf = sess.conf[:M].cpu().numpy()
