@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", type=str, default="1024,512,256,64,16")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -121,6 +123,13 @@ def main():
             "score_hbm_frac": round(score_bytes / (per["score"] * 1e-3) / HBM_PEAK, 4),
             "kernels_ms": {k: round(v, 4) for k, v in per.items()},
         })
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     head = results[0]
     M0 = head["M"]

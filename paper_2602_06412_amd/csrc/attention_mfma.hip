@@ -46,7 +46,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   __shared__ int cu[kMaxBatch + 2];
   const int M = min(*m_dev, m_upper);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int hh = blockIdx.y;
+  // blockIdx.x = head: consecutive workgroup ids go to different XCDs, so the query tiles of
+  // one head (same K/V) land on one XCD and share its L2
+  const int hh = blockIdx.x;
   // per-sequence row ranges: cu[b] = first packed row whose flat id >= b*N
   if (tid <= B) {
     int lo = 0, hi = M;
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
     cu[tid] = lo;
   }
   __syncthreads();
-  int b = 0, tile = blockIdx.x, row0 = -1, row_end = 0;
+  int b = 0, tile = blockIdx.y, row0 = -1, row_end = 0;
   for (; b < B; ++b) {
     const int cnt = cu[b + 1] - cu[b];
     const int nt = (cnt + QT - 1) / QT;
@@ -255,7 +257,7 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   if (B > kMaxBatch || n_pad % KT) return SL_EINVAL;
   int tps;
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
-  dim3 grid(sl_cdiv(m_upper, QT) + B - 1, H, Z), block(256);
+  dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
   if (Z == 1) {
     hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc,
                        (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, 0, nullptr, nullptr);
