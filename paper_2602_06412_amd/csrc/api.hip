@@ -225,11 +225,12 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows, int batch, int n
   Workspace w;
   size_t off = 0;
   auto take = [&](size_t n) { char* p = (char*)base + off; off += sl_align_up(n, 256); return p; };
+  const size_t rows32 = sl_align_up((size_t)rows, 32);     // tiled activation buffers hold whole 32-row blocks
   w.x = take((size_t)rows * c.d_model * ts);
-  w.h = take((size_t)rows * c.d_model * ts);
+  w.h = take(rows32 * c.d_model * ts);
   w.q = take((size_t)rows * hd * ts);
-  w.o = take((size_t)rows * hd * ts);
-  w.a = take((size_t)rows * c.d_ff * ts);
+  w.o = take(rows32 * hd * ts);
+  w.a = take(rows32 * c.d_ff * ts);
   size_t f32_elems = (size_t)rows * f32_cols;
   if (ctx->use_mfma) {
     const size_t e = sl_mfma_f32_elems(&c, rows);
@@ -279,12 +280,12 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
                                  ctx->n_seq, ctx->n_pad, ws.o));
     SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
-    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h, 0));
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
-    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a));
+    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a, 0));
     SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
-    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h, 0));
   }
   return SL_OK;
 }
@@ -310,7 +311,7 @@ extern "C" int sl_forward_layers(sl_ctx* ctx, void* stream, const void* x_in, vo
   hipStream_t s = (hipStream_t)stream;
   const sl_config& c = ctx->cfg;
   SL_TRY(slk_copy_rows(s, c.dtype, x_in, ws.x, m_dev, m_upper, c.d_model));
-  SL_TRY(slk_rmsnorm(s, c.dtype, ws.x, m_dev, m_upper, c.d_model, ctx->layers[layer_lo].attn_norm, c.rms_eps, ws.h));
+  SL_TRY(slk_rmsnorm(s, c.dtype, ws.x, m_dev, m_upper, c.d_model, ctx->layers[layer_lo].attn_norm, c.rms_eps, ws.h, ctx->use_mfma));
   SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, layer_lo, layer_hi));
   return slk_copy_rows(s, c.dtype, ws.x, x_out, m_dev, m_upper, c.d_model);
 }
@@ -391,7 +392,7 @@ extern "C" int sl_linear_forward(void* stream, const void* x, const void* packed
   if ((uintptr_t)x % 16 || (uintptr_t)packed % 16) return SL_EINVAL;
   if (splits == 0) splits = y_f32 ? slk_gemm_splits(m_upper, n, k) : 1;
   if (splits < 1 || k % (64 * splits) || (y_bf16 && splits != 1)) return SL_EINVAL;
-  return slk_gemm_mfma((hipStream_t)stream, x, packed, m_dev, m_upper, n, k, splits, y_f32, y_bf16, row_map, n);
+  return slk_gemm_mfma((hipStream_t)stream, x, 0, packed, m_dev, m_upper, n, k, splits, y_f32, y_bf16, row_map, n);
 }
 
 // ---- the step --------------------------------------------------------------------------------------
@@ -417,7 +418,7 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, lock, B, N, active_idx, cu_active));
   // block input of the active rows + first LN
   SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model,
-                           ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h));
+                           ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
   SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, 0, c.n_layers));
   // logits of the active rows, written to their rows of this step's posterior buffer
   void *cur = nullptr, *prev = nullptr;

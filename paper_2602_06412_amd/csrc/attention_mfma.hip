@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   }
   const float inv = 1.0f / l_tot;
   if (my_row < row_end) {
-    bf16_t* op = o + ((size_t)my_row * H + hh) * DH + 4 * (lane >> 5);
+    // o is written in the fragment-tiled activation layout the Out-projection GEMM reads
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
         bf16x4 w;
 #pragma unroll
         for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[mb][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + mb * 32 + 8 * g) = w;
+        *reinterpret_cast<bf16x4*>(o + afrag_index(my_row, hh * DH + mb * 32 + 8 * g + 4 * (lane >> 5), H * DH)) = w;
       }
   }
 }
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __res
     num = fmaf(w, part_o[slot * DH + dd], num);
     den = fmaf(w, part_ml[slot * 2 + 1], den);
   }
-  o[((size_t)row * H + hh) * DH + dd] = (bf16_t)(num / den);
+  o[afrag_index(row, hh * DH + dd, H * DH)] = (bf16_t)(num / den);
 }
 
 // Key-split plan for a launch bounded by m_upper rows: split while fewer than ~2 workgroups

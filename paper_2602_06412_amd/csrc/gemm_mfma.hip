@@ -52,7 +52,7 @@ int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_
 // OUT = 1: bf16 rows Cb[row_map ? row_map[row] : row][n] (no split-k)
 template <int BM, int WNB, int OUT, int DBG = 0>
 __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
-    const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
+    const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
     const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
   constexpr int MB = BM / 32;          // 32-row blocks per tile
@@ -86,15 +86,25 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
   }
   // Activation fragments go global -> LDS directly (no register staging): the hardware puts
   // lane L's 16 bytes at (wave-uniform LDS base) + 16*L, which is the fragment order.
-  const bf16_t* Ab = A + kbeg;
+  // A is row-major [m_upper, k] (a 32 x 16 fragment is gathered from 32 rows) or already
+  // fragment-tiled (one contiguous 1 KiB block per fragment).
+  const bf16_t* Ab = a_tiled ? A : A + kbeg;
+  const int a_kt_stride = a_tiled ? 4 * 512 : BK;         // elements per k-tile
   uint32_t a_off[NF];
   int a_frag[NF];                                         // fragment index (mb*4 + kb) inside a stage
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const int f = wave + 4 * i, mb = f % MB, kb = f / MB;
-    int row = m0 + mb * 32 + (lane & 31);
-    row = row < m_upper ? row : m_upper - 1;              // row tail: stay inside the buffer
-    a_off[i] = (uint32_t)row * (uint32_t)k + (uint32_t)(kb * 16 + (lane >> 5) * 8);
+    if (a_tiled) {
+      int mbg = m0 / 32 + mb;
+      const int mb_last = (m_upper + 31) / 32 - 1;
+      mbg = mbg < mb_last ? mbg : mb_last;                // row tail: stay inside the (32-row padded) buffer
+      a_off[i] = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16 + kb)) * 64u + (uint32_t)lane) * 8u;
+    } else {
+      int row = m0 + mb * 32 + (lane & 31);
+      row = row < m_upper ? row : m_upper - 1;            // row tail: stay inside the buffer
+      a_off[i] = (uint32_t)row * (uint32_t)k + (uint32_t)(kb * 16 + (lane >> 5) * 8);
+    }
     a_frag[i] = mb * 4 + kb;
   }
 
@@ -109,7 +119,7 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
   Frag b0[WNB][4], b1[WNB][4];          // weight fragments of the even / odd k-tile (ping-pong, no copies)
 
   auto load_a = [&](int kt, Frag* stage) {
-    const bf16_t* base = Ab + kt * BK;
+    const bf16_t* base = Ab + (size_t)kt * a_kt_stride;
 #pragma unroll
     for (int i = 0; i < NF; ++i)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + a_off[i]),
@@ -204,24 +214,26 @@ static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 // small against the weight stream (thin-M regime: k >= 16*S*mu) or against the MFMA time
 // (thick-M regime: S <= k/2048), and each split keeps an even number (>= 4) of k-tiles.
 int slk_gemm_splits(int mu, int n, int k) {
-  const int bm = pick_bm(mu);
+  const bool thick = mu > 128;                       // 256 x 256 tiles, one workgroup per CU
+  const int bm = thick ? 256 : pick_bm(mu);
   const int tiles = sl_cdiv(mu, bm) * sl_cdiv(n, 256);
+  const int target = thick ? 256 : 512;
   int s = 1;
-  while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
+  while (s < 8 && tiles * s < target && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
          ((size_t)(s * 2) * 16 * mu <= (size_t)k || s * 2 <= k / 2048))
     s *= 2;
   return s;
 }
 
 template <int BM, int WNB, int OUT, int DBG = 0>
-static int launch_gemm(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                        int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   constexpr int BN = 128 * WNB;
   const int tiles_m = sl_cdiv(mu, BM), tiles_n = sl_cdiv(n, BN);
   const size_t sh = 0;
   auto kern = gemm_mfma_kernel<BM, WNB, OUT, DBG>;
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(256);
-  hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
+  hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
                      (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
   SL_LAUNCH_CHECK();
   return SL_OK;
@@ -229,22 +241,23 @@ static int launch_gemm(hipStream_t s, const void* A, const void* Wp, const int32
 
 // C = A . Wp^T for a launch bounded by mu rows.  Cf != null: fp32 partials [splits][mu][n];
 // else bf16 rows into Cb through row_map (splits must be 1).
-int slk_gemm_mfma(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k, int splits,
-                  float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                  int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   if (mu <= 0) return SL_OK;
   if (splits < 1 || n % 32 || k % (2 * BK * splits)) return SL_EINVAL;     // even number of k-tiles per split
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;   // 32-bit offsets
   if (!Cf && splits != 1) return SL_EINVAL;
 #define GO(BM)                                                                                             \
-  return Cf ? launch_gemm<BM, 2, 0>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
-            : launch_gemm<BM, 2, 1>(s, A, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
+  return Cf ? launch_gemm<BM, 2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
+            : launch_gemm<BM, 2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
   static const int dbg = getenv("SL_GEMM_DBG") ? atoi(getenv("SL_GEMM_DBG")) : 0;
-  if (dbg == 1 && Cf) return launch_gemm<128, 2, 0, 1>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 2 && Cf) return launch_gemm<128, 2, 0, 2>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 5 && Cf) return launch_gemm<128, 2, 0, 5>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 6 && Cf) return launch_gemm<128, 2, 0, 6>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 3 && Cf) return launch_gemm<256, 2, 0, 1>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 4 && Cf) return launch_gemm<256, 2, 0, 2>(s, A, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 1 && Cf) return launch_gemm<128, 2, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 2 && Cf) return launch_gemm<128, 2, 0, 2>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 5 && Cf) return launch_gemm<128, 2, 0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 6 && Cf) return launch_gemm<128, 2, 0, 6>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 3 && Cf) return launch_gemm<256, 2, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 4 && Cf) return launch_gemm<256, 2, 0, 2>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 7) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
   static const int force_bm = getenv("SL_GEMM_BM") ? atoi(getenv("SL_GEMM_BM")) : 0;   // tuning aid
   if (force_bm == 32) { GO(32); }
   if (force_bm == 64) { GO(64); }

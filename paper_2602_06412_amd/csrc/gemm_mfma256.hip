@@ -1,0 +1,215 @@
+// Thick-M variant of the projection GEMM: one 256 x 256 output tile per CU, fed through a
+// deep ring of LDS stages.
+//
+// Why a second kernel.  Measured on the 128-row-tile kernel: with loads switched off the
+// MFMA loop runs at ~75% of peak, with them at ~45%, although neither HBM nor L2 bandwidth is
+// near its limit.  Every weight byte is touched for the first time exactly once (an L2 miss
+// served from HBM, ~2 us under load), all row tiles sharing the slab wait on that same miss,
+// and with a prefetch distance of one k-tile (~0.4-0.9 us of MFMA work) the latency is exposed
+// on every tile.  This kernel therefore keeps NS-1 k-tiles in flight:
+//  * eight waves (two per SIMD) own 128 x 64 sub-tiles of a 256 x 256 tile;
+//  * BOTH operands are staged in LDS by direct-to-LDS loads (no registers are tied up by
+//    loads in flight; each byte crosses the vector L1 once per CU: 32 B/clk at full MFMA
+//    rate, half of what the 128-row kernel needs);
+//  * k-tiles are 32 deep (32 KiB per stage), five stages fill the 160 KiB LDS, so four tiles
+//    (128 KiB per CU, 32 MiB chip-wide) are in flight while one is multiplied;
+//  * one barrier per k-tile, placed between the two MFMA k-steps, so the LDS reads on either
+//    side of it are covered by MFMAs; fragments are read one k-step ahead.
+// Operand fragments land in LDS in MFMA operand order (activation rows gathered 32 x 16 per
+// instruction, pre-tiled weights copied linearly), so LDS reads are conflict-free.
+#include "sl_common.h"
+#include <stdlib.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef bf16x8 Frag;
+
+constexpr int BK2 = 32;                   // k per stage: two MFMA k-steps
+constexpr int TILE = 256;
+constexpr int STAGE = 32 * 64;            // Frag elements per stage: 16 A + 16 B fragments (32 KiB)
+
+template <int OUT, int NS, int DBG = 0>
+__global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
+    const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
+    const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
+  extern __shared__ Frag lds[];           // [NS stages][A: 8 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
+
+  const int M = min(*m_dev, m_upper);
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
+  if (tn >= tiles_n) return;
+  const int m0 = tm * TILE;
+  if (m0 >= M) return;
+  const int n0 = tn * TILE;
+  const int kbeg = blockIdx.y * k_per_split;
+  const int ktiles = k_per_split / BK2;
+  const int last = ktiles - 1;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 2, wn = wave & 3;          // this wave's 128 x 64 sub-tile
+  const int K16 = k / 16, NB32 = n / 32;
+
+  // global -> LDS: 32 fragments per k-tile, 4 per wave: wave w moves the two A fragments of
+  // row block w and the two B fragments of column block w.
+  // A is row-major [m_upper, k] (a 32 x 16 fragment is gathered from 32 rows) or already
+  // fragment-tiled (one contiguous 1 KiB block per fragment, rows padded to 32).
+  const bf16_t* Ab = a_tiled ? A : A + kbeg;
+  const int a_kt_stride = a_tiled ? 2 * 512 : BK2, a_kb_stride = a_tiled ? 512 : 16;   // elements
+  uint32_t a_off;
+  if (a_tiled) {
+    int mbg = m0 / 32 + wave;
+    const int mb_last = (m_upper + 31) / 32 - 1;
+    mbg = mbg < mb_last ? mbg : mb_last;              // row tail: stay inside the buffer
+    a_off = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u;
+  } else {
+    int row = m0 + wave * 32 + (lane & 31);
+    row = row < m_upper ? row : m_upper - 1;          // row tail: stay inside the buffer
+    a_off = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8);
+  }
+  const Frag* Wf = reinterpret_cast<const Frag*>(Wp) + (size_t)(kbeg / 16) * 64;
+  uint32_t b_off;
+  {
+    int nb = n0 / 32 + wave;
+    nb = nb < NB32 ? nb : NB32 - 1;                   // column tail: valid but unused data
+    b_off = (uint32_t)nb * (uint32_t)K16 * 64u + (uint32_t)lane;
+  }
+  // Direct-to-LDS loads are issued as inline assembly on purpose: when the compiler sees an
+  // LDS-DMA instruction it makes every later LDS read wait for ALL of them (vmcnt(0)), which
+  // would collapse the ring to a depth of one.  Here the code itself guarantees, with explicit
+  // vmcnt waits and the barrier, that a stage is read only after its loads have landed.
+  // The hardware writes lane L's 16 bytes at M0 + 16*L.
+  auto dma16 = [&](const void* gptr, Frag* lptr) {
+    const uint32_t laddr =
+        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)lptr);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(laddr)
+                 : "memory", "m0");
+  };
+  auto issue = [&](int kt, int st) {
+    if (DBG == 1) return;
+    kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
+    Frag* sa = lds + st * STAGE + (wave * 2) * 64;
+    Frag* sb = lds + st * STAGE + 16 * 64 + (wave * 2) * 64;
+    const bf16_t* ap = Ab + (size_t)kt * a_kt_stride + a_off;
+    const Frag* bp = Wf + (size_t)kt * 128 + b_off;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      if (DBG == 5) dma16(Ab + (size_t)(kt * 4 + kb) * 512 + lane * 8, sa + kb * 64);   // contiguous 1 KiB (wrong data)
+      else if (DBG != 3) dma16(ap + kb * a_kb_stride, sa + kb * 64);
+      if (DBG != 4) dma16(bp + kb * 64, sb + kb * 64);
+    }
+  };
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  Frag a0[4], b0[2], a1[4], b1[2];        // operand fragments of k-step 0 / 1 of the current tile
+  auto read_frags = [&](int st, int kb, Frag (&af)[4], Frag (&bf)[2]) {
+    const Frag* sa = lds + st * STAGE + (wm * 8 + kb) * 64 + lane;          // mb = 4*wm + i
+    const Frag* sb = lds + st * STAGE + 16 * 64 + (wn * 4 + kb) * 64 + lane; // nb = 2*wn + i
+#pragma unroll
+    for (int i = 0; i < 4; ++i) af[i] = sa[(i * 2) * 64];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) bf[i] = sb[(i * 2) * 64];
+  };
+  auto mma = [&](const Frag (&af)[4], const Frag (&bf)[2]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int jn = 0; jn < 2; ++jn)
+        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[jn], acc[i][jn], 0, 0, 0);
+  };
+  // "s_waitcnt vmcnt(4*(NS-2))": all but this wave's newest NS-2 tiles have landed (loads
+  // complete in order, 4 per tile per wave)
+#define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (NS - 2)) : "memory")
+
+  // prologue: tiles 0 .. NS-2 in flight, tile 0 landed and published, its first fragments read
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) issue(t, t);
+  SL_WAIT_RING();
+  __syncthreads();
+  read_frags(0, 0, a0, b0);
+
+  // One k-tile per trip: refill the stage every wave finished reading before the previous
+  // barrier, multiply k-step 0 while reading k-step 1, wait for tile kt+1 and publish it,
+  // multiply k-step 1 while reading the first fragments of tile kt+1.
+  int st = 0;                                         // stage of tile kt
+  for (int kt = 0; kt < ktiles; ++kt) {
+    const int st_prev = st == 0 ? NS - 1 : st - 1;
+    const int st_next = st == NS - 1 ? 0 : st + 1;
+    issue(kt + NS - 1, st_prev);
+    read_frags(st, 1, a1, b1);
+    mma(a0, b0);
+    __builtin_amdgcn_sched_barrier(0);
+    SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
+    __syncthreads();                                  // ... and so has everyone else's
+    read_frags(st_next, 0, a0, b0);
+    mma(a1, b1);
+    __builtin_amdgcn_sched_barrier(0);
+    st = st_next;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // drain the (unused) tail re-fetches
+#undef SL_WAIT_RING
+
+  const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = m0 + wm * 128 + mb * 32 + 8 * (v / 4) + row_in + (v % 4);
+      if (row >= M) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int col = n0 + (wn * 2 + i) * 32 + col_in;
+        if (col >= n) continue;
+        if (OUT == 0) {
+          Cf[((size_t)blockIdx.y * m_upper + row) * ldc + col] = acc[mb][i][v];
+        } else {
+          const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
+          Cb[orow * ldc + col] = (bf16_t)acc[mb][i][v];
+        }
+      }
+    }
+  }
+}
+
+template <int OUT, int NS, int DBG = 0>
+static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                     int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
+  const size_t sh = (size_t)NS * STAGE * 16;
+  auto kern = gemm_mfma256_kernel<OUT, NS, DBG>;
+  SL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+  dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
+  hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
+                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                     int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  if (mu <= 0) return SL_OK;
+  if (splits < 1 || n % 32 || k % (BK2 * splits) || k / (BK2 * splits) < 8) return SL_EINVAL;
+  if (!Cf && splits != 1) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  static const int ns = getenv("SL_GEMM256_NS") ? atoi(getenv("SL_GEMM256_NS")) : 5;      // tuning aid
+  static const int dbg = getenv("SL_GEMM256_DBG") ? atoi(getenv("SL_GEMM256_DBG")) : 0;
+  if (dbg == 1 && Cf) return launch256<0, 5, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 3 && Cf) return launch256<0, 5, 3>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 4 && Cf) return launch256<0, 5, 4>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 5 && Cf) return launch256<0, 5, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+#define GO256(NS)                                                                                  \
+  return Cf ? launch256<0, NS>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)         \
+            : launch256<1, NS>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
+  if (ns == 3) { GO256(3); }
+  if (ns == 4) { GO256(4); }
+  GO256(5);
+#undef GO256
+}

@@ -83,26 +83,26 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   const sl_layer_weights& L = ctx->layers[l];
   // Q | K | V projections in one launch
   int S = slk_gemm_splits(mu, 3 * hd, d);
-  SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
+  SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, 1, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
   SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
                            ctx->kv, q, kv_k(ctx, l), kv_v(ctx, l)));
   SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
                             ctx->n_pad, o, attn_scratch));
   S = slk_gemm_splits(mu, d, hd);
-  SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
-  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h));
+  SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, 1, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
+  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
   S = slk_gemm_splits(mu, 2 * dff, d);
-  SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
-  SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a));
+  SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
+  SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1));
   S = slk_gemm_splits(mu, d, dff);
-  SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
-  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h));
+  SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, 1, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
+  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h, 1));
   return SL_OK;
 }
 
 int sl_mfma_lm_head(sl_ctx* ctx, hipStream_t s, const void* h, const int32_t* active_idx, const int32_t* m_dev, int mu,
                     void* logits_buf) {
   const sl_config& c = ctx->cfg;
-  return slk_gemm_mfma(s, h, ctx->packed_lm_head, m_dev, mu, c.vocab, c.d_model, 1, nullptr, logits_buf, active_idx,
+  return slk_gemm_mfma(s, h, 1, ctx->packed_lm_head, m_dev, mu, c.vocab, c.d_model, 1, nullptr, logits_buf, active_idx,
                        c.vocab);
 }

@@ -9,7 +9,7 @@ constexpr int kRowThreads = 256;
 // Alg. 1 'Initialize block input' for the active rows, fused with the first layer's LN:
 // x = Emb[token], h = rnd(x * rsqrt(mean(x^2) + eps) * gain).  The row (a few KB) is read a
 // second time from cache for the scaling pass instead of being held in registers.
-template <typename T>
+template <typename T, bool TILED>
 __global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_kernel(const T* __restrict__ emb,
                                                                     const int32_t* __restrict__ tokens,
                                                                     const int32_t* __restrict__ active_idx,
@@ -30,12 +30,12 @@ __global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_kernel(const T* __r
   ssq = block_sum<kRowThreads>(ssq, sh);
   const float rstd = 1.0f / sqrtf(ssq / (float)d + eps);
   for (int c = threadIdx.x; c < d; c += kRowThreads)
-    st<T>::stv(h + (size_t)r * d + c, st<T>::ld(src + c) * rstd * st<T>::ld(gain + c));
+    st<T>::stv(h + act_index<TILED>(r, c, d), st<T>::ld(src + c) * rstd * st<T>::ld(gain + c));
 }
 
 // x <- rnd(x + delta) (residual add in fp32; delta may arrive as S k-split partials),
 // then h = RMSNorm of the STORED x.
-template <typename T, bool ADD>
+template <typename T, bool ADD, bool TILED>
 __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const float* __restrict__ delta, int S,
                                                                   size_t sstride,
                                                                   const int32_t* __restrict__ m_dev, int m_upper,
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const fl
   ssq = block_sum<kRowThreads>(ssq, sh);
   const float rstd = 1.0f / sqrtf(ssq / (float)d + eps);
   for (int c = threadIdx.x; c < d; c += kRowThreads)   // each thread re-reads what it wrote itself
-    st<T>::stv(h + (size_t)r * d + c, st<T>::ld(xr + c) * rstd * st<T>::ld(gain + c));
+    st<T>::stv(h + act_index<TILED>(r, c, d), st<T>::ld(xr + c) * rstd * st<T>::ld(gain + c));
 }
 
 // q, k <- rnd(RoPE(q, k)) at the row's fixed slot; v <- rnd(v); k, v go to the row's own
@@ -119,7 +119,7 @@ __global__ void rope_table_kernel(float2* tab, int n_pad, int half, int dh, doub
   tab[t] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
-template <typename T>
+template <typename T, bool TILED>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int S, size_t sstride,
                                                      const int32_t* __restrict__ m_dev, int m_upper, int dff,
                                                      T* __restrict__ a) {
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ g
     g += gu[sp * sstride + (size_t)r * 2 * dff + c];
     u += gu[sp * sstride + (size_t)r * 2 * dff + dff + c];
   }
-  st<T>::stv(a + (size_t)r * dff + c, g / (1.0f + expf(-g)) * u);
+  st<T>::stv(a + act_index<TILED>(r, c, dff), g / (1.0f + expf(-g)) * u);
 }
 
 template <typename T>
@@ -172,31 +172,41 @@ __global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
     else { using T = float; __VA_ARGS__; }                      \
   } while (0)
 
+#define DISPATCH_TILED(tiled, ...)                      \
+  do {                                                  \
+    if (tiled) { constexpr bool TL = true; __VA_ARGS__; } \
+    else { constexpr bool TL = false; __VA_ARGS__; }    \
+  } while (0)
+
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
-                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h) {
+                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h,
+                      int tiled) {
   if (m_upper <= 0) return SL_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((embed_rmsnorm_kernel<T>), dim3(m_upper), dim3(kRowThreads), 0, s,
-                                       (const T*)emb, tokens, active_idx, m_dev, m_upper, d, (const T*)gain, eps,
-                                       (T*)x, (T*)h));
+  DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((embed_rmsnorm_kernel<T, TL>), dim3(m_upper),
+                                                             dim3(kRowThreads), 0, s, (const T*)emb, tokens,
+                                                             active_idx, m_dev, m_upper, d, (const T*)gain, eps,
+                                                             (T*)x, (T*)h)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
 
 int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
-                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h) {
+                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((add_rmsnorm_kernel<T, true>), dim3(m_upper), dim3(kRowThreads), 0, s, (T*)x,
-                                       delta, S, sstride, m_dev, m_upper, d, (const T*)gain, eps, (T*)h));
+  DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_kernel<T, true, TL>), dim3(m_upper),
+                                                             dim3(kRowThreads), 0, s, (T*)x, delta, S, sstride,
+                                                             m_dev, m_upper, d, (const T*)gain, eps, (T*)h)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
 
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d, const void* gain,
-                float eps, void* h) {
+                float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((add_rmsnorm_kernel<T, false>), dim3(m_upper), dim3(kRowThreads), 0, s,
-                                       (T*)const_cast<void*>(x), (const float*)nullptr, 1, (size_t)0, m_dev, m_upper, d,
-                                       (const T*)gain, eps, (T*)h));
+  DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_kernel<T, false, TL>), dim3(m_upper),
+                                                             dim3(kRowThreads), 0, s, (T*)const_cast<void*>(x),
+                                                             (const float*)nullptr, 1, (size_t)0, m_dev, m_upper, d,
+                                                             (const T*)gain, eps, (T*)h)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -221,10 +231,11 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
 }
 
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
-               int dff, void* a) {
+               int dff, void* a, int tiled) {
   if (m_upper <= 0) return SL_OK;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((swiglu_kernel<T>), dim3(sl_cdiv(dff, 256), m_upper), dim3(256), 0, s, gu,
-                                       S, sstride, m_dev, m_upper, dff, (T*)a));
+  DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((swiglu_kernel<T, TL>), dim3(sl_cdiv(dff, 256), m_upper),
+                                                             dim3(256), 0, s, gu, S, sstride, m_dev, m_upper, dff,
+                                                             (T*)a)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

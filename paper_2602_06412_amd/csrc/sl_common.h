@@ -40,6 +40,19 @@ __host__ __device__ inline size_t vc_index(int slot, int dim, int dh) {
   return (((size_t)(slot >> 4) * 2 + ((slot >> 2) & 1)) * dh + dim) * 8 + ((slot >> 3) & 1) * 4 + (slot & 3);
 }
 
+// ---- activation matrices feeding the MFMA GEMMs ------------------------------------------
+// "Tiled" layout of an [rows, K] bf16 matrix: MFMA A-operand fragments [rows/32][K/16][64][8],
+// lane = row%32 + 32*((col%16)/8).  A GEMM workgroup then fetches each 32 x 16 fragment as one
+// contiguous 1 KiB block instead of gathering 32 B from 32 different rows.  Rows are padded
+// to a multiple of 32 by the allocation.
+__host__ __device__ inline size_t afrag_index(int row, int col, int K) {
+  return (((size_t)(row >> 5) * (K >> 4) + (col >> 4)) * 64 + (row & 31) + 32 * ((col >> 3) & 1)) * 8 + (col & 7);
+}
+template <bool TILED>
+__host__ __device__ inline size_t act_index(int row, int col, int K) {
+  return TILED ? afrag_index(row, col, K) : (size_t)row * K + col;
+}
+
 // ---- wave / block reductions (wave = 64 lanes) ------------------------------------
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -146,18 +159,20 @@ int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, 
               const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step,
               float* kl, float* conf, int32_t* argmax);
 // rowwise_kernels.hip
+// `tiled`: write h / a in the fragment-tiled layout (afrag_index) instead of row-major
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
-                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h);
+                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h,
+                      int tiled);
 // delta / qkv / gu may be S k-split partials, `sstride` floats apart; they are summed in split order
 int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
-                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h);
+                    const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h, int tiled);
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d,
-                const void* gain, float eps, void* h);
+                const void* gain, float eps, void* h, int tiled);
 int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta);
 int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
                       const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
-               int dff, void* a);
+               int dff, void* a, int tiled);
 int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
                 void* k_out, void* v_out);
 int slk_fill_zero(hipStream_t s, void* p, size_t bytes);
@@ -173,8 +188,11 @@ int slk_attention_generic(hipStream_t s, int dtype, const void* q, const void* k
 // gemm_mfma.hip
 int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off);
 int slk_gemm_splits(int mu, int n, int k);
-int slk_gemm_mfma(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k, int splits,
-                  float* Cf, void* Cb, const int32_t* row_map, size_t ldc);
+// a_tiled: A is in the fragment-tiled layout (rows padded to 32) instead of row-major
+int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                  int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc);
+int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                     int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc);
 // attention_mfma.hip
 int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void* vc, const int32_t* active_idx,
                        const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o, float* scratch);
