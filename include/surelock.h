@@ -203,7 +203,10 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
 /* ---- the M-row projection alone ---------------------------------------------------------
  * y = x W^T for the packed active rows on the MFMA units (the GEMM terms Q, K, V, Out, FFN
  * of Sec. 2.4), bf16 only; n % 32 == 0, k % 64 == 0.  sl_linear_pack re-tiles W [n, k] into
- * the fragment layout (same byte count).  sl_linear_forward: x [m_upper, k] bf16; splits = 0
+ * the fragment layout (same byte count).  sl_linear_forward: x [m_upper, k] bf16, row-major
+ * (x_tiled = 0) or in the same 32 x 16 fragment tiling as the weights, rows padded to a
+ * multiple of 32 (x_tiled = 1: element (r, c) at
+ * (((r/32)*(k/16) + c/16)*64 + r%32 + 32*((c%16)/8))*8 + c%8); splits = 0
  * picks the k-split count (query it with sl_linear_splits); exactly one of
  *   y_f32  [splits][m_upper][n] fp32 partial sums (caller adds the splits), or
  *   y_bf16 [*, n] bf16 rows, row r written to row row_map[r] (row_map may be null; splits
@@ -211,8 +214,9 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
  * must be non-null. */
 int sl_linear_pack(void *stream, const void *w, int32_t n, int32_t k, void *packed, size_t packed_bytes);
 int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k);
-int sl_linear_forward(void *stream, const void *x, const void *packed, const int32_t *m_dev, int32_t m_upper,
-                      int32_t n, int32_t k, int32_t splits, float *y_f32, void *y_bf16, const int32_t *row_map);
+int sl_linear_forward(void *stream, const void *x, int32_t x_tiled, const void *packed, const int32_t *m_dev,
+                      int32_t m_upper, int32_t n, int32_t k, int32_t splits, float *y_f32, void *y_bf16,
+                      const int32_t *row_map);
 
 /* ---- measurement support ------------------------------------------------------------
  * Per-kernel timing of the step's launches with HIP events on the step's own stream.

@@ -52,7 +52,7 @@ _SIGS = {
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
     "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
     "sl_linear_splits": [_I, _I, _I],
-    "sl_linear_forward": [_P, _P, _P, _P, _I, _I, _I, _I, _P, _P, _P],
+    "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
     "sl_profile_begin": [_P, _I],
     "sl_profile_end": [_P, C.POINTER(C.c_float), C.POINTER(_I)],
     "sl_lock_test": [_P, _P, _I, _P, _I, _I, _P, _P, _P, _P, _P, _I, _P, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P],
@@ -238,9 +238,21 @@ def sl_linear_splits(m_upper, n, k):
     return r
 
 
-def sl_linear_forward(x, packed, m_dev, m_upper, n, k, splits=0, y_f32=None, y_bf16=None, row_map=None):
-    _check("sl_linear_forward", lib().sl_linear_forward(_stream(), _ptr(x), _ptr(packed), _ptr(m_dev), m_upper, n, k,
-                                                        splits, _ptr(y_f32), _ptr(y_bf16), _ptr(row_map)))
+def sl_linear_forward(x, packed, m_dev, m_upper, n, k, splits=0, y_f32=None, y_bf16=None, row_map=None, x_tiled=0):
+    _check("sl_linear_forward", lib().sl_linear_forward(_stream(), _ptr(x), int(x_tiled), _ptr(packed), _ptr(m_dev),
+                                                        m_upper, n, k, splits, _ptr(y_f32), _ptr(y_bf16),
+                                                        _ptr(row_map)))
+
+
+def tile_activations(x):
+    """[rows, k] bf16 row-major -> the fragment-tiled layout sl_linear_forward(x_tiled=1) reads
+    (rows padded to a multiple of 32).  A torch permutation, for tests and tuning."""
+    rows, k = x.shape
+    r32 = (rows + 31) // 32 * 32
+    xp = torch.zeros(r32, k, dtype=x.dtype, device=x.device)
+    xp[:rows] = x
+    # [mb, r, kb, half, e] -> [mb, kb, half, r, e]
+    return xp.view(r32 // 32, 32, k // 16, 2, 8).permute(0, 2, 3, 1, 4).contiguous().view(-1)
 
 
 PROF_SLOTS = ["compact", "embed_norm", "gemm_qkv", "rope_kv", "attention", "gemm_out", "add_norm", "gemm_gate_up",

@@ -209,21 +209,48 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
-// Number of k-splits for a launch bounded by mu rows: enough workgroups for two per CU,
-// capped so that the fp32 partial traffic (written here, read back by the consumer) stays
-// small against the weight stream (thin-M regime: k >= 16*S*mu) or against the MFMA time
-// (thick-M regime: S <= k/2048), and each split keeps an even number (>= 4) of k-tiles.
-int slk_gemm_splits(int mu, int n, int k) {
-  const bool thick = mu > 128;                       // 256 x 256 tiles, one workgroup per CU
-  const int bm = thick ? 256 : pick_bm(mu);
-  const int tiles = sl_cdiv(mu, bm) * sl_cdiv(n, 256);
-  const int target = thick ? 256 : 512;
-  int s = 1;
-  while (s < 8 && tiles * s < target && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
-         ((size_t)(s * 2) * 16 * mu <= (size_t)k || s * 2 <= k / 2048))
-    s *= 2;
-  return s;
+// Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
+//  * thin launches (mu <= 128) are weight-stream bound: one BM x 256 tile per 256 columns, k
+//    split until there are about two workgroups per CU, with the fp32 partial traffic capped
+//    at a fraction of the weight bytes (k >= 32*S*mu);
+//  * thick launches pick, by a small cost model calibrated on measured launches, between the
+//    256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep k-tile and wave of
+//    workgroups) and the 128 x 256 kernel (two per CU, ~1.8 us per 64-deep k-tile and wave),
+//    each with the split count that minimises  waves * (k-tiles per split + fixed) * t_tile
+//    + bytes of fp32 partials written and read back / 5 TB/s.
+struct GemmPlan {
+  int thick256;   // 1: gemm_mfma256_kernel
+  int splits;
+};
+static GemmPlan gemm_plan(int mu, int n, int k) {
+  GemmPlan p{0, 1};
+  if (mu <= 128) {
+    const int tiles = sl_cdiv(n, 256);
+    int s = 1;
+    while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
+           (size_t)(s * 2) * 16 * mu <= (size_t)k)
+      s *= 2;
+    p.splits = s;
+    return p;
+  }
+  double best = 1e30;
+  const int t256 = sl_cdiv(mu, 256) * sl_cdiv(n, 256), t128 = sl_cdiv(mu, 128) * sl_cdiv(n, 256);
+  for (int s = 1; s <= 8; s *= 2) {
+    if (k % (2 * BK * s)) break;
+    const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
+    if (k / (32 * s) >= 8) {
+      const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 + traffic_us;
+      if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
+    }
+    if (k / (BK * s) >= 4) {
+      const double t = sl_cdiv(t128 * s, 512) * (k / (64.0 * s) + 3.0) * 1.8 + traffic_us;
+      if (t < best) { best = t; p.thick256 = 0; p.splits = s; }
+    }
+  }
+  return p;
 }
+
+int slk_gemm_splits(int mu, int n, int k) { return gemm_plan(mu, n, k).splits; }
 
 template <int BM, int WNB, int OUT, int DBG = 0>
 static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
@@ -257,7 +284,12 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
   if (dbg == 6 && Cf) return launch_gemm<128, 2, 0, 6>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (dbg == 3 && Cf) return launch_gemm<256, 2, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (dbg == 4 && Cf) return launch_gemm<256, 2, 0, 2>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 7) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+  static const int thick = getenv("SL_GEMM_THICK") ? atoi(getenv("SL_GEMM_THICK")) : -1;   // tuning aid
+  if (mu > 128 && k / splits >= 256) {
+    const GemmPlan plan = gemm_plan(mu, n, k);
+    const bool use256 = thick >= 0 ? thick != 0 : (plan.splits == splits ? plan.thick256 != 0 : true);
+    if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+  }
   static const int force_bm = getenv("SL_GEMM_BM") ? atoi(getenv("SL_GEMM_BM")) : 0;   // tuning aid
   if (force_bm == 32) { GO(32); }
   if (force_bm == 64) { GO(64); }

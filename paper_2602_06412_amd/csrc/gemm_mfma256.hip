@@ -87,7 +87,7 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
                  : "memory", "m0");
   };
   auto issue = [&](int kt, int st) {
-    if (DBG == 1) return;
+    if (DBG == 1 || DBG == 6 || DBG == 7) return;
     kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
     Frag* sa = lds + st * STAGE + (wave * 2) * 64;
     Frag* sb = lds + st * STAGE + 16 * 64 + (wave * 2) * 64;
@@ -144,12 +144,12 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const int st_prev = st == 0 ? NS - 1 : st - 1;
     const int st_next = st == NS - 1 ? 0 : st + 1;
     issue(kt + NS - 1, st_prev);
-    read_frags(st, 1, a1, b1);
+    if (DBG != 7) read_frags(st, 1, a1, b1);
     mma(a0, b0);
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
-    __syncthreads();                                  // ... and so has everyone else's
-    read_frags(st_next, 0, a0, b0);
+    if (DBG != 6 && DBG != 7) __syncthreads();        // ... and so has everyone else's
+    if (DBG != 7) read_frags(st_next, 0, a0, b0);
     mma(a1, b1);
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
@@ -202,6 +202,8 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   static const int ns = getenv("SL_GEMM256_NS") ? atoi(getenv("SL_GEMM256_NS")) : 5;      // tuning aid
   static const int dbg = getenv("SL_GEMM256_DBG") ? atoi(getenv("SL_GEMM256_DBG")) : 0;
   if (dbg == 1 && Cf) return launch256<0, 5, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 6 && Cf) return launch256<0, 5, 6>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (dbg == 7 && Cf) return launch256<0, 5, 7>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (dbg == 3 && Cf) return launch256<0, 5, 3>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (dbg == 4 && Cf) return launch256<0, 5, 4>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (dbg == 5 && Cf) return launch256<0, 5, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
