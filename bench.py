@@ -24,6 +24,10 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK = 2.5e15      # dense bf16 FLOP/s, MI355X
 HBM_PEAK = 8.0e12            # B/s
+# HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
+# WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
+# the copy-kernel calibration given there), keyed by M.
+LM_HEAD_TRAFFIC_BYTES = {1024: 1832467661, 16: 1044180070}
 
 
 def main():
@@ -133,14 +137,23 @@ def main():
 
     head = results[0]
     M0 = head["M"]
+    # Dominant kernel of the step: the LM-head GEMM launch (one per step).  Its duration is the
+    # HIP-event time of that launch on the step's stream, averaged over the K profiled steps.
+    lm_ms = head["kernels_ms"]["lm_head"]
     if M0 >= 512:
-        roof = {"kernel": "gemm_mfma_kernel (QKV, Out, gate/up, down, LM head)", "bound": "mfma",
-                "achieved": head["gemm_tflops"], "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
-                "frac": head["gemm_mfma_frac"], "traffic": None}
+        ach = M0 * lm_flops / (lm_ms * 1e-3) / 1e12
+        roof = {"kernel": "gemm_mfma256_kernel<1> (LM head, M=%d x V=%d x d=%d)" % (M0, V, d), "bound": "mfma",
+                "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
+                "launch_ms": round(lm_ms, 4), "algorithmic_flops_per_launch": M0 * lm_flops,
+                "gemm_family_tflops": head["gemm_tflops"], "gemm_family_frac": head["gemm_mfma_frac"]}
     else:
-        roof = {"kernel": "gemm_mfma_kernel (weight stream)", "bound": "hbm",
-                "achieved": head["gemm_weight_stream_GBps"], "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": head["gemm_hbm_frac"], "traffic": None}
+        bytes_ = lm_w_bytes + 2 * M0 * d + 2 * M0 * V
+        ach = bytes_ / (lm_ms * 1e-3) / 1e9
+        roof = {"kernel": "gemm_mfma_kernel<1> (LM head weight stream, M=%d)" % M0, "bound": "hbm",
+                "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": round(ach * 1e9 / HBM_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
+                "launch_ms": round(lm_ms, 4), "algorithmic_bytes_per_launch": bytes_}
 
     cpu = None
     if not args.no_cpu_baseline:
