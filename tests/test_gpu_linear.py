@@ -1,0 +1,98 @@
+"""GPU parity of the stand-alone M-row projection (sl_linear_pack / sl_linear_forward) against
+the plain definition y = x W^T evaluated in fp64 on the CPU (the GEMM terms of Sec. 2.4).
+
+Inputs are bf16, hence exact in fp64; the kernel accumulates in fp32, so every output obeys the
+textbook dot-product bound |err| <= gamma_k * sum_j |x_j||w_j| with gamma_k ~ k * 2^-24 (any
+summation order), plus half a bf16 spacing when the result is stored as bf16."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_06412_amd import binding as B
+from tests.gpu_util import DEV, bf16_ulp
+
+pytestmark = pytest.mark.gpu
+
+# (n, k, m_upper, m): thin and thick launches, ragged m < m_upper, n not a multiple of 256
+CASES = [
+    (4160, 512, 32, 1),
+    (1024, 4096, 64, 33),
+    (4160, 1024, 128, 100),
+    (12288, 1536, 704, 700),
+    (8192, 4096, 1024, 1000),
+    (4096, 12288, 1024, 1024),
+]
+
+
+def _inputs(seed, n, k, m_upper):
+    g = torch.Generator().manual_seed(seed)
+    w = (torch.randn(n, k, generator=g) * 0.05).bfloat16()
+    x = torch.randn(m_upper, k, generator=g).bfloat16()
+    return w, x
+
+
+def _bound(x64, w64, k):
+    return 2.0 * k * 2.0 ** -24 * (np.abs(x64) @ np.abs(w64).T) + 1e-30
+
+
+@pytest.mark.parametrize("n,k,m_upper,m", CASES)
+@pytest.mark.parametrize("x_tiled", [0, 1])
+def test_linear_fp32_partials(n, k, m_upper, m, x_tiled):
+    w, x = _inputs(n + k + m, n, k, m_upper)
+    wd, xd = w.to(DEV), x.to(DEV)
+    packed = torch.empty_like(wd)
+    B.sl_linear_pack(wd, packed)
+    S = B.sl_linear_splits(m_upper, n, k)
+    assert S >= 1 and k % (16 * S) == 0
+    y = torch.full((S, m_upper, n), float("nan"), device=DEV)
+    m_dev = torch.tensor([m], dtype=torch.int32, device=DEV)
+    xin = B.tile_activations(xd) if x_tiled else xd
+    B.sl_linear_forward(xin, packed, m_dev, m_upper, n, k, S, y_f32=y, x_tiled=x_tiled)
+    torch.cuda.synchronize()
+    got = y[:, :m].double().sum(0).cpu().numpy()
+    x64, w64 = x[:m].double().numpy(), w.double().numpy()
+    ref = x64 @ w64.T
+    assert np.isfinite(got).all()
+    assert np.all(np.abs(got - ref) <= _bound(x64, w64, k))
+
+
+@pytest.mark.parametrize("n,k,m_upper,m", CASES[1:5])
+def test_linear_bf16_row_map(n, k, m_upper, m):
+    w, x = _inputs(7 * n + k + m, n, k, m_upper)
+    wd, xd = w.to(DEV), x.to(DEV)
+    packed = torch.empty_like(wd)
+    B.sl_linear_pack(wd, packed)
+    rows_out = 2 * m_upper
+    rng = np.random.default_rng(m)
+    row_map = np.sort(rng.choice(rows_out, size=m_upper, replace=False)).astype(np.int32)
+    y = torch.full((rows_out, n), -7.0, device=DEV, dtype=torch.bfloat16)
+    m_dev = torch.tensor([m], dtype=torch.int32, device=DEV)
+    B.sl_linear_forward(B.tile_activations(xd), packed, m_dev, m_upper, n, k, 1, y_bf16=y,
+                        row_map=torch.as_tensor(row_map, device=DEV), x_tiled=1)
+    torch.cuda.synchronize()
+    yh = y.double().cpu().numpy()
+    x64, w64 = x[:m].double().numpy(), w.double().numpy()
+    ref = x64 @ w64.T
+    got = yh[row_map[:m]]
+    assert np.all(np.abs(got - ref) <= _bound(x64, w64, k) + 0.5 * bf16_ulp(ref) * (1 + 1e-9))
+    untouched = np.ones(rows_out, dtype=bool)
+    untouched[row_map[:m]] = False
+    assert np.all(yh[untouched] == -7.0), "rows outside row_map[:m] must not be written"
+
+
+def test_linear_argument_errors():
+    wd = torch.zeros(64, 64, device=DEV, dtype=torch.bfloat16)
+    packed = torch.empty_like(wd)
+    B.sl_linear_pack(wd, packed)
+    x = torch.zeros(32, 64, device=DEV, dtype=torch.bfloat16)
+    m_dev = torch.tensor([1], dtype=torch.int32, device=DEV)
+    y = torch.zeros(1, 32, 64, device=DEV)
+    yb = torch.zeros(32, 64, device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(B.SureLockError):                      # both outputs given
+        B.sl_linear_forward(x, packed, m_dev, 32, 64, 64, 1, y_f32=y, y_bf16=yb)
+    with pytest.raises(B.SureLockError):                      # neither
+        B.sl_linear_forward(x, packed, m_dev, 32, 64, 64, 1)
+    with pytest.raises(B.SureLockError):                      # k not a multiple of 64
+        B.sl_linear_forward(x, packed, m_dev, 32, 64, 48, 1, y_f32=y)
+    with pytest.raises(B.SureLockError):                      # bf16 output with a k-split
+        B.sl_linear_forward(x, packed, m_dev, 32, 64, 64, 2, y_bf16=yb)
