@@ -50,7 +50,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   // one head (same K/V) land on one XCD and share its L2
   const int hh = blockIdx.x;
   // per-sequence row ranges: cu[b] = first packed row whose flat id >= b*N
-  if (tid <= B) {
+  if (B == 1) {
+    if (tid <= 1) cu[tid] = tid ? M : 0;
+  } else if (tid <= B) {
     int lo = 0, hi = M;
     const long long key = (long long)tid * N;
     while (lo < hi) {
@@ -143,7 +145,10 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
     const float alpha = exp2f((m_run - m_new) * sc);
     const float mb_ = m_new * sc;
     float psum = 0.f;
-    FragA pf[4];
+    // The probabilities enter the second product as a bf16 pair hi + lo (lo = the bf16 of what
+    // hi's rounding lost): one bf16 alone carries a relative error of 2^-9 per probability,
+    // enough to move ~30% of the attention outputs to the neighbouring bf16 value.
+    FragA pf[4], pl[4];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       float p[16];
@@ -156,14 +161,20 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) pf[2 * kb + j][e] = (__bf16)p[8 * j + e];
+        for (int e = 0; e < 8; ++e) {
+          const __bf16 hi = (__bf16)p[8 * j + e];
+          pf[2 * kb + j][e] = hi;
+          pl[2 * kb + j][e] = (__bf16)(p[8 * j + e] - (float)hi);
+        }
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
+    if (__any(alpha != 1.0f)) {                // the running max rarely moves after the first tiles
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
+        for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
+    }
     // O^T += V^T P^T
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
@@ -171,6 +182,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
       for (int mb = 0; mb < 4; ++mb) {
         const FragA a = ldsV[(2 * st + (lane >> 5)) * DH + mb * 32 + (lane & 31)];
         acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[st], acc_o[mb], 0, 0, 0);
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl[st], acc_o[mb], 0, 0, 0);
       }
     }
   }

@@ -35,18 +35,13 @@ def bf16_ulp(x):
 
 def logits_tol(z_oracle, storage):
     """Per-element tolerance on logits.
-    bf16: 3e-2 + one bf16 spacing at |z|.  Derivation: oracle and GPU keep the same bf16
-    rounding points but accumulate in fp64 / fp32, so a stored activation now and then lands on
-    the neighbouring bf16 value (spacing 2^-7 ~ 0.008 at |h| ~ 1).  Through the d = 4096-term LM
-    head with N(0, 0.02^2) weights such one-spacing differences give a logit drift of standard
-    deviation ~ sqrt(4096) * 0.004 * 0.02 ~ 5e-3 (measured mean |err| 3.6e-3); the maximum over
-    the ~1e6..1e8 logits of a test sits near 5-6 sigma, i.e. just above the nominal 2e-2, and
-    the final rounding of both sides to the bf16 grid (spacing 0.0156 on [2,4), 0.031 on [4,8))
-    adds up to one spacing.  The nominal 2e-2 is kept as a bound on the bulk: check_logits also
-    requires mean |err| <= 5e-3 and at most 1e-3 of the elements beyond 2e-2.
+    bf16: the nominal 2e-2 plus one bf16 spacing at |z|: oracle and GPU keep the same bf16
+    rounding points but accumulate in fp64 / fp32, so a value that sits on a rounding boundary
+    can land on the neighbouring bf16 number on either side (spacing 0.0156 on [2,4), 0.031 on
+    [4,8)); everything else must stay within 2e-2.
     fp32: 2e-4 absolute (fp32 accumulation over <= 4096-term dot products)."""
     if storage == "bf16":
-        return 3e-2 + bf16_ulp(z_oracle)
+        return 2e-2 + bf16_ulp(z_oracle)
     return np.full_like(z_oracle, 2e-4)
 
 
@@ -58,9 +53,7 @@ def check_logits(z_gpu, z_oracle, storage, what=""):
     assert np.all(err <= tol), (f"{what}: {int((err > tol).sum())} of {err.size} logits out of tolerance; worst: err "
                                 f"{err.flat[w]:.4g} vs tol {tol.flat[w]:.4g} at z={z_oracle.flat[w]:.4g}; "
                                 f"mean err {err.mean():.3g}, frac > 2e-2: {np.mean(err > 2e-2):.2e}")
-    if storage == "bf16":
-        assert err.mean() <= 5e-3, f"{what}: mean logit err {err.mean():.4g}"
-        assert np.mean(err > 2e-2) <= 1e-3, f"{what}: {np.mean(err > 2e-2):.2e} of logits off by more than 2e-2"
+    print(f"{what}: logits max err {err.max():.4g}, mean {err.mean():.3g}, frac > 2e-2: {np.mean(err > 2e-2):.2e}", flush=True)
     return err
 
 
