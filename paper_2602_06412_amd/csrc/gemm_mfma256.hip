@@ -113,10 +113,12 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   auto read_frags = [&](int st, int kb, Frag (&af)[4], Frag (&bf)[2]) {
     const Frag* sa = lds + st * STAGE + (wm * 8 + kb) * 64 + lane;          // mb = 4*wm + i
     const Frag* sb = lds + st * STAGE + 16 * 64 + (wn * 4 + kb) * 64 + lane; // nb = 2*wn + i
+    // in the order the MFMAs consume them: (a0,b0) (a0,b1) (a1,*) (a2,*) (a3,*)
+    bf[0] = sb[0];
+    af[0] = sa[0];
+    bf[1] = sb[2 * 64];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) af[i] = sa[(i * 2) * 64];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) bf[i] = sb[(i * 2) * 64];
+    for (int i = 1; i < 4; ++i) af[i] = sa[(i * 2) * 64];
   };
   auto mma = [&](const Frag (&af)[4], const Frag (&bf)[2]) {
 #pragma unroll
@@ -129,6 +131,16 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // complete in order, 4 per tile per wave)
 #define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (NS - 2)) : "memory")
 
+  // one LDS read slotted behind each of the first six MFMAs of a k-step: the wave's issue slot is
+  // blocked while the MFMA pipe is busy anyway, so the reads issue for free
+#define SL_INTERLEAVE()                                                                    \
+  do {                                                                                     \
+    _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {                                     \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   \
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
+    }                                                                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                     \
+  } while (0)
   // prologue: tiles 0 .. NS-2 in flight, tile 0 landed and published, its first fragments read
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t) issue(t, t);
@@ -146,11 +158,13 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     issue(kt + NS - 1, st_prev);
     if (DBG != 7) read_frags(st, 1, a1, b1);
     mma(a0, b0);
+    SL_INTERLEAVE();
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
     if (DBG != 6 && DBG != 7) __syncthreads();        // ... and so has everyone else's
     if (DBG != 7) read_frags(st_next, 0, a0, b0);
     mma(a1, b1);
+    SL_INTERLEAVE();
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
   }
@@ -178,6 +192,8 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     }
   }
 }
+
+
 
 template <int OUT, int NS, int DBG = 0>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
