@@ -417,7 +417,7 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   // A_t
   SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, lock, B, N, active_idx, cu_active));
   // block input of the active rows + first LN
-  SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model,
+  SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model, c.vocab,
                            ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
   SL_TRY(run_layers(ctx, s, ws, active_idx, m_dev, m_upper, 0, c.n_layers));
   // logits of the active rows, written to their rows of this step's posterior buffer

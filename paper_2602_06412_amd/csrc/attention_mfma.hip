@@ -28,22 +28,35 @@ constexpr int DH = 128;
 constexpr int kMaxBatch = 255;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t PFrag __attribute__((ext_vector_type(4)));   // eight bf16 probabilities, packed in pairs
 
 // SPLIT: the key tiles are divided over gridDim.z workgroups (thin launches would otherwise
 // leave most CUs idle and walk all N slots serially); each writes its unnormalised O, running
 // max and sum, and attention_merge_kernel combines them.
+//
+// Software pipeline.  With one wave per SIMD nothing else can hide the softmax arithmetic, so
+// each wave overlaps its own work: iteration t issues the MFMAs of O += V(t-1)^T P(t-1)^T and of
+// S(t+1) = K(t+1) Q^T while the vector ALU turns S(t) into P(t) (MFMAs run asynchronously once
+// issued).  O is kept relative to the running max of the tiles already ADDED, so the rescale by
+// alpha(t) follows the accumulation of tile t-1 and happens only when some lane's max moved.
+// K and V tiles arrive by direct-to-LDS loads into two-slot rings (K(t+2) and V(t) are issued in
+// iteration t, one iteration ahead of their use); one barrier per tile.
 template <bool SPLIT>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ q,
-                                                             const bf16_t* __restrict__ kc,
-                                                             const bf16_t* __restrict__ vc,
-                                                             const int32_t* __restrict__ active_idx,
-                                                             const int32_t* __restrict__ m_dev, int m_upper, int B,
-                                                             int H, int N, int n_pad, bf16_t* __restrict__ o,
-                                                             int tiles_per_split, float* __restrict__ part_o,
-                                                             float* __restrict__ part_ml) {
-  __shared__ FragA ldsK[KT * DH / 8];        // 16 KiB
-  __shared__ FragA ldsV[KT * DH / 8];        // 16 KiB
+__global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __restrict__ q,
+                                                                const bf16_t* __restrict__ kc,
+                                                                const bf16_t* __restrict__ vc,
+                                                                const int32_t* __restrict__ active_idx,
+                                                                const int32_t* __restrict__ m_dev, int m_upper, int B,
+                                                                int H, int N, int n_pad, bf16_t* __restrict__ o,
+                                                                int tiles_per_split, float* __restrict__ part_o,
+                                                                float* __restrict__ part_ml) {
+  extern __shared__ FragA lds[];             // K ring [R][16 KiB] | V ring [R][16 KiB]
   __shared__ int cu[kMaxBatch + 2];
+  constexpr int TILE_F = KT * DH / 8;        // FragA elements per tile
+  FragA* const ldsK = lds;
+  constexpr int R = 3;                       // ring depth: tiles are requested R-1 iterations ahead
+  FragA* const ldsV = lds + R * TILE_F;
   const int M = min(*m_dev, m_upper);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // blockIdx.x = head: consecutive workgroup ids go to different XCDs, so the query tiles of
@@ -74,6 +87,31 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   const size_t head_base = ((size_t)b * H + hh) * n_pad * DH;
   const FragA* kg = reinterpret_cast<const FragA*>(kc + head_base);
   const FragA* vg = reinterpret_cast<const FragA*>(vc + head_base);
+  const int kt_lo = SPLIT ? blockIdx.z * tiles_per_split : 0;
+  const int kt_hi = SPLIT ? min(n_pad / KT, kt_lo + tiles_per_split) : n_pad / KT;
+  const int T = kt_hi - kt_lo;               // >= 1 tiles for this workgroup
+
+  // a 16 KiB tile is a straight copy: 16 chunks of 1 KiB, four per wave, lane L's 16 bytes land at
+  // chunk base + 16 L
+  auto load_chunk = [&](const FragA* g, FragA* l, int c) {
+    const int chunk = wave * 4 + c;
+    const uint32_t laddr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) FragA*)(l + chunk * 64));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(g + chunk * 64 + lane), "s"(laddr)
+                 : "memory", "m0");
+  };
+  auto load_tile = [&](const FragA* g, FragA* l) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) load_chunk(g, l, c);
+  };
+  // prologue loads: K(0..R-1), V(0..R-3); V(0) also into the slot iteration 0 multiplies by P = 0
+#pragma unroll
+  for (int j = 0; j < R; ++j) load_tile(kg + (size_t)min(kt_lo + j, kt_hi - 1) * TILE_F, ldsK + j * TILE_F);
+#pragma unroll
+  for (int j = 0; j < R - 2; ++j) load_tile(vg + (size_t)min(kt_lo + j, kt_hi - 1) * TILE_F, ldsV + j * TILE_F);
+  load_tile(vg + (size_t)kt_lo * TILE_F, ldsV + (R - 1) * TILE_F);
 
   // Q^T fragments: lane holds query (lane&31), dims ks*16 + (lane>>5)*8 .. +7
   const int my_row = row0 + wave * 32 + (lane & 31);
@@ -93,79 +131,127 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(d_h)
 
-  const int kt_lo = SPLIT ? blockIdx.z * tiles_per_split : 0;
-  const int n_tiles = SPLIT ? min(n_pad / KT, kt_lo + tiles_per_split) : n_pad / KT;
-  FragA kreg[4], vreg[4];
-  {
-    const FragA* k0 = kg + (size_t)kt_lo * (KT * DH / 8);
-    const FragA* v0 = vg + (size_t)kt_lo * (KT * DH / 8);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { kreg[i] = k0[tid + 256 * i]; vreg[i] = v0[tid + 256 * i]; }
-  }
-
-  for (int kt = kt_lo; kt < n_tiles; ++kt) {
-    __syncthreads();                          // previous tile fully consumed
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { ldsK[tid + 256 * i] = kreg[i]; ldsV[tid + 256 * i] = vreg[i]; }
-    __syncthreads();
-    if (kt + 1 < n_tiles) {
-      const FragA* kn = kg + (size_t)(kt + 1) * (KT * DH / 8);
-      const FragA* vn = vg + (size_t)(kt + 1) * (KT * DH / 8);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { kreg[i] = kn[tid + 256 * i]; vreg[i] = vn[tid + 256 * i]; }
-    }
-    // S^T = K Q^T : two 32-key blocks
-    f32x16 s[2];
+  // S^T = K Q^T for one tile: two 32-key blocks
+  auto scores = [&](const FragA* kt_lds, f32x16 (&sv)[2]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+      for (int v = 0; v < 16; ++v) sv[kb][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const FragA a = ldsK[(kb * 16 + 2 * ks) * 32 + lane];
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], s[kb], 0, 0, 0);
+        const FragA a = kt_lds[(kb * 8 + ks) * 64 + lane];
+        sv[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sv[kb], 0, 0, 0);
       }
     }
-    // accumulator register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
-    if ((kt + 1) * KT > N) {
-      const int kbase = kt * KT + 4 * (lane >> 5);
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) s[kb][v] = -INFINITY;
-    }
-    float mx = s[0][0];
+  };
+  // accumulator register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
+  auto mask_tail = [&](int kt, f32x16 (&sv)[2]) {
+    const int kbase = kt * KT + 4 * (lane >> 5);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+      for (int v = 0; v < 16; ++v)
+        if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) sv[kb][v] = -INFINITY;
+  };
+  // O^T += V^T P^T with P = hi + lo
+  auto pv = [&](const FragA* vt_lds, const PFrag (&ph)[4], const PFrag (&pl)[4]) {
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      FragA a[4];
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) a[mb] = vt_lds[(2 * st + (lane >> 5)) * DH + mb * 32 + (lane & 31)];
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+    }
+  };
+  // One pipeline step for tile t: scores sc_cur -> probabilities (p_new_hi/lo), while the MFMAs
+  // add tile t-1 (p_old) and compute the scores of tile t+1 (sc_next).
+  auto step = [&](int t, f32x16 (&sc_cur)[2], f32x16 (&sc_next)[2], const PFrag (&poh)[4], const PFrag (&pol)[4],
+                  PFrag (&pnh)[4], PFrag (&pnl)[4]) {
+    // loads complete in order, eight chunks per wave per iteration: all but those of the last
+    // R-2 iterations have landed, which covers K(t+1) and V(t-1)
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (R - 2)) : "memory");
+    __syncthreads();      // ... for everyone; the slots of K(t) and V(t-2) are free
+    // K(t+R) and V(t+R-2) go into the two slots the barrier just freed, one 1 KiB chunk every fourth
+    // MFMA slot below (a burst of eight would fill the load queue and stall the wave at issue).
+    // Past the last tile K re-fetches the last one; nothing reads it.
+    const FragA* k_src = kg + (size_t)min(kt_lo + t + R, kt_hi - 1) * TILE_F;
+    const FragA* v_src = vg + (size_t)min(kt_lo + t + R - 2, kt_hi - 1) * TILE_F;
+    FragA* const k_dst = ldsK + (t % R) * TILE_F;
+    FragA* const v_dst = ldsV + ((t + R - 2) % R) * TILE_F;
+    const FragA* vt_lds = ldsV + ((t + R - 1) % R) * TILE_F + (lane >> 5) * DH + (lane & 31);
+    const FragA* kt_lds = ldsK + ((t + 1) % R) * TILE_F + lane;
+    // The block below is laid out by hand as 48 slots, one MFMA each, fenced so that the
+    // compiler keeps the order: slots 0..31 add tile t-1 (V fragment groups of four, hi then lo),
+    // slots 32..47 compute the scores of tile t+1; LDS fragments are read 8..10 slots ahead of
+    // their MFMA; the softmax of tile t rides along, one pair of probabilities every third slot
+    // (an MFMA occupies the matrix pipe for 32 cycles, a pair costs ~76 vector-ALU cycles).
+    FragA va[2][4], kf[16];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) va[0][mb] = vt_lds[mb * 32];
+    // running max of tile t while those first reads are in flight
+    float mx = sc_cur[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc_cur[kb][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one real key
-    const float alpha = exp2f((m_run - m_new) * sc);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
     const float mb_ = m_new * sc;
     float psum = 0.f;
-    // The probabilities enter the second product as a bf16 pair hi + lo (lo = the bf16 of what
-    // hi's rounding lost): one bf16 alone carries a relative error of 2^-9 per probability,
-    // enough to move ~30% of the attention outputs to the neighbouring bf16 value.
-    FragA pf[4], pl[4];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        p[v] = exp2f(fmaf(s[kb][v], sc, -mb_));
-        psum += p[v];
+    for (int i = 0; i < 48; ++i) {
+      if (i < 32 && i % 4 == 0) {
+        if (i < 16) load_chunk(k_src, k_dst, i / 4);
+        else load_chunk(v_src, v_dst, i / 4 - 4);
       }
-      // step st = 2*kb + j uses registers 8j .. 8j+7: keys 16*st + 8a + 4h + i  <->  e = 4a + i
+      if (i < 32) {
+        const int st = i >> 3, r = i & 7;
+        if (r < 4 && st < 3) va[(st + 1) & 1][r] = vt_lds[(2 * (st + 1)) * DH + r * 32];
+      }
+      if (i >= 22 && i < 38) {
+        const int q = i - 22, jr = (q & 1) * 8 + (q >> 1);
+        kf[jr] = kt_lds[jr * 64];
+      }
+      if (i < 32) {
+        const int st = i >> 3, r = i & 7, mb = r & 3;
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][mb], __builtin_bit_cast(FragA, (r >> 2) ? pol[st] : poh[st]),
+                                                            acc_o[mb], 0, 0, 0);
+      } else {
+        const int jj = i - 32, kb = jj & 1, ks = jj >> 1, j = kb * 8 + ks;   // the two score blocks alternate
+        if (ks == 0) {
+          f32x16 z;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const __bf16 hi = (__bf16)p[8 * j + e];
-          pf[2 * kb + j][e] = hi;
-          pl[2 * kb + j][e] = (__bf16)(p[8 * j + e] - (float)hi);
+          for (int v = 0; v < 16; ++v) z[v] = 0.f;
+          sc_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], z, 0, 0, 0);
+        } else {
+          sc_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], sc_next[kb], 0, 0, 0);
         }
+      }
+      if (i % 3 == 0) {
+        // probabilities 2pr, 2pr+1 of this lane: register v of block kb, for P^T step 2*kb + v/8
+        const int pr = i / 3;
+        const int x = 2 * pr, kb = x >> 4, v = x & 15, stp = 2 * kb + (v >> 3), e = v & 7;
+        float pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
+        float pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
+        psum += pa + pb;
+        const __bf16 ha = (__bf16)pa, hb = (__bf16)pb;
+        bf16x2 hpk = {ha, hb};
+        bf16x2 lpk = {(__bf16)(pa - (float)ha), (__bf16)(pb - (float)hb)};
+        uint32_t hw = __builtin_bit_cast(uint32_t, hpk), lw = __builtin_bit_cast(uint32_t, lpk);
+        // the empty asm ties these values to this slot: without it the compiler sinks the whole
+        // softmax below the last MFMA, where nothing overlaps it
+        asm volatile("" : "+v"(hw), "+v"(lw), "+v"(psum));
+        pnh[stp][e >> 1] = hw;
+        pnl[stp][e >> 1] = lw;
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -175,17 +261,28 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
     }
-    // O^T += V^T P^T
+    if ((kt_lo + t + 2) * KT > N) mask_tail(kt_lo + t + 1, sc_next);
+  };
+
+  f32x16 s0[2], s1[2];
+  PFrag p0h[4], p0l[4], p1h[4], p1l[4];
 #pragma unroll
-    for (int st = 0; st < 4; ++st) {
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
-        const FragA a = ldsV[(2 * st + (lane >> 5)) * DH + mb * 32 + (lane & 31)];
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[st], acc_o[mb], 0, 0, 0);
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pl[st], acc_o[mb], 0, 0, 0);
-      }
-    }
+    for (int e = 0; e < 4; ++e) { p0h[i][e] = 0u; p0l[i][e] = 0u; }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  scores(ldsK, s0);
+  if ((kt_lo + 1) * KT > N) mask_tail(kt_lo, s0);
+  for (int t = 0; t < T; t += 2) {
+    step(t, s0, s1, p0h, p0l, p1h, p1l);
+    if (t + 1 < T) step(t + 1, s1, s0, p1h, p1l, p0h, p0l);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                            // V(T-1) landed
+  if (T & 1) pv(ldsV + ((T - 1) % R) * TILE_F, p1h, p1l);
+  else pv(ldsV + ((T - 1) % R) * TILE_F, p0h, p0l);
+
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (SPLIT) {
     if (my_row < row_end) {
@@ -270,15 +367,18 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   int tps;
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
   dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
+  const size_t sh = 6 * (size_t)KT * DH * 2;           // K and V rings, three 16 KiB slots each
+  SL_HIP(hipFuncSetAttribute((const void*)attention_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+  SL_HIP(hipFuncSetAttribute((const void*)attention_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
   if (Z == 1) {
-    hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc,
+    hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, sh, s, (const bf16_t*)q, (const bf16_t*)kc,
                        (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, 0, nullptr, nullptr);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)Z * m_upper * H * DH;
-  hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, block, 0, s, (const bf16_t*)q, (const bf16_t*)kc,
+  hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, block, sh, s, (const bf16_t*)q, (const bf16_t*)kc,
                      (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, tps, part_o, part_ml);
   SL_LAUNCH_CHECK();
   hipLaunchKernelGGL(attention_merge_kernel, dim3(m_upper, H), dim3(DH), 0, s, part_o, part_ml, m_dev, m_upper, H, Z,

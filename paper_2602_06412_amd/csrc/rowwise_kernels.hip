@@ -14,13 +14,16 @@ __global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_kernel(const T* __r
                                                                     const int32_t* __restrict__ tokens,
                                                                     const int32_t* __restrict__ active_idx,
                                                                     const int32_t* __restrict__ m_dev, int m_upper,
-                                                                    int d, const T* __restrict__ gain, float eps,
-                                                                    T* __restrict__ x, T* __restrict__ h) {
+                                                                    int d, int vocab, const T* __restrict__ gain,
+                                                                    float eps, T* __restrict__ x, T* __restrict__ h) {
   __shared__ float sh[kRowThreads / 64];
   const int M = min(*m_dev, m_upper);
   const int r = blockIdx.x;
   if (r >= M) return;
-  const T* src = emb + (size_t)tokens[active_idx[r]] * d;
+  // token ids are device data nobody validated: an id outside the table (a caller's mistake, or
+  // an argmax over non-finite logits) must not become an out-of-bounds read
+  const int tok = min(max(tokens[active_idx[r]], 0), vocab - 1);
+  const T* src = emb + (size_t)tok * d;
   float ssq = 0.f;
   for (int c = threadIdx.x; c < d; c += kRowThreads) {
     const T v = src[c];
@@ -179,13 +182,13 @@ __global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
   } while (0)
 
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
-                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h,
-                      int tiled) {
+                      const int32_t* m_dev, int m_upper, int d, int vocab, const void* gain, float eps, void* x,
+                      void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((embed_rmsnorm_kernel<T, TL>), dim3(m_upper),
                                                              dim3(kRowThreads), 0, s, (const T*)emb, tokens,
-                                                             active_idx, m_dev, m_upper, d, (const T*)gain, eps,
-                                                             (T*)x, (T*)h)));
+                                                             active_idx, m_dev, m_upper, d, vocab, (const T*)gain,
+                                                             eps, (T*)x, (T*)h)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

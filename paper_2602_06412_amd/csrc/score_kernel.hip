@@ -140,7 +140,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
     for (int w = 1; w < NT / 64; ++w) acc_merge(t, sh[w]);
     t.S += t.Sc;
     conf[r] = __expf(t.bestv - t.m) / t.S;
-    argmax[r] = t.besti;
+    argmax[r] = t.besti < V ? t.besti : 0;     // a row without any comparable logit (all NaN) still yields a valid id
     kl[r] = FIRST ? INFINITY : fmaxf(0.f, t.W / t.S + log1pf(t.dS / t.S));
   }
 }

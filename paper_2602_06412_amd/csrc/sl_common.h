@@ -161,8 +161,8 @@ int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, 
 // rowwise_kernels.hip
 // `tiled`: write h / a in the fragment-tiled layout (afrag_index) instead of row-major
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
-                      const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* x, void* h,
-                      int tiled);
+                      const int32_t* m_dev, int m_upper, int d, int vocab, const void* gain, float eps, void* x,
+                      void* h, int tiled);
 // delta / qkv / gu may be S k-split partials, `sstride` floats apart; they are summed in split order
 int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
                     const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h, int tiled);

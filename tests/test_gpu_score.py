@@ -100,3 +100,16 @@ def test_score_large_shift_between_rows():
     kl, conf, am = _run(z0, z1, "fp32", np.arange(3), 0)
     want = posterior.kl_rows(posterior.log_softmax(z1), posterior.log_softmax(z0))
     assert np.all(np.isfinite(kl)) and np.allclose(kl, want, rtol=1e-4)
+
+
+def test_score_nan_row_gives_valid_argmax():
+    """A row without a single comparable logit (all NaN) must still yield a token id inside the
+    vocabulary: the id is written into `tokens` by UpdateMASK and indexes the embedding table in
+    the next step.  Finite rows beside it are unaffected."""
+    V, R = 4160, 3
+    z0, z1 = _rows(7, R, V, "fp32", 1.0, 0.1)
+    z1n = z1.copy()
+    z1n[1, :] = np.nan
+    _, _, am = _run(z0, z1n, "fp32", np.arange(R), packed=False)
+    assert 0 <= am[1] < V
+    assert am[0] == int(np.argmax(z1[0])) and am[2] == int(np.argmax(z1[2]))

@@ -250,3 +250,27 @@ def test_m_upper_tight_and_errors():
         assert e.value.status == B.SL_ENOSPC
     finally:
         sess.close()
+
+
+def test_out_of_range_token_ids_are_clamped():
+    """Token ids are device data the library cannot validate on the host; ids outside the
+    vocabulary read the nearest table row instead of memory outside the table."""
+    shape = wl.C1
+    w = weights_to_device(wl.make_weights(shape, seed=1))
+    sess = B.Session(shape, w, 1, 128)
+    try:
+        lock = dev(np.zeros(128, dtype=np.uint8))
+        masked = dev(np.zeros(128, dtype=np.uint8))
+        eps_d = dev(np.array([1e-3], dtype=np.float32))
+        tok = wl.prompt_uniform(3, 128, shape.vocab, shape.mask_id).astype(np.int64)
+        bad, ok = tok.copy(), tok.copy()
+        bad[5], ok[5] = shape.vocab + 12345, shape.vocab - 1
+        bad[9], ok[9] = -3, 0
+        bad[17], ok[17] = 2 ** 31 - 1, shape.vocab - 1
+        sess.step(dev(ok, torch.int32), masked, lock, eps_d, 1, 0, 128, 0, m_upper=128)
+        z_ok = sess.logits_view(1).clone()
+        sess.step(dev(bad, torch.int32), masked, lock, eps_d, 1, 0, 128, 0, m_upper=128)
+        torch.cuda.synchronize()
+        assert torch.equal(z_ok, sess.logits_view(1))
+    finally:
+        sess.close()
