@@ -212,6 +212,7 @@ extern "C" int sl_logits_ptr(const sl_ctx* ctx, int32_t t, void** out) {
 struct Workspace {
   char *x, *h, *q, *o, *a;
   float *f32, *attn;
+  void* score;                      // partial states of rows split over several workgroups
   size_t bytes;
 };
 
@@ -242,6 +243,7 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows, int batch, int n
     const int n_pad = (int)sl_align_up((size_t)n_seq, 64);
     w.attn = (float*)take(slk_attention_scratch_elems(rows, batch, c.n_heads, n_pad) * sizeof(float));
   }
+  w.score = take(slk_score_scratch_bytes());
   w.bytes = off;
   return w;
 }
@@ -333,7 +335,7 @@ extern "C" int sl_score_posteriors(void* stream, const void* logits_cur, int32_t
   if (vocab < 8 || vocab % 8 || m_upper < 0) return SL_EINVAL;
   if ((uintptr_t)logits_cur % 16 || (uintptr_t)logits_prev % 16) return SL_EINVAL;
   return slk_score((hipStream_t)stream, logits_cur, cur_packed, logits_prev, dtype, vocab, active_idx, m_dev, m_upper,
-                   first_step, kl, conf, argmax);
+                   first_step, kl, conf, argmax, nullptr);
 }
 
 extern "C" int sl_unmask_topk(void* stream, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
@@ -430,7 +432,7 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
     SL_RUN(ctx, s, SL_PROF_LM_HEAD, slk_gemm_generic(s, c.dtype, ws.h, ctx->plain.lm_head, m_dev, m_upper, c.vocab, c.d_model, nullptr, cur,
                             active_idx, c.vocab));
   // score -> UpdateMASK -> candidates -> lock
-  SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax));
+  SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax, ws.score));
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
   SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
   return SL_OK;

@@ -52,8 +52,9 @@ int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t
 // ---- UpdateMASK: top-k by confidence inside the current block, one workgroup per sequence --
 // Every eligible row gets the 64-bit key (conf bits << 32) | ~row: keys are distinct, a larger
 // key means more confident, and among equal confidences the lower position (= lower packed
-// row) wins.  The k-th largest key is found by an 8-bit-per-pass radix select over LDS
-// histograms; rows whose key reaches it are unmasked.  Confidences are probabilities
+// row) wins.  The k-th largest key (or a lower bound of it that no unwanted key reaches) is
+// found by an 8-bit-per-pass radix select over LDS histograms; rows whose key reaches it are
+// unmasked.  Confidences are probabilities
 // (non-negative floats), whose bit patterns order like the values.
 __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ tokens, uint8_t* __restrict__ masked,
                                                           const int32_t* __restrict__ active_idx,
@@ -65,7 +66,8 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
   __shared__ int count;
   __shared__ int hist[256];
   __shared__ unsigned long long prefix_sh;
-  __shared__ int want_sh;
+  __shared__ int want_sh, done_sh;
+  __shared__ int wave_tot[4];
   const int b = blockIdx.x, tid = threadIdx.x;
   const int r0 = cu_active[b], r1 = cu_active[b + 1];
   if (tid == 0) count = 0;
@@ -83,28 +85,42 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
   if (n == 0) return;
   unsigned long long thresh = 0;                   // k >= n: everything eligible is taken
   if (k < n) {
-    // radix select of the k-th largest key, most significant byte first
-    if (tid == 0) { prefix_sh = 0; want_sh = k; }
+    // radix select of the k-th largest key, most significant byte first.  Thread b owns bin b:
+    // a suffix sum over the histogram (wave shuffles + the four wave totals) tells each thread
+    // how many keys sit in higher bins; exactly one thread finds the k-th largest in its bin.
+    // Once a bin holds exactly the keys still wanted, every key in it qualifies and the
+    // remaining bytes need not be examined.
+    const int lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { prefix_sh = 0; want_sh = k; done_sh = 0; }
     for (int shift = 56; shift >= 0; shift -= 8) {
       hist[tid] = 0;
       __syncthreads();
       const unsigned long long prefix = prefix_sh;
+      const int want = want_sh;
       const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
       for (int e = tid; e < n; e += 256) {
         const unsigned long long key = keys[e];
         if ((key & himask) == prefix) atomicAdd(&hist[(int)((key >> shift) & 0xff)], 1);
       }
       __syncthreads();
-      if (tid == 0) {
-        int want = want_sh, bin = 255;
-        for (; bin > 0; --bin) {                   // walk down from the largest byte value
-          if (hist[bin] >= want) break;
-          want -= hist[bin];
-        }
-        want_sh = want;
-        prefix_sh = prefix | ((unsigned long long)bin << shift);
+      const int c = hist[tid];
+      int incl = c;                                // keys in bins tid .. 64*wave+63
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_down(incl, o, 64);
+        if (lane + o < 64) incl += y;
+      }
+      if (lane == 0) wave_tot[wave] = incl;
+      __syncthreads();
+      for (int w = wave + 1; w < 4; ++w) incl += wave_tot[w];      // keys in bins >= tid
+      const int above = incl - c;                  // keys in bins > tid
+      if (above < want && want <= incl) {
+        prefix_sh = prefix | ((unsigned long long)tid << shift);
+        want_sh = want - above;
+        if (want - above == c) done_sh = 1;
       }
       __syncthreads();
+      if (done_sh) break;
     }
     thresh = prefix_sh;
   }

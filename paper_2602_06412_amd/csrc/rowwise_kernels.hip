@@ -168,7 +168,200 @@ __global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
   for (int c = threadIdx.x; c < d; c += blockDim.x) dst[(size_t)r * d + c] = src[(size_t)r * d + c];
 }
 
+// ---- bf16 variants with 16-byte accesses ---------------------------------------------------------
+// Same arithmetic, in the same order, as the element-wise kernels above; a thread owns chunks of
+// consecutive columns, so loads and stores are 8 or 16 bytes wide (also in the fragment-tiled
+// layout, where the eight columns starting at a multiple of eight are contiguous) and all loads
+// of a thread are in flight together.  Used when shapes and pointers allow, else the kernels above.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+
+__device__ inline void ld8(const bf16_t* p, float (&v)[8]) {
+  const bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)u[e];
+}
+__device__ inline void st8(bf16_t* p, const float (&v)[8]) {
+  bf16x8_t u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) u[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x8_t*>(p) = u;
+}
+__device__ inline void ld8f(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+constexpr int kMaxChunks = 4;             // chunks of 8 columns per thread: rows up to 8192 columns
+
+template <bool TILED>
+__global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_vec_kernel(
+    const bf16_t* __restrict__ emb, const int32_t* __restrict__ tokens, const int32_t* __restrict__ active_idx,
+    const int32_t* __restrict__ m_dev, int m_upper, int d, int vocab, const bf16_t* __restrict__ gain, float eps,
+    bf16_t* __restrict__ x, bf16_t* __restrict__ h) {
+  __shared__ float sh[kRowThreads / 64];
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.x;
+  if (r >= M) return;
+  const int tok = min(max(tokens[active_idx[r]], 0), vocab - 1);     // see embed_rmsnorm_kernel
+  const bf16_t* src = emb + (size_t)tok * d;
+  const int nch = d >> 3;
+  float v[kMaxChunks][8];
+  float ssq = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c8 = threadIdx.x + j * kRowThreads;
+    if (c8 < nch) {
+      const bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(src + c8 * 8);
+      *reinterpret_cast<bf16x8_t*>(x + (size_t)r * d + c8 * 8) = u;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { v[j][e] = (float)u[e]; ssq += v[j][e] * v[j][e]; }
+    }
+  }
+  ssq = block_sum<kRowThreads>(ssq, sh);
+  const float rstd = 1.0f / sqrtf(ssq / (float)d + eps);
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c8 = threadIdx.x + j * kRowThreads;
+    if (c8 < nch) {
+      float g[8], o[8];
+      ld8(gain + c8 * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = v[j][e] * rstd * g[e];
+      st8(h + act_index<TILED>(r, c8 * 8, d), o);
+    }
+  }
+}
+
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+__device__ inline void ld4(const bf16_t* p, float (&v)[4]) {
+  const bf16x4_t u = *reinterpret_cast<const bf16x4_t*>(p);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = (float)u[e];
+}
+__device__ inline void st4(bf16_t* p, const float (&v)[4]) {
+  bf16x4_t u;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) u[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x4_t*>(p) = u;
+}
+__device__ inline void ld4f(const float* p, float (&v)[4]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+}
+
+template <bool ADD, bool TILED>
+__global__ __launch_bounds__(kRowThreads) void add_rmsnorm_vec_kernel(bf16_t* x, const float* __restrict__ delta, int S,
+                                                                      size_t sstride,
+                                                                      const int32_t* __restrict__ m_dev, int m_upper,
+                                                                      int d, const bf16_t* __restrict__ gain,
+                                                                      float eps, bf16_t* __restrict__ h) {
+  __shared__ float sh[kRowThreads / 64];
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.x;
+  if (r >= M) return;
+  bf16_t* xr = x + (size_t)r * d;
+  const int nch = d >> 3;
+  float v[kMaxChunks][8];
+  float ssq = 0.f;
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c8 = threadIdx.x + j * kRowThreads;
+    if (c8 < nch) {
+      ld8(xr + c8 * 8, v[j]);
+      if (ADD) {
+        const float* dp = delta + (size_t)r * d + c8 * 8;
+        float dl[8];
+        ld8f(dp, dl);
+        for (int sp = 1; sp < S; ++sp) {          // k-split partials, fixed order
+          float pp[8];
+          ld8f(dp + sp * sstride, pp);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dl[e] += pp[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[j][e] = st<bf16_t>::rnd(v[j][e] + dl[e]);
+        st8(xr + c8 * 8, v[j]);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ssq += v[j][e] * v[j][e];
+    }
+  }
+  ssq = block_sum<kRowThreads>(ssq, sh);
+  const float rstd = 1.0f / sqrtf(ssq / (float)d + eps);
+#pragma unroll
+  for (int j = 0; j < kMaxChunks; ++j) {
+    const int c8 = threadIdx.x + j * kRowThreads;
+    if (c8 < nch) {
+      float g[8], o[8];
+      ld8(gain + c8 * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = v[j][e] * rstd * g[e];
+      st8(h + act_index<TILED>(r, c8 * 8, d), o);
+    }
+  }
+}
+
+// Thin-launch variant.  One thread per (head, four rotation pairs): fp32 loads are 16 bytes and
+// those of a wave contiguous, q and K leave as 8-byte stores (consecutive dims
+// of one slot are contiguous in the K layout); V keeps 2-byte stores, its layout puts eight
+// SLOTS side by side, not eight dims.
+__global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __restrict__ qkv, int S, size_t sstride,
+                                                                const int32_t* __restrict__ active_idx,
+                                                                const int32_t* __restrict__ m_dev, int m_upper, int H,
+                                                                int dh, int N, int n_pad,
+                                                                const float2* __restrict__ rope_tab,
+                                                                bf16_t* __restrict__ q, bf16_t* __restrict__ kc,
+                                                                bf16_t* __restrict__ vc) {
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.x;
+  if (r >= M) return;
+  const int g = active_idx[r];
+  const int b = g / N, i = g - b * N;
+  const int half = dh >> 1, hd = H * dh, per_head = half >> 2;
+  const float* row = qkv + (size_t)r * 3 * hd;
+  for (int t = threadIdx.x; t < H * per_head; t += blockDim.x) {
+    const int hh = t / per_head, j = (t - hh * per_head) * 4;
+    const int c0 = hh * dh + j, c1 = c0 + half;
+    float q0[4], q1[4], k0[4], k1[4], v0[4], v1[4], cs0[4], cs1[4];
+    ld4f(row + c0, q0); ld4f(row + c1, q1);
+    ld4f(row + hd + c0, k0); ld4f(row + hd + c1, k1);
+    ld4f(row + 2 * hd + c0, v0); ld4f(row + 2 * hd + c1, v1);
+    const float* tab = reinterpret_cast<const float*>(rope_tab + (size_t)i * half + j);   // (cos, sin) x 4
+    ld4f(tab, cs0); ld4f(tab + 4, cs1);
+    for (int sp = 1; sp < S; ++sp) {                     // k-split partials, fixed order
+      const float* pr = row + sp * sstride;
+      float p[4];
+#define SL_ACC4(dst, src) do { ld4f(src, p); _Pragma("unroll") for (int e = 0; e < 4; ++e) dst[e] += p[e]; } while (0)
+      SL_ACC4(q0, pr + c0); SL_ACC4(q1, pr + c1);
+      SL_ACC4(k0, pr + hd + c0); SL_ACC4(k1, pr + hd + c1);
+      SL_ACC4(v0, pr + 2 * hd + c0); SL_ACC4(v1, pr + 2 * hd + c1);
+#undef SL_ACC4
+    }
+    float qa[4], qb[4], ka[4], kb[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)], sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
+      qa[e] = q0[e] * c - q1[e] * sn;
+      qb[e] = q1[e] * c + q0[e] * sn;
+      ka[e] = k0[e] * c - k1[e] * sn;
+      kb[e] = k1[e] * c + k0[e] * sn;
+    }
+    st4(q + (size_t)r * hd + c0, qa);
+    st4(q + (size_t)r * hd + c1, qb);
+    const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
+    st4(kc + head_base + kc_index(i, j, dh), ka);
+    st4(kc + head_base + kc_index(i, j + half, dh), kb);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vc[head_base + vc_index(i, j + e, dh)] = (bf16_t)v0[e];
+      vc[head_base + vc_index(i, j + half + e, dh)] = (bf16_t)v1[e];
+    }
+  }
+}
+
 // ---- launchers ---------------------------------------------------------------------------------
+static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
 #define DISPATCH_T(dtype, ...)                                  \
   do {                                                          \
     if ((dtype) == SL_BF16) { using T = bf16_t; __VA_ARGS__; }  \
@@ -185,6 +378,13 @@ int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* 
                       const int32_t* m_dev, int m_upper, int d, int vocab, const void* gain, float eps, void* x,
                       void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
+  if (dtype == SL_BF16 && d % 8 == 0 && d <= 8 * kRowThreads * kMaxChunks && al16(emb) && al16(gain) && al16(x) && al16(h)) {
+    DISPATCH_TILED(tiled, hipLaunchKernelGGL((embed_rmsnorm_vec_kernel<TL>), dim3(m_upper), dim3(kRowThreads), 0, s,
+                                             (const bf16_t*)emb, tokens, active_idx, m_dev, m_upper, d, vocab,
+                                             (const bf16_t*)gain, eps, (bf16_t*)x, (bf16_t*)h));
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((embed_rmsnorm_kernel<T, TL>), dim3(m_upper),
                                                              dim3(kRowThreads), 0, s, (const T*)emb, tokens,
                                                              active_idx, m_dev, m_upper, d, vocab, (const T*)gain,
@@ -196,6 +396,14 @@ int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* 
 int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
                     const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
+  if (dtype == SL_BF16 && d % 8 == 0 && d <= 8 * kRowThreads * kMaxChunks && sstride % 4 == 0 && al16(x) && al16(delta) &&
+      al16(gain) && al16(h)) {
+    DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_vec_kernel<true, TL>), dim3(m_upper), dim3(kRowThreads), 0, s,
+                                             (bf16_t*)x, delta, S, sstride, m_dev, m_upper, d, (const bf16_t*)gain,
+                                             eps, (bf16_t*)h));
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_kernel<T, true, TL>), dim3(m_upper),
                                                              dim3(kRowThreads), 0, s, (T*)x, delta, S, sstride,
                                                              m_dev, m_upper, d, (const T*)gain, eps, (T*)h)));
@@ -206,6 +414,13 @@ int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d, const void* gain,
                 float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
+  if (dtype == SL_BF16 && d % 8 == 0 && d <= 8 * kRowThreads * kMaxChunks && al16(x) && al16(gain) && al16(h)) {
+    DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_vec_kernel<false, TL>), dim3(m_upper), dim3(kRowThreads), 0, s,
+                                             (bf16_t*)const_cast<void*>(x), (const float*)nullptr, 1, (size_t)0, m_dev,
+                                             m_upper, d, (const bf16_t*)gain, eps, (bf16_t*)h));
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_kernel<T, false, TL>), dim3(m_upper),
                                                              dim3(kRowThreads), 0, s, (T*)const_cast<void*>(x),
                                                              (const float*)nullptr, 1, (size_t)0, m_dev, m_upper, d,
@@ -226,6 +441,14 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
                       const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc,
                       void* vc) {
   if (m_upper <= 0) return SL_OK;
+  // thin launches are latency-bound (wide accesses, few instructions win); thick ones are bound by the
+  // scattered 2-byte V stores, where the element-wise kernel's many threads per row do better
+  if (m_upper <= 256 && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
+    hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
+                       m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_kernel<T>), dim3(m_upper), dim3(256), 0, s, qkv, S, sstride,
                                        active_idx, m_dev, m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (T*)q, (T*)kc,
                                        (T*)vc));

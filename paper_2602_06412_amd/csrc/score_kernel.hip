@@ -62,7 +62,8 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ m_dev, int m_upper,
                                                                float* __restrict__ kl, float* __restrict__ conf,
-                                                               int32_t* __restrict__ argmax) {
+                                                               int32_t* __restrict__ argmax, int parts,
+                                                               ScoreAcc* __restrict__ partial) {
   constexpr int E = st<T>::kVec;
   const int M = min(*m_dev, m_upper);
   const int r = blockIdx.x;
@@ -71,7 +72,9 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
   const T* a_row = cur + (size_t)(cur_packed ? r : g) * V;
   const T* b_row = prev + (size_t)g * V;
   ScoreAcc acc{-INFINITY, 0.f, 0.f, 0.f, 0.f, -INFINITY, 0x7fffffff};
-  const int n_chunks = V / E;
+  // blockIdx.y = which of `parts` equal shares of the row this workgroup streams
+  const int c_lo = (int)((long long)(V / E) * blockIdx.y / parts);
+  const int n_chunks = (int)((long long)(V / E) * (blockIdx.y + 1) / parts);
   auto consume = [&](const float (&a)[E], const float (&b)[E], int c) {
     float cm = a[0];
 #pragma unroll
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
     acc.S = t;
   };
   // two chunks per trip so that four 16-byte loads are in flight per thread
-  int c = threadIdx.x;
+  int c = c_lo + threadIdx.x;
   for (; c + NT < n_chunks; c += 2 * NT) {
     float a0[E], b0[E], a1[E], b1[E];
     chunk_io<T>::load(a_row + (size_t)c * E, a0);
@@ -139,42 +142,89 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
 #pragma unroll
     for (int w = 1; w < NT / 64; ++w) acc_merge(t, sh[w]);
     t.S += t.Sc;
+    t.Sc = 0.f;
+    if (parts > 1) {                             // score_merge_kernel finishes the row
+      partial[(size_t)r * parts + blockIdx.y] = t;
+      return;
+    }
     conf[r] = __expf(t.bestv - t.m) / t.S;
     argmax[r] = t.besti < V ? t.besti : 0;     // a row without any comparable logit (all NaN) still yields a valid id
     kl[r] = FIRST ? INFINITY : fmaxf(0.f, t.W / t.S + log1pf(t.dS / t.S));
   }
 }
 
+// Thin launches: a row is ~0.5 MB, and with fewer rows than CUs one workgroup per row leaves
+// most of the chip idle.  Each row is then streamed by `parts` workgroups and this kernel merges
+// their partial states in part order (one thread per row).
+template <bool FIRST>
+__global__ void score_merge_kernel(const ScoreAcc* __restrict__ partial, int parts, const int32_t* __restrict__ m_dev,
+                                   int m_upper, int V, float* __restrict__ kl, float* __restrict__ conf,
+                                   int32_t* __restrict__ argmax) {
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= M) return;
+  ScoreAcc t = partial[(size_t)r * parts];
+  for (int q = 1; q < parts; ++q) acc_merge(t, partial[(size_t)r * parts + q]);
+  conf[r] = __expf(t.bestv - t.m) / t.S;
+  argmax[r] = t.besti < V ? t.besti : 0;
+  kl[r] = FIRST ? INFINITY : fmaxf(0.f, t.W / t.S + log1pf(t.dS / t.S));
+}
+
 template <typename T, int NT>
 static int launch_score_nt(hipStream_t s, const void* cur, int cur_packed, const void* prev, int V,
                            const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl,
-                           float* conf, int32_t* argmax) {
-  dim3 grid(m_upper), block(NT);
+                           float* conf, int32_t* argmax, int parts, ScoreAcc* partial) {
+  dim3 grid(m_upper, parts), block(NT);
   if (first_step)
     hipLaunchKernelGGL((score_kernel<T, true, NT>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)cur, V,
-                       active_idx, m_dev, m_upper, kl, conf, argmax);
+                       active_idx, m_dev, m_upper, kl, conf, argmax, parts, partial);
   else
     hipLaunchKernelGGL((score_kernel<T, false, NT>), grid, block, 0, s, (const T*)cur, cur_packed, (const T*)prev, V,
-                       active_idx, m_dev, m_upper, kl, conf, argmax);
+                       active_idx, m_dev, m_upper, kl, conf, argmax, parts, partial);
   SL_LAUNCH_CHECK();
+  if (parts > 1) {
+    if (first_step)
+      hipLaunchKernelGGL(score_merge_kernel<true>, dim3(sl_cdiv(m_upper, 64)), dim3(64), 0, s, partial, parts, m_dev,
+                         m_upper, V, kl, conf, argmax);
+    else
+      hipLaunchKernelGGL(score_merge_kernel<false>, dim3(sl_cdiv(m_upper, 64)), dim3(64), 0, s, partial, parts, m_dev,
+                         m_upper, V, kl, conf, argmax);
+    SL_LAUNCH_CHECK();
+  }
   return SL_OK;
 }
+
+// Rows per launch at or below which a row is split (needs the caller's scratch), and how far.
+int slk_score_parts(int m_upper, int V) {
+  if (m_upper > 128 || V < 65536) return 1;
+  int parts = sl_cdiv(512, m_upper);
+  return parts > 16 ? 16 : parts;
+}
+size_t slk_score_scratch_bytes() { return (size_t)128 * 16 * sizeof(ScoreAcc); }
 
 template <typename T>
 static int launch_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int V,
                         const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl,
-                        float* conf, int32_t* argmax) {
+                        float* conf, int32_t* argmax, void* scratch) {
   if (m_upper <= 0) return SL_OK;
+  const int parts = scratch ? slk_score_parts(m_upper, V) : 1;
+  if (parts > 1)
+    return launch_score_nt<T, 256>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf,
+                                   argmax, parts, (ScoreAcc*)scratch);
   if (m_upper <= 512 && V >= 16384)
     return launch_score_nt<T, 1024>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf,
-                                    argmax);
-  return launch_score_nt<T, 256>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
+                                    argmax, 1, nullptr);
+  return launch_score_nt<T, 256>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax,
+                                 1, nullptr);
 }
 
+// scratch: slk_score_scratch_bytes() of device memory, or null (rows are then never split)
 int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int dtype, int V,
               const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step, float* kl, float* conf,
-              int32_t* argmax) {
+              int32_t* argmax, void* scratch) {
   if (dtype == SL_BF16)
-    return launch_score<bf16_t>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
-  return launch_score<float>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax);
+    return launch_score<bf16_t>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax,
+                                scratch);
+  return launch_score<float>(s, cur, cur_packed, prev, V, active_idx, m_dev, m_upper, first_step, kl, conf, argmax,
+                             scratch);
 }

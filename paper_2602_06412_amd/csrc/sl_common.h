@@ -157,7 +157,8 @@ int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, con
 // score_kernel.hip
 int slk_score(hipStream_t s, const void* cur, int cur_packed, const void* prev, int dtype, int V,
               const int32_t* active_idx, const int32_t* m_dev, int m_upper, int first_step,
-              float* kl, float* conf, int32_t* argmax);
+              float* kl, float* conf, int32_t* argmax, void* scratch);
+size_t slk_score_scratch_bytes();
 // rowwise_kernels.hip
 // `tiled`: write h / a in the fragment-tiled layout (afrag_index) instead of row-major
 int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* tokens, const int32_t* active_idx,
