@@ -336,13 +336,15 @@ __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __res
   o[afrag_index(row, hh * DH + dd, H * DH)] = (bf16_t)(num / den);
 }
 
-// Key-split plan for a launch bounded by m_upper rows: split while fewer than ~2 workgroups
-// per CU would run.  Returns Z (1 = no split) and the tiles per split.
+// Key-split plan for a launch bounded by m_upper rows.  One workgroup occupies a CU (LDS rings,
+// 390 registers per lane), so the keys are split just far enough to give every CU one workgroup;
+// splitting further only adds partial-result traffic and a second round of workgroups.
+// Returns Z (1 = no split) and the tiles per split.
 int slk_attention_splits(int m_upper, int B, int H, int n_pad, int* tiles_per_split) {
   const int n_tiles = n_pad / KT;
   const int blocks = (sl_cdiv(m_upper, QT) + B - 1) * H;
-  int Z = 1;
-  if (blocks < 256) Z = sl_cdiv(512, blocks);
+  int Z = 256 / blocks;
+  if (Z < 1) Z = 1;
   if (Z > n_tiles) Z = n_tiles;
   const int tps = sl_cdiv(n_tiles, Z);
   *tiles_per_split = tps;

@@ -17,7 +17,6 @@
 //  * Workgroup ids are mapped so that all M-tiles of one weight slab run back to back on
 //    the same XCD (ids are dealt round-robin over the 8 XCDs), i.e. re-reads hit that L2.
 #include "sl_common.h"
-#include <stdlib.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -50,7 +49,7 @@ int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_
 // ---- the kernel ----------------------------------------------------------------------------
 // OUT = 0: fp32 partials Cf[split][row][n] (ldc = n, split stride = m_upper * n)
 // OUT = 1: bf16 rows Cb[row_map ? row_map[row] : row][n] (no split-k)
-template <int BM, int WNB, int OUT, int DBG = 0>
+template <int BM, int WNB, int OUT>
 __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
@@ -168,14 +167,14 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
   // direct-to-LDS loads must have landed (vmcnt) before the barrier that publishes them.
   const int last = ktiles - 1;
   for (int kt = 0; kt < ktiles; kt += 2) {
-    if (DBG != 1 && DBG != 6) load_b(kt + 1, b1);
-    if (DBG != 1 && DBG != 5) load_a(kt + 1, stage1);
+    load_b(kt + 1, b1);
+    load_a(kt + 1, stage1);
     compute(stage0, b0);
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load issued so far has landed
     __syncthreads();
     const int nk = kt + 2 < ktiles ? kt + 2 : last;
-    if (DBG != 1 && DBG != 6) load_b(nk, b0);
-    if (DBG != 1 && DBG != 5) load_a(nk, stage0);
+    load_b(nk, b0);
+    load_a(nk, stage0);
     compute(stage1, b1);
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): every load issued so far has landed
     __syncthreads();
@@ -202,6 +201,137 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
       }
     }
   }
+}
+
+// ---- thin launches (at most 32 rows; the kernel itself handles 32 MB): a pure weight stream ------------------------------------
+// Below ~300 rows the projection is bound by reading the weights once (2 n k bytes), so the only
+// thing that matters is keeping enough loads in flight.  Here every wave streams its own 64
+// columns with no LDS and no barrier: operand fragments go global -> registers, DEPTH k-steps
+// (16 deep each) ahead of the MFMAs that consume them, in a register ring the compiler tracks
+// load by load (vmcnt(n) waits, never a drain).  The activation fragments (1 KiB per 32 rows and
+// k-step) are fetched by all four waves of a workgroup; they are a few hundred KB in total and
+// stay in L1/L2, while the weights come from HBM exactly once.
+template <int MB, int OUT>
+__global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
+    const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
+    const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_n) {
+  constexpr int DEPTH = 8;
+  const int M = min(*m_dev, m_upper);
+  const int tn = blockIdx.x;
+  if (tn >= tiles_n || M <= 0) return;
+  const int n0 = tn * 256;
+  const int kbeg = blockIdx.y * k_per_split;
+  const int ksteps = k_per_split / 16;                 // a multiple of DEPTH
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int K16 = k / 16, NB32 = n / 32;
+
+  const Frag* bp[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    int nb = n0 / 32 + wave * 2 + i;
+    nb = nb < NB32 ? nb : NB32 - 1;                    // column tail: load something valid, never stored
+    bp[i] = reinterpret_cast<const Frag*>(Wp) + ((size_t)nb * K16 + kbeg / 16) * 64 + lane;
+  }
+  // activation fragment of row block mb at k-step s: tiled -> one contiguous 1 KiB block,
+  // row-major -> 16 bytes from row (lane % 32), columns 16 s + 8 (lane / 32) ..
+  const bf16_t* ap[MB];
+  size_t a_step;                                       // elements between consecutive k-steps
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    if (a_tiled) {
+      int mbg = mb;
+      const int mb_last = (m_upper + 31) / 32 - 1;
+      mbg = mbg < mb_last ? mbg : mb_last;
+      ap[mb] = A + (((size_t)mbg * K16 + kbeg / 16) * 64 + lane) * 8;
+    } else {
+      int row = mb * 32 + (lane & 31);
+      row = row < m_upper ? row : m_upper - 1;
+      ap[mb] = A + (size_t)row * k + kbeg + (lane >> 5) * 8;
+    }
+  }
+  a_step = a_tiled ? 512 : 16;
+
+  f32x16 acc[MB][2];
+#pragma unroll
+  for (int a = 0; a < MB; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  // The loads are issued as inline assembly and waited for with explicit vmcnt counts: left to
+  // the compiler, loads that cross the loop's back edge are drained (vmcnt(0)) at the top of
+  // every trip, which empties the pipeline DEPTH k-steps at a time.  Loads return in order and
+  // each k-step issues 2 + MB of them, so the operands of a step have landed once at most
+  // (DEPTH-1)(2+MB) younger loads are outstanding.  The waits name the registers they release,
+  // which keeps the MFMAs behind them.
+  Frag fa[DEPTH][MB], fb[DEPTH][2];
+  auto fetch = [&](int step, int slot) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
+  };
+  auto landed = [&](int slot) {
+    if (MB == 1)
+      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]) : "n"((DEPTH - 1) * 3));
+    else
+      asm volatile("s_waitcnt vmcnt(%4)"
+                   : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]), "+v"(fa[slot][MB - 1])
+                   : "n"((DEPTH - 1) * 4));
+  };
+#pragma unroll
+  for (int u = 0; u < DEPTH; ++u) fetch(u, u);
+  const int last = ksteps - 1;
+  for (int s0 = 0; s0 < ksteps; s0 += DEPTH) {
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+      landed(u);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][mb], fb[u][i], acc[mb][i], 0, 0, 0);
+      const int nx = s0 + u + DEPTH;                   // past the end: re-fetch the last step (never used)
+      fetch(nx < ksteps ? nx : last, u);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the unused tail re-fetches
+
+  const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
+      if (row >= M) continue;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int col = n0 + (wave * 2 + i) * 32 + col_in;
+        if (col >= n) continue;
+        if (OUT == 0) {
+          Cf[((size_t)blockIdx.y * m_upper + row) * ldc + col] = acc[mb][i][v];
+        } else {
+          const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
+          Cb[orow * ldc + col] = (bf16_t)acc[mb][i][v];
+        }
+      }
+    }
+  }
+}
+
+template <int MB, int OUT>
+static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                         int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  const int tiles_n = sl_cdiv(n, 256);
+  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, a_tiled,
+                     (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
 }
 
 // ---- host side ------------------------------------------------------------------------------
@@ -252,13 +382,13 @@ static GemmPlan gemm_plan(int mu, int n, int k) {
 
 int slk_gemm_splits(int mu, int n, int k) { return gemm_plan(mu, n, k).splits; }
 
-template <int BM, int WNB, int OUT, int DBG = 0>
+template <int BM, int WNB, int OUT>
 static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                        int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   constexpr int BN = 128 * WNB;
   const int tiles_m = sl_cdiv(mu, BM), tiles_n = sl_cdiv(n, BN);
   const size_t sh = 0;
-  auto kern = gemm_mfma_kernel<BM, WNB, OUT, DBG>;
+  auto kern = gemm_mfma_kernel<BM, WNB, OUT>;
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(256);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
                      (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
@@ -277,24 +407,16 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
 #define GO(BM)                                                                                             \
   return Cf ? launch_gemm<BM, 2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
             : launch_gemm<BM, 2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  static const int dbg = getenv("SL_GEMM_DBG") ? atoi(getenv("SL_GEMM_DBG")) : 0;
-  if (dbg == 1 && Cf) return launch_gemm<128, 2, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 2 && Cf) return launch_gemm<128, 2, 0, 2>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 5 && Cf) return launch_gemm<128, 2, 0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 6 && Cf) return launch_gemm<128, 2, 0, 6>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 3 && Cf) return launch_gemm<256, 2, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 4 && Cf) return launch_gemm<256, 2, 0, 2>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  static const int thick = getenv("SL_GEMM_THICK") ? atoi(getenv("SL_GEMM_THICK")) : -1;   // tuning aid
   if (mu > 128 && k / splits >= 256) {
     const GemmPlan plan = gemm_plan(mu, n, k);
-    const bool use256 = thick >= 0 ? thick != 0 : (plan.splits == splits ? plan.thick256 != 0 : true);
+    const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
     if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
   }
-  static const int force_bm = getenv("SL_GEMM_BM") ? atoi(getenv("SL_GEMM_BM")) : 0;   // tuning aid
-  if (force_bm == 32) { GO(32); }
-  if (force_bm == 64) { GO(64); }
-  if (force_bm == 128) { GO(128); }
-  if (force_bm == 256) { GO(256); }
+  // at most 32 rows: the barrier-free weight stream (measured a few per cent ahead of the LDS kernel
+  // there, behind it at 64 rows)
+  if (mu <= 32 && (k / splits) % 128 == 0)
+    return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+              : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
   const int bm = pick_bm(mu);
   if (bm == 32) { GO(32); }
   if (bm == 64) { GO(64); }

@@ -18,7 +18,6 @@
 // Operand fragments land in LDS in MFMA operand order (activation rows gathered 32 x 16 per
 // instruction, pre-tiled weights copied linearly), so LDS reads are conflict-free.
 #include "sl_common.h"
-#include <stdlib.h>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -28,7 +27,7 @@ constexpr int BK2 = 32;                   // k per stage: two MFMA k-steps
 constexpr int TILE = 256;
 constexpr int STAGE = 32 * 64;            // Frag elements per stage: 16 A + 16 B fragments (32 KiB)
 
-template <int OUT, int NS, int DBG = 0>
+template <int OUT, int NS>
 __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
@@ -87,7 +86,6 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
                  : "memory", "m0");
   };
   auto issue = [&](int kt, int st) {
-    if (DBG == 1 || DBG == 6 || DBG == 7) return;
     kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
     Frag* sa = lds + st * STAGE + (wave * 2) * 64;
     Frag* sb = lds + st * STAGE + 16 * 64 + (wave * 2) * 64;
@@ -95,9 +93,8 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const Frag* bp = Wf + (size_t)kt * 128 + b_off;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      if (DBG == 5) dma16(Ab + (size_t)(kt * 4 + kb) * 512 + lane * 8, sa + kb * 64);   // contiguous 1 KiB (wrong data)
-      else if (DBG != 3) dma16(ap + kb * a_kb_stride, sa + kb * 64);
-      if (DBG != 4) dma16(bp + kb * 64, sb + kb * 64);
+      dma16(ap + kb * a_kb_stride, sa + kb * 64);
+      dma16(bp + kb * 64, sb + kb * 64);
     }
   };
 
@@ -156,13 +153,13 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const int st_prev = st == 0 ? NS - 1 : st - 1;
     const int st_next = st == NS - 1 ? 0 : st + 1;
     issue(kt + NS - 1, st_prev);
-    if (DBG != 7) read_frags(st, 1, a1, b1);
+    read_frags(st, 1, a1, b1);
     mma(a0, b0);
     SL_INTERLEAVE();
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
-    if (DBG != 6 && DBG != 7) __syncthreads();        // ... and so has everyone else's
-    if (DBG != 7) read_frags(st_next, 0, a0, b0);
+    __syncthreads();                                  // ... and so has everyone else's
+    read_frags(st_next, 0, a0, b0);
     mma(a1, b1);
     SL_INTERLEAVE();
     __builtin_amdgcn_sched_barrier(0);
@@ -195,12 +192,12 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
 
 
 
-template <int OUT, int NS, int DBG = 0>
+template <int OUT, int NS>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                      int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
   const size_t sh = (size_t)NS * STAGE * 16;
-  auto kern = gemm_mfma256_kernel<OUT, NS, DBG>;
+  auto kern = gemm_mfma256_kernel<OUT, NS>;
   SL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
@@ -215,19 +212,6 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   if (splits < 1 || n % 32 || k % (BK2 * splits) || k / (BK2 * splits) < 8) return SL_EINVAL;
   if (!Cf && splits != 1) return SL_EINVAL;
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
-  static const int ns = getenv("SL_GEMM256_NS") ? atoi(getenv("SL_GEMM256_NS")) : 5;      // tuning aid
-  static const int dbg = getenv("SL_GEMM256_DBG") ? atoi(getenv("SL_GEMM256_DBG")) : 0;
-  if (dbg == 1 && Cf) return launch256<0, 5, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 6 && Cf) return launch256<0, 5, 6>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 7 && Cf) return launch256<0, 5, 7>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 3 && Cf) return launch256<0, 5, 3>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 4 && Cf) return launch256<0, 5, 4>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (dbg == 5 && Cf) return launch256<0, 5, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-#define GO256(NS)                                                                                  \
-  return Cf ? launch256<0, NS>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)         \
-            : launch256<1, NS>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  if (ns == 3) { GO256(3); }
-  if (ns == 4) { GO256(4); }
-  GO256(5);
-#undef GO256
+  return Cf ? launch256<0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+            : launch256<1, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
 }
