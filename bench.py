@@ -27,7 +27,7 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
 # WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
 # the copy-kernel calibration given there), keyed by M.
-LM_HEAD_TRAFFIC_BYTES = {1024: 1832467661, 16: 1044180070}
+LM_HEAD_TRAFFIC_BYTES = {1024: 1832454553, 16: 1044635443}
 
 
 def main():
@@ -150,7 +150,7 @@ def main():
     else:
         bytes_ = lm_w_bytes + 2 * M0 * d + 2 * M0 * V
         ach = bytes_ / (lm_ms * 1e-3) / 1e9
-        roof = {"kernel": "gemm_mfma_kernel<1> (LM head weight stream, M=%d)" % M0, "bound": "hbm",
+        roof = {"kernel": "thin-launch GEMM (LM head weight stream, M=%d)" % M0, "bound": "hbm",
                 "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": round(ach * 1e9 / HBM_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
                 "launch_ms": round(lm_ms, 4), "algorithmic_bytes_per_launch": bytes_}
