@@ -57,6 +57,9 @@ typedef struct sl_config {
   int32_t mask_id;      /* token id of [MASK] (only used for validation)                */
   float rms_eps;
   float rope_theta;
+  int32_t candidates_pre_update; /* 0: Alg. 1 as printed, UpdateMASK precedes the candidate line, so a
+                                  * position unmasked at step t may lock at step t; 1: candidates
+                                  * are taken from the unmasked set as it was BEFORE UpdateMASK    */
 } sl_config;
 
 /* Plain weights, caller-owned device memory of type T, `[out_features, in_features]`

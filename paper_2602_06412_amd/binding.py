@@ -17,7 +17,7 @@ class sl_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_head", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
                 ("dtype", C.c_int32), ("mask_id", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("candidates_pre_update", C.c_int32)]
 
 
 class sl_layer_weights(C.Structure):
@@ -110,10 +110,10 @@ def dtype_code(dt):
     return {torch.float32: SL_F32, torch.bfloat16: SL_BF16}[dt]
 
 
-def make_config(shape):
+def make_config(shape, candidates_pre_update=0):
     return sl_config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab,
                      {"fp32": SL_F32, "bf16": SL_BF16}[shape.storage], shape.mask_id, shape.rms_eps,
-                     shape.rope_theta)
+                     shape.rope_theta, int(candidates_pre_update))
 
 
 # ---- entry points, same names as the header -------------------------------------------------
@@ -276,11 +276,11 @@ class Session:
     """Owns the torch buffers a context needs (packed weights, K/V cache, posterior store,
     workspace, per-step outputs) and forwards to the entry points above."""
 
-    def __init__(self, shape, weights, batch, n_seq, device="cuda:0"):
+    def __init__(self, shape, weights, batch, n_seq, device="cuda:0", candidates_pre_update=False):
         self.shape, self.B, self.N, self.device = shape, batch, n_seq, torch.device(device)
         self.weights = weights
         self.T = {"fp32": torch.float32, "bf16": torch.bfloat16}[shape.storage]
-        self.ctx = sl_init(make_config(shape))
+        self.ctx = sl_init(make_config(shape, candidates_pre_update))
         dev = self.device
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
         self.packed = u8(sl_packed_weights_bytes(self.ctx))

@@ -27,6 +27,7 @@ static bool cfg_ok(const sl_config* c) {
   if (c->vocab % 8 || c->d_model % 8 || c->d_ff % 8) return false;
   if (c->mask_id < 0 || c->mask_id >= c->vocab) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return false;
+  if (c->candidates_pre_update != 0 && c->candidates_pre_update != 1) return false;
   return true;
 }
 
@@ -433,7 +434,12 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
                             active_idx, c.vocab));
   // score -> UpdateMASK -> candidates -> lock
   SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax, ws.score));
+  // (with candidates_pre_update the lock rule simply runs first: it then sees `masked` as it
+  // was before UpdateMASK, and neither kernel reads what the other writes)
+  if (c.candidates_pre_update)
+    SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
-  SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
+  if (!c.candidates_pre_update)
+    SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
   return SL_OK;
 }

@@ -25,7 +25,7 @@ from tests.trajectory import near_tie_in_topk, run_oracle, unmask_is_valid
 pytestmark = pytest.mark.gpu
 
 
-def _check_traj(shape, steps, sess, eps, strict_decisions):
+def _check_traj(shape, steps, sess, eps, strict_decisions, pre_update=False):
     Bn, N, V = sess.B, sess.N, shape.vocab
     T = sess.T
     eps_d = dev(np.asarray(eps, dtype=np.float32))
@@ -69,7 +69,8 @@ def _check_traj(shape, steps, sess, eps, strict_decisions):
             r0, r1 = st.cu_active[b], st.cu_active[b + 1]
             pos = st.active_idx[r0:r1] - b * N
             control.update_mask(want_msk[b], want_tok[b], pos, conf[r0:r1], am[r0:r1], lo, hi, k)
-            F = control.lock_rule(st.lock_in[b], want_msk[b], pos, kl[r0:r1].astype(np.float32), np.zeros(r1 - r0),
+            F = control.lock_rule(st.lock_in[b], st.masked_in[b] if pre_update else want_msk[b], pos,
+                                  kl[r0:r1].astype(np.float32), np.zeros(r1 - r0),
                                   np.float32(eps[b]), st.t == 1)
             want_lock[b, F] = 1
         assert np.array_equal(tokens.cpu().numpy().reshape(Bn, N), want_tok), f"t={st.t}"
@@ -147,6 +148,25 @@ def test_c1_tiny_fp32_full_run():
     finally:
         sess.close()
     _decisions_on_oracle_logits(shape, steps, eps)
+
+
+def test_c1_candidates_from_pre_update_mask():
+    """The other reading of the candidate line (Alg. 1 prints UpdateMASK first; Sec. 2.1 can be read
+    as 'unmasked before this step'): config switch in the library, flag in the oracle; the whole
+    config-1 trajectory must agree, and it must differ from the literal reading's."""
+    shape = wl.C1
+    w = wl.make_weights(shape, seed=1)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    prompts = [wl.prompt_uniform(7, 32, shape.vocab, shape.mask_id)]
+    eps = [1e-3]
+    steps = run_oracle(cfg, w64, prompts, 96, 32, 96, eps, candidates_pre_update=True)
+    literal = run_oracle(cfg, w64, prompts, 96, 32, 96, eps)
+    assert any(not np.array_equal(a.lock_out, b.lock_out) for a, b in zip(steps, literal))
+    sess = B.Session(shape, weights_to_device(w), 1, 128, candidates_pre_update=True)
+    try:
+        _check_traj(shape, steps, sess, eps, strict_decisions=True, pre_update=True)
+    finally:
+        sess.close()
 
 
 def test_c1_lock_disabled_is_full_recompute():
