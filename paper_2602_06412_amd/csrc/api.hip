@@ -286,7 +286,7 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, L.ffn_norm, c.rms_eps, ws.h, 0));
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_gate, m_dev, mu, dff, d, ws.f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_generic(s, dt, ws.h, L.w_up, m_dev, mu, dff, d, ws.f32 + dff, nullptr, nullptr, 2 * (size_t)dff));
-    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a, 0));
+    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, dt, ws.f32, 1, 0, m_dev, mu, dff, ws.a, 0, 0));
     SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_generic(s, dt, ws.a, L.w_down, m_dev, mu, d, dff, ws.f32, nullptr, nullptr, d));
     SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, dt, ws.x, ws.f32, 1, 0, m_dev, mu, d, next_gain, c.rms_eps, ws.h, 0));
   }
@@ -379,7 +379,7 @@ extern "C" int sl_linear_pack(void* stream, const void* w, int32_t n, int32_t k,
   if (!w || !packed || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
   if ((uintptr_t)w % 16 || (uintptr_t)packed % 16) return SL_EINVAL;
   if (packed_bytes < (size_t)n * k * 2) return SL_ENOSPC;
-  return slk_pack_weight((hipStream_t)stream, w, n, k, packed, 0);
+  return slk_pack_weight((hipStream_t)stream, w, n, k, packed, 0, 1);
 }
 
 extern "C" int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k) {

@@ -27,21 +27,24 @@ typedef bf16x8 Frag;        // one lane's 16-byte share of an MFMA operand fragm
 
 // ---- weight pre-tiling -------------------------------------------------------------------
 // One thread moves one 16-byte chunk W[nrow][k8*8 .. k8*8+7] to its fragment slot.
-__global__ void pack_weight_kernel(const bf16_t* __restrict__ W, int n, int k, bf16_t* __restrict__ P, int nb_off) {
+__global__ void pack_weight_kernel(const bf16_t* __restrict__ W, int n, int k, bf16_t* __restrict__ P, int nb_off,
+                                   int nb_stride) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int k8n = k / 8;
   if (t >= (size_t)n * k8n) return;
   const int row = t / k8n, k8 = t - (size_t)row * k8n;
-  const int nb = row / 32 + nb_off, kb = k8 / 2;
+  const int nb = (row / 32) * nb_stride + nb_off, kb = k8 / 2;
   const int lane = (row & 31) + 32 * (k8 & 1);
   const uint4 v = *reinterpret_cast<const uint4*>(W + (size_t)row * k + (size_t)k8 * 8);
   reinterpret_cast<uint4*>(P)[((size_t)nb * (k / 16) + kb) * 64 + lane] = v;
 }
 
-int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off) {
+// 32-row block j of W becomes column block j * nb_stride + nb_off of the packed matrix (several
+// matrices can share one packed matrix side by side or interleaved).
+int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off, int nb_stride) {
   const size_t chunks = (size_t)n * (k / 8);
   hipLaunchKernelGGL(pack_weight_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, (const bf16_t*)W, n,
-                     k, (bf16_t*)P, nb_off);
+                     k, (bf16_t*)P, nb_off, nb_stride);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -340,7 +343,7 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
 // Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
-//  * thin launches (mu <= 128) are weight-stream bound: one BM x 256 tile per 256 columns, k
+//  * thin launches (mu <= 64) are weight-stream bound: one BM x 256 tile per 256 columns, k
 //    split until there are about two workgroups per CU, with the fp32 partial traffic capped
 //    at a fraction of the weight bytes (k >= 32*S*mu);
 //  * thick launches pick, by a small cost model calibrated on measured launches, between the
@@ -354,7 +357,7 @@ struct GemmPlan {
 };
 static GemmPlan gemm_plan(int mu, int n, int k) {
   GemmPlan p{0, 1};
-  if (mu <= 128) {
+  if (mu <= 64) {
     const int tiles = sl_cdiv(n, 256);
     int s = 1;
     while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
@@ -381,6 +384,13 @@ static GemmPlan gemm_plan(int mu, int n, int k) {
 }
 
 int slk_gemm_splits(int mu, int n, int k) { return gemm_plan(mu, n, k).splits; }
+// 1 if the launch plan for (mu, n, k) is the 256 x 256 ring kernel without a k-split (the only
+// form whose epilogue can apply SwiGLU to finished sums)
+int slk_gemm_unsplit_thick(int mu, int n, int k) {
+  if (mu <= 64 || k < 256) return 0;
+  const GemmPlan p = gemm_plan(mu, n, k);
+  return p.thick256 && p.splits == 1;
+}
 
 template <int BM, int WNB, int OUT>
 static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
@@ -407,7 +417,7 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
 #define GO(BM)                                                                                             \
   return Cf ? launch_gemm<BM, 2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
             : launch_gemm<BM, 2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  if (mu > 128 && k / splits >= 256) {
+  if (mu > 64 && k / splits >= 256) {
     const GemmPlan plan = gemm_plan(mu, n, k);
     const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
     if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);

@@ -175,6 +175,16 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     for (int v = 0; v < 16; ++v) {
       const int row = m0 + wm * 128 + mb * 32 + 8 * (v / 4) + row_in + (v % 4);
       if (row >= M) continue;
+      if (OUT == 2) {
+        // columns are gate/up interleaved by 32-column blocks: this thread's two accumulators are
+        // gate column c and up column c of the same row; n = 2 d_ff, ldc = d_ff
+        const int c = (n0 / 64 + wn) * 32 + col_in;
+        if (c < (n >> 1)) {
+          const float g = acc[mb][0][v], u = acc[mb][1][v];
+          Cb[afrag_index(row, c, (int)ldc)] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+        }
+        continue;
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int col = n0 + (wn * 2 + i) * 32 + col_in;
@@ -214,4 +224,13 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   return Cf ? launch256<0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
             : launch256<1, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
+}
+
+int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
+                            void* a) {
+  if (mu <= 0) return SL_OK;
+  const int n = 2 * dff;
+  if (dff % 32 || k % BK2 || k / BK2 < 8) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  return launch256<2, 5>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
 }

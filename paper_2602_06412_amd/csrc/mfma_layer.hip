@@ -40,16 +40,18 @@ int sl_mfma_pack_all(sl_ctx* ctx, hipStream_t s, void* packed) {
   for (int l = 0; l < c.n_layers; ++l) {
     const sl_layer_weights& L = ctx->layers[l];
     char* lb = base + (size_t)l * p.layer_bytes;
-    SL_TRY(slk_pack_weight(s, L.wq, hd, d, lb + p.qkv, 0));
-    SL_TRY(slk_pack_weight(s, L.wk, hd, d, lb + p.qkv, hd / 32));
-    SL_TRY(slk_pack_weight(s, L.wv, hd, d, lb + p.qkv, 2 * hd / 32));
-    SL_TRY(slk_pack_weight(s, L.wo, d, hd, lb + p.wo, 0));
-    SL_TRY(slk_pack_weight(s, L.w_gate, dff, d, lb + p.wgu, 0));
-    SL_TRY(slk_pack_weight(s, L.w_up, dff, d, lb + p.wgu, dff / 32));
-    SL_TRY(slk_pack_weight(s, L.w_down, d, dff, lb + p.wdown, 0));
+    SL_TRY(slk_pack_weight(s, L.wq, hd, d, lb + p.qkv, 0, 1));
+    SL_TRY(slk_pack_weight(s, L.wk, hd, d, lb + p.qkv, hd / 32, 1));
+    SL_TRY(slk_pack_weight(s, L.wv, hd, d, lb + p.qkv, 2 * hd / 32, 1));
+    SL_TRY(slk_pack_weight(s, L.wo, d, hd, lb + p.wo, 0, 1));
+    // gate and up interleaved by 32-column blocks (gate j, up j, gate j+1, ..): the thread that holds
+    // gate column c of a row also holds up column c, so SwiGLU can run in the GEMM epilogue
+    SL_TRY(slk_pack_weight(s, L.w_gate, dff, d, lb + p.wgu, 0, 2));
+    SL_TRY(slk_pack_weight(s, L.w_up, dff, d, lb + p.wgu, 1, 2));
+    SL_TRY(slk_pack_weight(s, L.w_down, d, dff, lb + p.wdown, 0, 1));
     ctx->packed[l] = sl_packed_layer{lb + p.qkv, lb + p.wo, lb + p.wgu, lb + p.wdown};
   }
-  SL_TRY(slk_pack_weight(s, ctx->plain.lm_head, c.vocab, d, base + p.lm_head, 0));
+  SL_TRY(slk_pack_weight(s, ctx->plain.lm_head, c.vocab, d, base + p.lm_head, 0, 1));
   ctx->packed_lm_head = base + p.lm_head;
   return SL_OK;
 }
@@ -91,9 +93,13 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   S = slk_gemm_splits(mu, d, hd);
   SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, 1, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
   SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
-  S = slk_gemm_splits(mu, 2 * dff, d);
-  SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
-  SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1));
+  if (slk_gemm_unsplit_thick(mu, 2 * dff, d)) {
+    SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma256_swiglu(s, h, P.wgu, m_dev, mu, dff, d, a));
+  } else {
+    S = slk_gemm_splits(mu, 2 * dff, d);
+    SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
+    SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1, 1));
+  }
   S = slk_gemm_splits(mu, d, dff);
   SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, 1, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
   SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h, 1));

@@ -122,19 +122,23 @@ __global__ void rope_table_kernel(float2* tab, int n_pad, int half, int dh, doub
   tab[t] = make_float2((float)cos(ang), (float)sin(ang));
 }
 
+// gu holds gate and up side by side ([gate dff | up dff], interleaved = 0) or interleaved by
+// 32-column blocks (gate j, up j, gate j+1, .., interleaved = 1).
 template <typename T, bool TILED>
 __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ gu, int S, size_t sstride,
                                                      const int32_t* __restrict__ m_dev, int m_upper, int dff,
-                                                     T* __restrict__ a) {
+                                                     int interleaved, T* __restrict__ a) {
   const int M = min(*m_dev, m_upper);
   const int r = blockIdx.y;
   if (r >= M) return;
   const int c = blockIdx.x * blockDim.x + threadIdx.x;
   if (c >= dff) return;
-  float g = gu[(size_t)r * 2 * dff + c], u = gu[(size_t)r * 2 * dff + dff + c];
+  const size_t gi = (size_t)r * 2 * dff + (interleaved ? (c >> 5) * 64 + (c & 31) : c);
+  const size_t ui = gi + (interleaved ? 32 : dff);
+  float g = gu[gi], u = gu[ui];
   for (int sp = 1; sp < S; ++sp) {
-    g += gu[sp * sstride + (size_t)r * 2 * dff + c];
-    u += gu[sp * sstride + (size_t)r * 2 * dff + dff + c];
+    g += gu[sp * sstride + gi];
+    u += gu[sp * sstride + ui];
   }
   st<T>::stv(a + act_index<TILED>(r, c, dff), g / (1.0f + expf(-g)) * u);
 }
@@ -457,11 +461,11 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
 }
 
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
-               int dff, void* a, int tiled) {
+               int dff, void* a, int tiled, int interleaved) {
   if (m_upper <= 0) return SL_OK;
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((swiglu_kernel<T, TL>), dim3(sl_cdiv(dff, 256), m_upper),
                                                              dim3(256), 0, s, gu, S, sstride, m_dev, m_upper, dff,
-                                                             (T*)a)));
+                                                             interleaved, (T*)a)));
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

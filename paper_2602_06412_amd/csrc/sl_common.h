@@ -173,7 +173,7 @@ int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta);
 int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
                       const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
-               int dff, void* a, int tiled);
+               int dff, void* a, int tiled, int interleaved);
 int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
                 void* k_out, void* v_out);
 int slk_fill_zero(hipStream_t s, void* p, size_t bytes);
@@ -187,7 +187,12 @@ int slk_attention_generic(hipStream_t s, int dtype, const void* q, const void* k
                           int H, int dh, int N, int n_pad, void* o);
 
 // gemm_mfma.hip
-int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off);
+int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off, int nb_stride);
+int slk_gemm_unsplit_thick(int mu, int n, int k);
+// gate|up projection with interleaved 32-column blocks (gate j, up j, gate j+1, ..) and SwiGLU in the
+// epilogue: a[row, c] = silu(g) * u as bf16 in the fragment-tiled layout; no k-split
+int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
+                            void* a);
 int slk_gemm_splits(int mu, int n, int k);
 // a_tiled: A is in the fragment-tiled layout (rows padded to 32) instead of row-major
 int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
