@@ -93,13 +93,18 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
 
   // a 16 KiB tile is a straight copy: 16 chunks of 1 KiB, four per wave, lane L's 16 bytes land at
   // chunk base + 16 L
-  auto load_chunk = [&](const FragA* g, FragA* l, int c) {
-    const int chunk = wave * 4 + c;
-    const uint32_t laddr = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) FragA*)(l + chunk * 64));
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+  // Addressing is scalar except for one per-lane byte offset: the tile pointer g is uniform
+  // (instruction form "vgpr offset + sgpr base"), and the LDS destination is a scalar sum on the
+  // wave's LDS base, read once.  l is a slot of the K or V ring, given as its index into lds.
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) FragA*)(lds + wave * 4 * 64));
+  const uint32_t lane_voff = (uint32_t)((wave * 4 * 64 + lane) * 16);
+  auto load_chunk = [&](const FragA* g, const FragA* l, int c) {
+    const uint32_t laddr = lds_wave + (uint32_t)((l - lds) + c * 64) * 16u;
+    const uint64_t gbase = (uint64_t)(uintptr_t)g + (uint64_t)(c * 1024);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(g + chunk * 64 + lane), "s"(laddr)
+                 : "v"(lane_voff), "s"(gbase), "s"(laddr)
                  : "memory", "m0");
   };
   auto load_tile = [&](const FragA* g, FragA* l) {

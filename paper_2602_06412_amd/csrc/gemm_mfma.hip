@@ -355,7 +355,10 @@ struct GemmPlan {
   int thick256;   // 1: gemm_mfma256_kernel
   int splits;
 };
-static GemmPlan gemm_plan(int mu, int n, int k) {
+// swiglu_consumer: the output is the gate|up pair that SwiGLU consumes; an unsplit launch of the
+// 256 x 256 kernel then writes bf16 activations from its epilogue, every other plan writes fp32
+// planes that a second kernel reads back.
+static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
   GemmPlan p{0, 1};
   if (mu <= 64) {
     const int tiles = sl_cdiv(n, 256);
@@ -372,7 +375,9 @@ static GemmPlan gemm_plan(int mu, int n, int k) {
     if (k % (2 * BK * s)) break;
     const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
     if (k / (32 * s) >= 8) {
-      const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 + traffic_us;
+      const double fused_us = (double)mu * n / 5.0e6;      // bf16 activations of half the width, written once
+      const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 +
+                       (swiglu_consumer && s == 1 ? fused_us : traffic_us);
       if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
     }
     if (k / (BK * s) >= 4) {
@@ -388,9 +393,11 @@ int slk_gemm_splits(int mu, int n, int k) { return gemm_plan(mu, n, k).splits; }
 // form whose epilogue can apply SwiGLU to finished sums)
 int slk_gemm_unsplit_thick(int mu, int n, int k) {
   if (mu <= 64 || k < 256) return 0;
-  const GemmPlan p = gemm_plan(mu, n, k);
+  const GemmPlan p = gemm_plan(mu, n, k, true);
   return p.thick256 && p.splits == 1;
 }
+// split count of the gate|up projection when it is NOT fused with SwiGLU
+int slk_gemm_splits_gate_up(int mu, int n, int k) { return gemm_plan(mu, n, k, true).splits; }
 
 template <int BM, int WNB, int OUT>
 static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,

@@ -77,26 +77,32 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // would collapse the ring to a depth of one.  Here the code itself guarantees, with explicit
   // vmcnt waits and the barrier, that a stage is read only after its loads have landed.
   // The hardware writes lane L's 16 bytes at M0 + 16*L.
-  auto dma16 = [&](const void* gptr, Frag* lptr) {
-    const uint32_t laddr =
-        __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)lptr);
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gptr), "s"(laddr)
-                 : "memory", "m0");
-  };
+  // Addressing is split so that almost all of it is scalar work: the per-lane part of a global
+  // address is a 32-bit byte offset computed once, the per-tile part a 64-bit scalar base
+  // (instruction form "vgpr offset + sgpr base"), and the LDS destination a scalar sum on a
+  // base read once per wave.
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)(lds + (wave * 2) * 64));
+  const uint32_t a_voff0 = a_off * 2u, a_voff1 = a_voff0 + (uint32_t)a_kb_stride * 2u;   // bytes
+  const uint32_t b_voff0 = b_off * 16u, b_voff1 = b_voff0 + 1024u;
+  const uint64_t a_base = (uint64_t)(uintptr_t)Ab, b_base = (uint64_t)(uintptr_t)Wf;
+  const uint32_t a_kt_bytes = (uint32_t)a_kt_stride * 2u;
+  // (no immediate offsets: an instruction offset would be added to the LDS address as well)
+#define SL_DMA(voff, sbase, m0val)                                                              \
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"                    \
+               :                                                                                \
+               : "v"(voff), "s"(sbase), "s"(m0val)                                              \
+               : "memory", "m0")
   auto issue = [&](int kt, int st) {
     kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
-    Frag* sa = lds + st * STAGE + (wave * 2) * 64;
-    Frag* sb = lds + st * STAGE + 16 * 64 + (wave * 2) * 64;
-    const bf16_t* ap = Ab + (size_t)kt * a_kt_stride + a_off;
-    const Frag* bp = Wf + (size_t)kt * 128 + b_off;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      dma16(ap + kb * a_kb_stride, sa + kb * 64);
-      dma16(bp + kb * 64, sb + kb * 64);
-    }
+    const uint32_t la = lds_wave + (uint32_t)(st * STAGE) * 16u, lb = la + 16u * 64u * 16u;
+    const uint64_t ga = a_base + (uint64_t)kt * a_kt_bytes, gb = b_base + (uint64_t)kt * (128u * 16u);
+    SL_DMA(a_voff0, ga, la);
+    SL_DMA(b_voff0, gb, lb);
+    SL_DMA(a_voff1, ga, la + 1024u);
+    SL_DMA(b_voff1, gb, lb + 1024u);
   };
+#undef SL_DMA
 
   f32x16 acc[4][2];
 #pragma unroll

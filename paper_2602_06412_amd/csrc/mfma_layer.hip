@@ -64,7 +64,12 @@ size_t sl_mfma_f32_elems(const sl_config* c, int rows) {
   size_t best = 0;
   for (int mu = 1; mu <= rows; ++mu)
     for (auto& sh : shapes) {
-      const size_t e = (size_t)slk_gemm_splits(mu, sh[0], sh[1]) * mu * sh[0];
+      int S = slk_gemm_splits(mu, sh[0], sh[1]);
+      if (sh[0] == 2 * dff) {                        // the gate|up launch follows its own plan
+        const int Sg = slk_gemm_splits_gate_up(mu, sh[0], sh[1]);
+        S = Sg > S ? Sg : S;
+      }
+      const size_t e = (size_t)S * mu * sh[0];
       if (e > best) best = e;
     }
   return best;
@@ -96,7 +101,7 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   if (slk_gemm_unsplit_thick(mu, 2 * dff, d)) {
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma256_swiglu(s, h, P.wgu, m_dev, mu, dff, d, a));
   } else {
-    S = slk_gemm_splits(mu, 2 * dff, d);
+    S = slk_gemm_splits_gate_up(mu, 2 * dff, d);
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1, 1));
   }
