@@ -212,8 +212,8 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
  * (((r/32)*(k/16) + c/16)*64 + r%32 + 32*((c%16)/8))*8 + c%8); splits = 0
  * picks the k-split count (query it with sl_linear_splits); exactly one of
  *   y_f32  [splits][m_upper][n] fp32 partial sums (caller adds the splits), or
- *   y_bf16 [*, n] bf16 rows, row r written to row row_map[r] (row_map may be null; splits
- *          must resolve to 1: pass splits = 1)
+ *   y_bf16 [*, n] bf16 rows (16-byte aligned), row r written to row row_map[r] (row_map may
+ *          be null; splits must resolve to 1: pass splits = 1)
  * must be non-null. */
 int sl_linear_pack(void *stream, const void *w, int32_t n, int32_t k, void *packed, size_t packed_bytes);
 int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k);

@@ -392,7 +392,7 @@ extern "C" int sl_linear_forward(void* stream, const void* x, int32_t x_tiled, c
                                  const int32_t* row_map) {
   if (!x || !packed || !m_dev || m_upper < 0 || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
   if ((y_f32 == nullptr) == (y_bf16 == nullptr)) return SL_EINVAL;
-  if ((uintptr_t)x % 16 || (uintptr_t)packed % 16) return SL_EINVAL;
+  if ((uintptr_t)x % 16 || (uintptr_t)packed % 16 || (uintptr_t)y_bf16 % 16) return SL_EINVAL;
   if (splits == 0) splits = y_f32 ? slk_gemm_splits(m_upper, n, k) : 1;
   if (splits < 1 || k % (64 * splits) || (y_bf16 && splits != 1)) return SL_EINVAL;
   return slk_gemm_mfma((hipStream_t)stream, x, x_tiled ? 1 : 0, packed, m_dev, m_upper, n, k, splits, y_f32, y_bf16, row_map, n);

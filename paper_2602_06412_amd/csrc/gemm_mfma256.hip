@@ -175,22 +175,70 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
 #undef SL_WAIT_RING
 
   const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+  if (OUT == 1) {
+    // bf16 rows: an accumulator lane owns one column, so direct stores would be 2 bytes wide
+    // (64-byte runs).  The ring is drained, so each wave stages its 128 x 64 sub-tile in LDS as
+    // bf16 (row stride 144 bytes: the two half-waves of a write, four rows apart, hit disjoint
+    // banks) and writes it out as 16-byte stores, eight lanes per 128-byte row segment.
+    __syncthreads();                                  // every wave is done reading operand stages
+    constexpr int RS = 72;                            // bf16 elements per staged row
+    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) stage[r * RS + i * 32 + col_in] = (bf16_t)acc[mb][i][v];
+      }
+    // same-wave LDS traffic is ordered; no barrier needed between a wave's writes and its reads
+    const int chunk = lane & 7, rsub = lane >> 3;
+    const int col = n0 + wn * 64 + chunk * 8;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int r = it * 8 + rsub;
+      const int row = m0 + wm * 128 + r;
+      const Frag val = *reinterpret_cast<const Frag*>(stage + r * RS + chunk * 8);
+      if (row < M && col < n) {
+        const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
+        *reinterpret_cast<Frag*>(Cb + orow * ldc + col) = val;
+      }
+    }
+    return;
+  }
+  if (OUT == 2) {
+    // columns are gate/up interleaved by 32-column blocks: a thread's two accumulators are gate
+    // column c and up column c of the same row (n = 2 d_ff, ldc = d_ff).  silu(g) * u is staged
+    // per wave as a 128 x 32 bf16 block and leaves as 16-byte stores: eight consecutive columns
+    // of a row are contiguous in the fragment-tiled layout.
+    __syncthreads();
+    constexpr int RS = 40;
+    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
+        const float g = acc[mb][0][v], u = acc[mb][1][v];
+        stage[r * RS + col_in] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+      }
+    const int chunk = lane & 3, rsub = lane >> 2;
+    const int c = (n0 / 64 + wn) * 32 + chunk * 8;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int r = it * 16 + rsub;
+      const int row = m0 + wm * 128 + r;
+      const Frag val = *reinterpret_cast<const Frag*>(stage + r * RS + chunk * 8);
+      if (row < M && c < (n >> 1)) *reinterpret_cast<Frag*>(Cb + afrag_index(row, c, (int)ldc)) = val;
+    }
+    return;
+  }
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int row = m0 + wm * 128 + mb * 32 + 8 * (v / 4) + row_in + (v % 4);
       if (row >= M) continue;
-      if (OUT == 2) {
-        // columns are gate/up interleaved by 32-column blocks: this thread's two accumulators are
-        // gate column c and up column c of the same row; n = 2 d_ff, ldc = d_ff
-        const int c = (n0 / 64 + wn) * 32 + col_in;
-        if (c < (n >> 1)) {
-          const float g = acc[mb][0][v], u = acc[mb][1][v];
-          Cb[afrag_index(row, c, (int)ldc)] = (bf16_t)(g / (1.0f + expf(-g)) * u);
-        }
-        continue;
-      }
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int col = n0 + (wn * 2 + i) * 32 + col_in;
