@@ -60,6 +60,9 @@ typedef struct sl_config {
   int32_t candidates_pre_update; /* 0: Alg. 1 as printed, UpdateMASK precedes the candidate line, so a
                                   * position unmasked at step t may lock at step t; 1: candidates
                                   * are taken from the unmasked set as it was BEFORE UpdateMASK    */
+  float gate_percentile;         /* 0: the optional confidence gate of the lock rule is off (the
+                                  * step then uses sl_lock_rule); m in (0, 100]: the step uses
+                                  * sl_lock_rule_gated with this m (Sec. 2.2)                      */
 } sl_config;
 
 /* Plain weights, caller-owned device memory of type T, `[out_features, in_features]`
@@ -193,6 +196,18 @@ int sl_lock_rule(void *stream, const uint8_t *lock, const uint8_t *masked,
                  const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
                  const float *kl, const float *eps, int32_t batch, int32_t n_seq,
                  int32_t first_step, uint8_t *new_lock);
+
+/* The lock rule with the optional confidence gate (Alg. 1, the percentile line and the lock
+ * line; Sec. 2.2): per sequence, theta = the gate_percentile-th percentile of u = 1 - conf over
+ * the candidates Z_t, by nearest rank (the ceil(m n / 100)-th smallest of the n values, at least
+ * the first; ties at theta pass); F_t = {i in Z_t : u_i <= theta and D_i <= eps_b}.
+ * u is formed in fp32 as max(0, 1 - conf).  gate_percentile in (0, 100].  conf [>= m_upper] and
+ * cu_active [batch + 1] as the step or sl_score_posteriors / sl_compact_active produce them;
+ * n_seq <= 15360.  new_lock may alias lock. */
+int sl_lock_rule_gated(void *stream, const uint8_t *lock, const uint8_t *masked,
+                       const int32_t *active_idx, const int32_t *cu_active, int32_t m_upper,
+                       const float *kl, const float *conf, const float *eps, float gate_percentile,
+                       int32_t batch, int32_t n_seq, int32_t first_step, uint8_t *new_lock);
 
 /* lock_test(eps): Alg. 1 from 'Unmasking' to 'Lock' on given logits = score ->
  * UpdateMASK -> candidates -> lock rule, in that order. */

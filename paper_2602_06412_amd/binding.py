@@ -17,7 +17,8 @@ class sl_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("d_head", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
                 ("dtype", C.c_int32), ("mask_id", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("candidates_pre_update", C.c_int32)]
+                ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("candidates_pre_update", C.c_int32),
+                ("gate_percentile", C.c_float)]
 
 
 class sl_layer_weights(C.Structure):
@@ -50,6 +51,7 @@ _SIGS = {
     "sl_score_posteriors": [_P, _P, _I, _P, _I, _I, _P, _P, _I, _I, _P, _P, _P],
     "sl_unmask_topk": [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I],
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
+    "sl_lock_rule_gated": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _I, _I, _I, _P],
     "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
     "sl_linear_splits": [_I, _I, _I],
     "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
@@ -110,10 +112,10 @@ def dtype_code(dt):
     return {torch.float32: SL_F32, torch.bfloat16: SL_BF16}[dt]
 
 
-def make_config(shape, candidates_pre_update=0):
+def make_config(shape, candidates_pre_update=0, gate_percentile=0.0):
     return sl_config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab,
                      {"fp32": SL_F32, "bf16": SL_BF16}[shape.storage], shape.mask_id, shape.rms_eps,
-                     shape.rope_theta, int(candidates_pre_update))
+                     shape.rope_theta, int(candidates_pre_update), float(gate_percentile))
 
 
 # ---- entry points, same names as the header -------------------------------------------------
@@ -217,6 +219,13 @@ def sl_lock_rule(lock, masked, active_idx, m_dev, m_upper, kl, eps, batch, n_seq
                                               _ptr(new_lock)))
 
 
+def sl_lock_rule_gated(lock, masked, active_idx, cu_active, m_upper, kl, conf, eps, gate_percentile, batch, n_seq,
+                       first_step, new_lock):
+    _check("sl_lock_rule_gated", lib().sl_lock_rule_gated(
+        _stream(), _ptr(lock), _ptr(masked), _ptr(active_idx), _ptr(cu_active), m_upper, _ptr(kl), _ptr(conf), _ptr(eps),
+        C.c_float(gate_percentile), batch, n_seq, int(first_step), _ptr(new_lock)))
+
+
 def sl_lock_test(logits_cur, cur_packed, logits_prev, dtype, vocab, tokens, masked, lock, active_idx, cu_active,
                  m_upper, eps, batch, n_seq, first_step, block_lo, block_hi, k, kl, conf, argmax, new_lock):
     _check("sl_lock_test", lib().sl_lock_test(
@@ -276,11 +285,12 @@ class Session:
     """Owns the torch buffers a context needs (packed weights, K/V cache, posterior store,
     workspace, per-step outputs) and forwards to the entry points above."""
 
-    def __init__(self, shape, weights, batch, n_seq, device="cuda:0", candidates_pre_update=False):
+    def __init__(self, shape, weights, batch, n_seq, device="cuda:0", candidates_pre_update=False,
+                 gate_percentile=0.0):
         self.shape, self.B, self.N, self.device = shape, batch, n_seq, torch.device(device)
         self.weights = weights
         self.T = {"fp32": torch.float32, "bf16": torch.bfloat16}[shape.storage]
-        self.ctx = sl_init(make_config(shape, candidates_pre_update))
+        self.ctx = sl_init(make_config(shape, candidates_pre_update, gate_percentile))
         dev = self.device
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
         self.packed = u8(sl_packed_weights_bytes(self.ctx))

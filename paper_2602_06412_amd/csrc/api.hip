@@ -28,6 +28,7 @@ static bool cfg_ok(const sl_config* c) {
   if (c->mask_id < 0 || c->mask_id >= c->vocab) return false;
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return false;
   if (c->candidates_pre_update != 0 && c->candidates_pre_update != 1) return false;
+  if (!(c->gate_percentile >= 0.f) || c->gate_percentile > 100.f) return false;
   return true;
 }
 
@@ -358,6 +359,17 @@ extern "C" int sl_lock_rule(void* stream, const uint8_t* lock, const uint8_t* ma
                        first_step, new_lock);
 }
 
+extern "C" int sl_lock_rule_gated(void* stream, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                                  const int32_t* cu_active, int32_t m_upper, const float* kl, const float* conf,
+                                  const float* eps, float gate_percentile, int32_t batch, int32_t n_seq,
+                                  int32_t first_step, uint8_t* new_lock) {
+  if (!lock || !masked || !active_idx || !cu_active || !kl || !conf || !eps || !new_lock) return SL_EINVAL;
+  if (batch < 1 || n_seq < 1 || m_upper < 0) return SL_EINVAL;
+  if (!(gate_percentile > 0.f) || gate_percentile > 100.f) return SL_EINVAL;
+  return slk_lock_rule_gated((hipStream_t)stream, lock, masked, active_idx, cu_active, m_upper, kl, conf, eps,
+                             gate_percentile, batch, n_seq, first_step, new_lock);
+}
+
 extern "C" int sl_lock_test(void* stream, const void* logits_cur, int32_t cur_packed, const void* logits_prev,
                             int32_t dtype, int32_t vocab, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
                             const int32_t* active_idx, const int32_t* cu_active, int32_t m_upper, const float* eps,
@@ -436,10 +448,14 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax, ws.score));
   // (with candidates_pre_update the lock rule simply runs first: it then sees `masked` as it
   // was before UpdateMASK, and neither kernel reads what the other writes)
-  if (c.candidates_pre_update)
-    SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
+  auto lock_rule = [&]() -> int {
+    if (c.gate_percentile > 0.f)
+      return slk_lock_rule_gated(s, lock, masked, active_idx, cu_active, m_upper, kl, conf, eps, c.gate_percentile, B, N,
+                                 t == 1, new_lock);
+    return slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock);
+  };
+  if (c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
-  if (!c.candidates_pre_update)
-    SL_RUN(ctx, s, SL_PROF_LOCK_RULE, slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock));
+  if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;
 }

@@ -173,3 +173,94 @@ int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, con
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
+
+// ---- lock rule with the confidence gate: theta_b = nearest-rank percentile of u over Z_t -----
+// One workgroup per sequence.  The candidates' u = max(0, 1 - conf) (non-negative floats, whose bit
+// patterns order like the values) are collected in LDS; the rank-th smallest is found by a 4-pass
+// radix select (thread b owns bin b, shuffle prefix sums); then F_t = {u <= theta and D <= eps}.
+__global__ __launch_bounds__(256) void lock_rule_gated_kernel(const uint8_t* lock, const uint8_t* __restrict__ masked,
+                                                              const int32_t* __restrict__ active_idx,
+                                                              const int32_t* __restrict__ cu_active, int m_upper,
+                                                              const float* __restrict__ kl,
+                                                              const float* __restrict__ conf,
+                                                              const float* __restrict__ eps, double gate_m, int N,
+                                                              int first_step, uint8_t* new_lock) {
+  extern __shared__ unsigned int ukeys[];          // [N]
+  __shared__ int count, want_sh, done_sh;
+  __shared__ unsigned int prefix_sh;
+  __shared__ int hist[256];
+  __shared__ int wave_tot[4];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r0 = min(cu_active[b], m_upper), r1 = min(cu_active[b + 1], m_upper);
+  // positions locked before stay locked (threads beyond the row range take no part in the rest)
+  for (int p = tid; p < N; p += 256)
+    if (lock[(size_t)b * N + p]) new_lock[(size_t)b * N + p] = 1;
+  if (tid == 0) count = 0;
+  __syncthreads();
+  if (!first_step) {
+    for (int r = r0 + tid; r < r1; r += 256) {
+      if (masked[active_idx[r]] == 0) {
+        const int slot = atomicAdd(&count, 1);
+        ukeys[slot] = __float_as_uint(fmaxf(0.f, 1.0f - conf[r]));
+      }
+    }
+  }
+  __syncthreads();
+  const int n = count;
+  unsigned int theta = 0;
+  if (n > 0) {
+    int rank = (int)ceil(gate_m * (double)n / 100.0);
+    rank = rank < 1 ? 1 : (rank > n ? n : rank);
+    if (tid == 0) { prefix_sh = 0; want_sh = rank; done_sh = 0; }
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      hist[tid] = 0;
+      __syncthreads();
+      const unsigned int prefix = prefix_sh;
+      const int want = want_sh;
+      const unsigned int himask = shift == 24 ? 0u : (~0u << (shift + 8));
+      for (int e = tid; e < n; e += 256) {
+        const unsigned int key = ukeys[e];
+        if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
+      }
+      __syncthreads();
+      const int c = hist[tid];
+      int incl = c;                                // keys in bins 64*wave .. tid
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += y;
+      }
+      if (lane == 63) wave_tot[wave] = incl;
+      __syncthreads();
+      for (int w = 0; w < wave; ++w) incl += wave_tot[w];      // keys in bins <= tid
+      const int below = incl - c;
+      if (below < want && want <= incl) {
+        // everything in this bin that is still wanted: if that is the whole bin, the bin's largest
+        // possible key is a valid threshold and the remaining bytes need not be examined
+        prefix_sh = prefix | ((unsigned int)tid << shift);
+        want_sh = want - below;
+        if (want - below == c) { prefix_sh = prefix | ((unsigned int)tid << shift) | (shift ? ((1u << shift) - 1u) : 0u); done_sh = 1; }
+      }
+      __syncthreads();
+      if (done_sh) break;
+    }
+    theta = prefix_sh;
+  }
+  for (int r = r0 + tid; r < r1; r += 256) {
+    const int g = active_idx[r];
+    bool F = false;
+    if (!first_step && masked[g] == 0)
+      F = __float_as_uint(fmaxf(0.f, 1.0f - conf[r])) <= theta && kl[r] <= eps[b];
+    new_lock[g] = F ? 1 : 0;
+  }
+}
+
+int slk_lock_rule_gated(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                        const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
+                        float gate_m, int B, int N, int first_step, uint8_t* new_lock) {
+  if ((size_t)N * 4 > 60 * 1024) return SL_EINVAL;
+  hipLaunchKernelGGL(lock_rule_gated_kernel, dim3(B), dim3(256), (size_t)N * 4, s, lock, masked, active_idx, cu_active,
+                     m_upper, kl, conf, eps, (double)gate_m, N, first_step, new_lock);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}

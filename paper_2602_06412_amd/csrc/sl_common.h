@@ -147,6 +147,9 @@ struct sl_ctx {
 
 // ---- kernel launchers (one translation unit each) ------------------------------------------
 // control_kernels.hip
+int slk_lock_rule_gated(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                        const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
+                        float gate_m, int B, int N, int first_step, uint8_t* new_lock);
 int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active);
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
                     const int32_t* cu_active, const float* conf, const int32_t* argmax,

@@ -25,7 +25,7 @@ from tests.trajectory import near_tie_in_topk, run_oracle, unmask_is_valid
 pytestmark = pytest.mark.gpu
 
 
-def _check_traj(shape, steps, sess, eps, strict_decisions, pre_update=False):
+def _check_traj(shape, steps, sess, eps, strict_decisions, pre_update=False, gate_m=None):
     Bn, N, V = sess.B, sess.N, shape.vocab
     T = sess.T
     eps_d = dev(np.asarray(eps, dtype=np.float32))
@@ -70,8 +70,9 @@ def _check_traj(shape, steps, sess, eps, strict_decisions, pre_update=False):
             pos = st.active_idx[r0:r1] - b * N
             control.update_mask(want_msk[b], want_tok[b], pos, conf[r0:r1], am[r0:r1], lo, hi, k)
             F = control.lock_rule(st.lock_in[b], st.masked_in[b] if pre_update else want_msk[b], pos,
-                                  kl[r0:r1].astype(np.float32), np.zeros(r1 - r0),
-                                  np.float32(eps[b]), st.t == 1)
+                                  kl[r0:r1].astype(np.float32),
+                                  np.maximum(np.float32(0), np.float32(1) - conf[r0:r1]).astype(np.float32),
+                                  np.float32(eps[b]), st.t == 1, gate_m=gate_m)
             want_lock[b, F] = 1
         assert np.array_equal(tokens.cpu().numpy().reshape(Bn, N), want_tok), f"t={st.t}"
         assert np.array_equal(masked.cpu().numpy().reshape(Bn, N), want_msk)
@@ -165,6 +166,26 @@ def test_c1_candidates_from_pre_update_mask():
     sess = B.Session(shape, weights_to_device(w), 1, 128, candidates_pre_update=True)
     try:
         _check_traj(shape, steps, sess, eps, strict_decisions=True, pre_update=True)
+    finally:
+        sess.close()
+
+
+def test_c1_with_confidence_gate():
+    """Config 1 with the paper's default gate (only candidates within the 20th percentile of
+    uncertainty may lock): the step's own decisions from its own scores equal the oracle's rule
+    applied to the same scores at every step, and the gate does change the trajectory."""
+    shape = wl.C1
+    w = wl.make_weights(shape, seed=1)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    prompts = [wl.prompt_uniform(7, 32, shape.vocab, shape.mask_id)]
+    eps = [1e-3]
+    ungated = run_oracle(cfg, w64, prompts, 96, 32, 96, eps)
+    steps = run_oracle(cfg, w64, prompts, 96, 32, 96, eps, gate_m=20.0)
+    assert steps[-1].lock_out.sum() > 0
+    assert any(not np.array_equal(a.lock_out, b.lock_out) for a, b in zip(steps, ungated))
+    sess = B.Session(shape, weights_to_device(w), 1, 128, gate_percentile=20.0)
+    try:
+        _check_traj(shape, steps, sess, eps, strict_decisions=False, gate_m=20.0)
     finally:
         sess.close()
 

@@ -31,7 +31,7 @@ class BatchStep:
 
 
 def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, seed=0, keep_states=False,
-               candidates_pre_update=False):
+               candidates_pre_update=False, gate_m=None):
     """prompts: list of B int arrays (same length); eps: list of B thresholds.
     forced_M_end: None -> the KL rule drives the mask; else a list of per-sequence final
     active counts: a seeded priority force-locks eligible rows so M falls linearly, and the
@@ -57,7 +57,7 @@ def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, s
         pre = [(s.tokens.copy(), s.masked.copy(), s.lock.copy()) for s in states]
         recs = [sampler.surelock_step(cfg, w64, states[b], eps[b], lo, hi, k, forced_lock=hooks[b],
                                       kl_drives_lock=forced_M_end is None,
-                                      candidates_pre_update=candidates_pre_update) for b in range(Bn)]
+                                      candidates_pre_update=candidates_pre_update, gate_m=gate_m) for b in range(Bn)]
         idx = np.concatenate([r.active_pos + b * N for b, r in enumerate(recs)])
         cu = np.concatenate([[0], np.cumsum([len(r.active_pos) for r in recs])])
         rule = np.stack([p[2].copy() for p in pre])
