@@ -375,8 +375,9 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
   dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
   const size_t sh = 6 * (size_t)KT * DH * 2;           // K and V rings, three 16 KiB slots each
-  SL_HIP(hipFuncSetAttribute((const void*)attention_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
-  SL_HIP(hipFuncSetAttribute((const void*)attention_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+  static unsigned long long lds_ok[2] = {0, 0};
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[0], attention_mfma_kernel<false>, sh);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[1], attention_mfma_kernel<true>, sh);
   if (Z == 1) {
     hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, sh, s, (const bf16_t*)q, (const bf16_t*)kc,
                        (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, 0, nullptr, nullptr);

@@ -262,7 +262,8 @@ static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
   const size_t sh = (size_t)NS * STAGE * 16;
   auto kern = gemm_mfma256_kernel<OUT, NS>;
-  SL_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh));
+  static unsigned long long lds_ok = 0;              // one per kernel instantiation
+  SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
                      (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);

@@ -101,6 +101,18 @@ extern thread_local int g_sl_last_hip_error;
     }                                                  \
   } while (0)
 #define SL_LAUNCH_CHECK() SL_HIP(hipGetLastError())
+// Raise a kernel's dynamic-LDS limit the first time it is launched on a device (the attribute is
+// per device and function; `done` is a launcher-owned bit mask over device ids; two first calls
+// racing only repeat an idempotent call).  Kept out of the steady-state launch path.
+#define SL_ALLOW_DYNAMIC_LDS(done, kern, bytes)                                                          \
+  do {                                                                                                   \
+    int dev_ = 0;                                                                                        \
+    SL_HIP(hipGetDevice(&dev_));                                                                         \
+    if (dev_ >= 64 || !(((done) >> dev_) & 1ull)) {                                                      \
+      SL_HIP(hipFuncSetAttribute((const void*)(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes))); \
+      if (dev_ < 64) (done) |= 1ull << dev_;                                                             \
+    }                                                                                                    \
+  } while (0)
 #define SL_REQUIRE(cond) do { if (!(cond)) return SL_EINVAL; } while (0)
 
 static inline size_t sl_align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
