@@ -36,10 +36,12 @@ __device__ inline void acc_merge(ScoreAcc& x, const ScoreAcc& y) {
   }
 }
 
+// 16-byte chunks: `raw` is what a load leaves in registers, unpack() turns it into E floats.
 template <typename T> struct chunk_io;
 template <> struct chunk_io<bf16_t> {
-  __device__ static inline void load(const bf16_t* p, float (&v)[8]) {
-    const uint4 u = *reinterpret_cast<const uint4*>(p);
+  typedef uint4 raw;
+  __device__ static inline raw load_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static inline void unpack(const raw& u, float (&v)[8]) {
     v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
     v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
     v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
@@ -47,10 +49,9 @@ template <> struct chunk_io<bf16_t> {
   }
 };
 template <> struct chunk_io<float> {
-  __device__ static inline void load(const float* p, float (&v)[4]) {
-    const float4 u = *reinterpret_cast<const float4*>(p);
-    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
-  }
+  typedef float4 raw;
+  __device__ static inline raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static inline void unpack(const raw& u, float (&v)[4]) { v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w; }
 };
 
 
@@ -75,10 +76,14 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
   // blockIdx.y = which of `parts` equal shares of the row this workgroup streams
   const int c_lo = (int)((long long)(V / E) * blockIdx.y / parts);
   const int n_chunks = (int)((long long)(V / E) * (blockIdx.y + 1) / parts);
+  // Exponentials are taken in base 2 (one fma + v_exp per term): e^{a-m} = 2^{a L - m L}, L = log2 e.
+  // The same expression serves both rows, so equal logits give exactly equal terms and KL(p||p) = 0.
+  constexpr float L2E = 1.4426950408889634f;
   auto consume = [&](const float (&a)[E], const float (&b)[E], int c) {
-    float cm = a[0];
+    float amax = a[0];
 #pragma unroll
-    for (int j = 1; j < E; ++j) cm = fmaxf(cm, a[j]);
+    for (int j = 1; j < E; ++j) amax = fmaxf(amax, a[j]);
+    float cm = amax;
     if (!FIRST) {
 #pragma unroll
       for (int j = 0; j < E; ++j) cm = fmaxf(cm, b[j]);
@@ -88,17 +93,24 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
       acc.S *= f; acc.Sc *= f; acc.dS *= f; acc.W *= f;
       acc.m = cm;
     }
+    if (amax > acc.bestv) {                     // rare after the first chunks; first (lowest) index wins ties
+      int jb = E - 1;
+#pragma unroll
+      for (int j = E - 2; j >= 0; --j) jb = (a[j] == amax) ? j : jb;
+      acc.bestv = amax;
+      acc.besti = c * E + jb;
+    }
+    const float m2 = -acc.m * L2E;
     float cs = 0.f;                             // this chunk's share of S
 #pragma unroll
     for (int j = 0; j < E; ++j) {
-      const float ea = __expf(a[j] - acc.m);
+      const float ea = __builtin_amdgcn_exp2f(fmaf(a[j], L2E, m2));
       cs += ea;
       if (!FIRST) {
-        const float eb = __expf(b[j] - acc.m);
+        const float eb = __builtin_amdgcn_exp2f(fmaf(b[j], L2E, m2));
         acc.dS += eb - ea;
         acc.W = fmaf(ea, a[j] - b[j], acc.W);
       }
-      if (a[j] > acc.bestv) { acc.bestv = a[j]; acc.besti = c * E + j; }
     }
     // S += cs with an error-free two-sum: once a dominant term (e^0 = 1) is in S, plain
     // adds of the many ~1e-8 terms of a peaked posterior would be rounded away
@@ -107,24 +119,28 @@ __global__ __launch_bounds__(NT) void score_kernel(const T* __restrict__ cur, in
     acc.Sc += (acc.S - (t - bp)) + (cs - bp);
     acc.S = t;
   };
-  // two chunks per trip so that four 16-byte loads are in flight per thread
+  // two chunks per trip so that four 16-byte loads are in flight per thread (issuing the next
+  // trip's loads ahead of the arithmetic as well was measured and gained nothing)
+  typedef typename chunk_io<T>::raw Raw;
+  auto eat = [&](const Raw& ra, const Raw& rb, int c) {
+    float a[E], b[E];
+    chunk_io<T>::unpack(ra, a);
+    chunk_io<T>::unpack(FIRST ? ra : rb, b);
+    consume(a, b, c);
+  };
   int c = c_lo + threadIdx.x;
   for (; c + NT < n_chunks; c += 2 * NT) {
-    float a0[E], b0[E], a1[E], b1[E];
-    chunk_io<T>::load(a_row + (size_t)c * E, a0);
-    chunk_io<T>::load(a_row + (size_t)(c + NT) * E, a1);
-    if (!FIRST) {
-      chunk_io<T>::load(b_row + (size_t)c * E, b0);
-      chunk_io<T>::load(b_row + (size_t)(c + NT) * E, b1);
-    }
-    consume(a0, b0, c);
-    consume(a1, b1, c + NT);
+    const Raw a0 = chunk_io<T>::load_raw(a_row + (size_t)c * E);
+    const Raw a1 = chunk_io<T>::load_raw(a_row + (size_t)(c + NT) * E);
+    const Raw b0 = FIRST ? a0 : chunk_io<T>::load_raw(b_row + (size_t)c * E);
+    const Raw b1 = FIRST ? a1 : chunk_io<T>::load_raw(b_row + (size_t)(c + NT) * E);
+    eat(a0, b0, c);
+    eat(a1, b1, c + NT);
   }
   if (c < n_chunks) {
-    float a0[E], b0[E];
-    chunk_io<T>::load(a_row + (size_t)c * E, a0);
-    if (!FIRST) chunk_io<T>::load(b_row + (size_t)c * E, b0);
-    consume(a0, b0, c);
+    const Raw ra = chunk_io<T>::load_raw(a_row + (size_t)c * E);
+    const Raw rb = FIRST ? ra : chunk_io<T>::load_raw(b_row + (size_t)c * E);
+    eat(ra, rb, c);
   }
   // wave reduction, then across the block's waves through LDS
 #pragma unroll
