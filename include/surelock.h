@@ -226,7 +226,7 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
  * multiple of 32 (x_tiled = 1: element (r, c) at
  * (((r/32)*(k/16) + c/16)*64 + r%32 + 32*((c%16)/8))*8 + c%8); splits = 0
  * picks the k-split count (query it with sl_linear_splits); exactly one of
- *   y_f32  [splits][m_upper][n] fp32 partial sums (caller adds the splits), or
+ *   y_f32  [splits][m_upper][n] fp32 partial sums (16-byte aligned; caller adds the splits), or
  *   y_bf16 [*, n] bf16 rows (16-byte aligned), row r written to row row_map[r] (row_map may
  *          be null; splits must resolve to 1: pass splits = 1)
  * must be non-null. */

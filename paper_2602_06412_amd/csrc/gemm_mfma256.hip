@@ -15,13 +15,24 @@
 //    (128 KiB per CU, 32 MiB chip-wide) are in flight while one is multiplied;
 //  * one barrier per k-tile, placed between the two MFMA k-steps, so the LDS reads on either
 //    side of it are covered by MFMAs; fragments are read one k-step ahead.
-// Operand fragments land in LDS in MFMA operand order (activation rows gathered 32 x 16 per
-// instruction, pre-tiled weights copied linearly), so LDS reads are conflict-free.
+// Operands land in LDS as 32 x 16 blocks of 1 KiB (activation rows gathered 32 x 16 per
+// instruction, pre-tiled weights copied linearly): element (r, k) of a block sits in the 16-byte
+// slot (r % 32) + 32 * ((k % 16) / 8).
+//
+// The products are v_mfma_f32_16x16x32_bf16, not 32x32x16: same flops per cycle, but measured
+// on this chip with random operands a loop of 16x16x32 sustains ~1.93 PFLOP/s at ~1.95 GHz where
+// 32x32x16 sustains ~1.65 at ~1.65 GHz (the clock is managed by power, and the deeper dot
+// product moves a quarter of the accumulator data per flop).  A 16 x 32 operand of that
+// instruction (lane l: row l % 16, k = 8 * (l / 16) .. +7) is gathered from two neighbouring
+// 32 x 16 blocks by giving every lane its own slot address; each group of 16 lanes still reads
+// 256 contiguous bytes.  The weight fragment is passed as the first operand, so a lane ends up
+// with four consecutive columns of one output row (16-byte fp32 / 8-byte bf16 pieces).
 #include "sl_common.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef bf16x8 Frag;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK2 = 32;                   // k per stage: two MFMA k-steps
 constexpr int TILE = 256;
@@ -104,92 +115,113 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   };
 #undef SL_DMA
 
-  f32x16 acc[4][2];
+  // acc[a][b]: rows 16a .. 16a+15, columns 16b .. 16b+15 of this wave's 128 x 64 sub-tile; lane l
+  // holds row l % 16, columns 4 * (l / 16) .. +3
+  f32x4 acc[8][4];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < 8; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    for (int b = 0; b < 4; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  Frag a0[4], b0[2], a1[4], b1[2];        // operand fragments of k-step 0 / 1 of the current tile
-  auto read_frags = [&](int st, int kb, Frag (&af)[4], Frag (&bf)[2]) {
-    const Frag* sa = lds + st * STAGE + (wm * 8 + kb) * 64 + lane;          // mb = 4*wm + i
-    const Frag* sb = lds + st * STAGE + 16 * 64 + (wn * 4 + kb) * 64 + lane; // nb = 2*wn + i
-    // in the order the MFMAs consume them: (a0,b0) (a0,b1) (a1,*) (a2,*) (a3,*)
-    bf[0] = sb[0];
-    af[0] = sa[0];
-    bf[1] = sb[2 * 64];
+  // 16 x 32 operand out of the 32 x 16 blocks of a stage: lane l wants row l % 16 and the 8 k of
+  // group g = l / 16, i.e. slot (l % 16) + 32 * (g % 2) of k-block g / 2; a second 16-row half
+  // of a block is 16 slots further on
+  const int frag_lane = (lane >> 5) * 64 + ((lane >> 4) & 1) * 32 + (lane & 15);
+  const Frag* sa0 = lds + wm * 4 * 128 + frag_lane;                 // 32-row block 4*wm + i at i * 128
+  const Frag* sb0 = lds + 16 * 64 + wn * 2 * 128 + frag_lane;       // 32-column block 2*wn + i
+  auto a_frag = [&](int st, int a) { return sa0[st * STAGE + (a >> 1) * 128 + (a & 1) * 16]; };
+  auto b_frag = [&](int st, int b) { return sb0[st * STAGE + (b >> 1) * 128 + (b & 1) * 16]; };
+  // A fragments of rows 0..63 (lo) / 64..127 (hi) of the sub-tile, B fragments of two successive k-tiles
+  Frag a_lo[4], a_hi[4], b_even[4], b_odd[4];
+  // in the order the MFMAs consume them: (a0,b0) (a0,b1) (a0,b2) (a0,b3) (a1,*) ...
+  auto read_tile_head = [&](int st, Frag (&af)[4], Frag (&bf)[4]) {
+    bf[0] = b_frag(st, 0);
+    af[0] = a_frag(st, 0);
 #pragma unroll
-    for (int i = 1; i < 4; ++i) af[i] = sa[(i * 2) * 64];
+    for (int b = 1; b < 4; ++b) bf[b] = b_frag(st, b);
+#pragma unroll
+    for (int a = 1; a < 4; ++a) af[a] = a_frag(st, a);
   };
-  auto mma = [&](const Frag (&af)[4], const Frag (&bf)[2]) {
+  auto read_tile_rest = [&](int st, Frag (&af)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int a = 0; a < 4; ++a) af[a] = a_frag(st, 4 + a);
+  };
+  auto mma = [&](int a_base, const Frag (&af)[4], const Frag (&bf)[4]) {
 #pragma unroll
-      for (int jn = 0; jn < 2; ++jn)
-        acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[jn], acc[i][jn], 0, 0, 0);
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        acc[a_base + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[b], af[a], acc[a_base + a][b], 0, 0, 0);
   };
   // "s_waitcnt vmcnt(4*(NS-2))": all but this wave's newest NS-2 tiles have landed (loads
   // complete in order, 4 per tile per wave)
 #define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (NS - 2)) : "memory")
 
-  // one LDS read slotted behind each of the first six MFMAs of a k-step: the wave's issue slot is
-  // blocked while the MFMA pipe is busy anyway, so the reads issue for free
-#define SL_INTERLEAVE()                                                                    \
+  // NR LDS reads slotted one behind each of the first MFMAs of a group of 16: the wave's issue
+  // slot is blocked while the MFMA pipe is busy anyway, so the reads issue for free
+#define SL_INTERLEAVE(NR)                                                                  \
   do {                                                                                     \
-    _Pragma("unroll") for (int q_ = 0; q_ < 6; ++q_) {                                     \
+    _Pragma("unroll") for (int q_ = 0; q_ < (NR); ++q_) {                                  \
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   \
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
     }                                                                                      \
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                     \
+    __builtin_amdgcn_sched_group_barrier(0x008, 16 - (NR), 0);                             \
   } while (0)
   // prologue: tiles 0 .. NS-2 in flight, tile 0 landed and published, its first fragments read
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t) issue(t, t);
   SL_WAIT_RING();
   __syncthreads();
-  read_frags(0, 0, a0, b0);
+  read_tile_head(0, a_lo, b_even);
 
-  // One k-tile per trip: refill the stage every wave finished reading before the previous
-  // barrier, multiply k-step 0 while reading k-step 1, wait for tile kt+1 and publish it,
-  // multiply k-step 1 while reading the first fragments of tile kt+1.
+  // One k-tile per step: refill the stage every wave finished reading before the previous
+  // barrier, multiply rows 0..63 of the sub-tile while reading the A fragments of rows 64..127,
+  // wait for tile kt+1 and publish it, multiply rows 64..127 while reading the first fragments
+  // of tile kt+1.  B fragments alternate between two register sets, hence two steps per trip.
   int st = 0;                                         // stage of tile kt
-  for (int kt = 0; kt < ktiles; ++kt) {
+  auto step = [&](int kt, Frag (&b_cur)[4], Frag (&b_next)[4]) {
     const int st_prev = st == 0 ? NS - 1 : st - 1;
     const int st_next = st == NS - 1 ? 0 : st + 1;
     issue(kt + NS - 1, st_prev);
-    read_frags(st, 1, a1, b1);
-    mma(a0, b0);
-    SL_INTERLEAVE();
+    read_tile_rest(st, a_hi);
+    mma(0, a_lo, b_cur);
+    SL_INTERLEAVE(4);
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
     __syncthreads();                                  // ... and so has everyone else's
-    read_frags(st_next, 0, a0, b0);
-    mma(a1, b1);
-    SL_INTERLEAVE();
+    read_tile_head(st_next, a_lo, b_next);
+    mma(4, a_hi, b_cur);
+    SL_INTERLEAVE(8);
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
+  };
+  int kt = 0;
+  for (; kt + 1 < ktiles; kt += 2) {
+    step(kt, b_even, b_odd);
+    step(kt + 1, b_odd, b_even);
   }
+  if (kt < ktiles) step(kt, b_even, b_odd);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // drain the (unused) tail re-fetches
 #undef SL_WAIT_RING
+#undef SL_INTERLEAVE
 
-  const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+  const int row_in = lane & 15, col_in = 4 * (lane >> 4);   // this lane's place in a 16 x 16 block
   if (OUT == 1) {
-    // bf16 rows: an accumulator lane owns one column, so direct stores would be 2 bytes wide
-    // (64-byte runs).  The ring is drained, so each wave stages its 128 x 64 sub-tile in LDS as
-    // bf16 (row stride 144 bytes: the two half-waves of a write, four rows apart, hit disjoint
-    // banks) and writes it out as 16-byte stores, eight lanes per 128-byte row segment.
+    // bf16 rows: a lane's piece of a row is 8 bytes, scattered over 16 rows per instruction.  The
+    // ring is drained, so each wave stages its 128 x 64 sub-tile in LDS as bf16 (row stride 144
+    // bytes) with 8-byte writes and sends it out as 16-byte stores, eight lanes per 128-byte
+    // row segment.
     __syncthreads();                                  // every wave is done reading operand stages
     constexpr int RS = 72;                            // bf16 elements per staged row
     bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int a = 0; a < 8; ++a)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
+      for (int b = 0; b < 4; ++b) {
+        bf16x4 v4;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) stage[r * RS + i * 32 + col_in] = (bf16_t)acc[mb][i][v];
+        for (int v = 0; v < 4; ++v) v4[v] = (bf16_t)acc[a][b][v];
+        *reinterpret_cast<bf16x4*>(stage + (a * 16 + row_in) * RS + b * 16 + col_in) = v4;
       }
     // same-wave LDS traffic is ordered; no barrier needed between a wave's writes and its reads
     const int chunk = lane & 7, rsub = lane >> 3;
@@ -207,20 +239,25 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     return;
   }
   if (OUT == 2) {
-    // columns are gate/up interleaved by 32-column blocks: a thread's two accumulators are gate
-    // column c and up column c of the same row (n = 2 d_ff, ldc = d_ff).  silu(g) * u is staged
-    // per wave as a 128 x 32 bf16 block and leaves as 16-byte stores: eight consecutive columns
-    // of a row are contiguous in the fragment-tiled layout.
+    // columns are gate/up interleaved by 32-column blocks: of a wave's 64 columns the first 32
+    // are gate columns c .. c+31 and the last 32 the up columns of the same c (n = 2 d_ff,
+    // ldc = d_ff), so accumulators b and b+2 of a lane pair up.  silu(g) * u is staged per wave
+    // as a 128 x 32 bf16 block and leaves as 16-byte stores: eight consecutive columns of a row
+    // are contiguous in the fragment-tiled layout.
     __syncthreads();
     constexpr int RS = 40;
     bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int a = 0; a < 8; ++a)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
-        const float g = acc[mb][0][v], u = acc[mb][1][v];
-        stage[r * RS + col_in] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+      for (int b = 0; b < 2; ++b) {
+        bf16x4 v4;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float g = acc[a][b][v], u = acc[a][b + 2][v];
+          v4[v] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+        }
+        *reinterpret_cast<bf16x4*>(stage + (a * 16 + row_in) * RS + b * 16 + col_in) = v4;
       }
     const int chunk = lane & 3, rsub = lane >> 2;
     const int c = (n0 / 64 + wn) * 32 + chunk * 8;
@@ -233,28 +270,18 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     }
     return;
   }
+  // fp32 partial plane of this k-split: 16 bytes per lane, 64 contiguous bytes per row
 #pragma unroll
-  for (int mb = 0; mb < 4; ++mb) {
+  for (int a = 0; a < 8; ++a) {
+    const int row = m0 + wm * 128 + a * 16 + row_in;
+    if (row >= M) continue;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = m0 + wm * 128 + mb * 32 + 8 * (v / 4) + row_in + (v % 4);
-      if (row >= M) continue;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int col = n0 + (wn * 2 + i) * 32 + col_in;
-        if (col >= n) continue;
-        if (OUT == 0) {
-          Cf[((size_t)blockIdx.y * m_upper + row) * ldc + col] = acc[mb][i][v];
-        } else {
-          const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
-          Cb[orow * ldc + col] = (bf16_t)acc[mb][i][v];
-        }
-      }
+    for (int b = 0; b < 4; ++b) {
+      const int col = n0 + wn * 64 + b * 16 + col_in;
+      if (col < n) *reinterpret_cast<f32x4*>(Cf + ((size_t)blockIdx.y * m_upper + row) * ldc + col) = acc[a][b];
     }
   }
 }
-
-
 
 template <int OUT, int NS>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
@@ -276,6 +303,7 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   if (mu <= 0) return SL_OK;
   if (splits < 1 || n % 32 || k % (BK2 * splits) || k / (BK2 * splits) < 8) return SL_EINVAL;
   if (!Cf && splits != 1) return SL_EINVAL;
+  if (Cf && ((uintptr_t)Cf % 16 || ldc % 4)) return SL_EINVAL;       // 16-byte fp32 stores
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   return Cf ? launch256<0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
             : launch256<1, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
