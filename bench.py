@@ -27,7 +27,31 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
 # WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
 # the copy-kernel calibration given there), keyed by M.
-LM_HEAD_TRAFFIC_BYTES = {1024: 1832269824, 16: 1044615680}
+LM_HEAD_TRAFFIC_BYTES = {1024: 1832257536, 16: 1044631142}
+
+
+def lm_head_clock_probe(B, torch, w_lm, M, V, d, seed, launches=12):
+    """Shader clock and matrix-pipe occupancy inside the LM-head GEMM, from the library's in-kernel
+    cycle probe (one mid-grid workgroup, last of `launches` back-to-back launches)."""
+    dev = w_lm.device
+    packed = torch.empty_like(w_lm)
+    B.sl_linear_pack(w_lm, packed)
+    g = torch.Generator(device="cpu").manual_seed(seed + 7)
+    x = B.tile_activations(torch.randn(M, d, generator=g).to(torch.bfloat16).to(dev))
+    m_dev = torch.tensor([M], dtype=torch.int32, device=dev)
+    y = torch.empty(M, V, dtype=torch.bfloat16, device=dev)
+    counters = torch.zeros(8, dtype=torch.int64, device=dev)
+    for _ in range(launches):
+        B.sl_linear_clock_probe(x, packed, m_dev, M, V, d, y, counters, x_tiled=1)
+    torch.cuda.synchronize()
+    c = [int(v) for v in counters.cpu()]
+    del packed, y
+    if c[4] <= 0 or c[1] <= 0:
+        return None
+    return {"sclk_mhz_in_k_loop": round(c[1] / c[4] * 100.0, 1),
+            "matrix_pipe_busy_in_k_loop": round(1024.0 * c[7] / c[1], 4),
+            "prologue_us": round(c[3] / 100.0, 2), "k_loop_us": round(c[4] / 100.0, 2),
+            "epilogue_us": round(c[5] / 100.0, 2), "workgroups": c[6], "k_tiles": c[7], "nominal_mhz": 2400}
 
 
 def main():
@@ -154,6 +178,9 @@ def main():
                 "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
                 "frac": round(ach * 1e9 / HBM_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
                 "launch_ms": round(lm_ms, 4), "algorithmic_bytes_per_launch": bytes_}
+
+    if M0 >= 512:
+        roof["clock"] = lm_head_clock_probe(B, torch, w["lm_head"], M0, V, d, args.seed)
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -236,6 +236,20 @@ int sl_linear_forward(void *stream, const void *x, int32_t x_tiled, const void *
                       int32_t m_upper, int32_t n, int32_t k, int32_t splits, float *y_f32, void *y_bf16,
                       const int32_t *row_map);
 
+/* Measurement aid for the roofline of the projections (Sec. 2.4 GEMM terms): the same product as
+ * sl_linear_forward with a bf16 destination, through the thick-M (256 x 256 tile) kernel only
+ * (m_upper >= 65, k >= 256), with one workgroup in the middle of the grid recording into
+ * counters[0..7] (device memory, 8 x int64, written when the kernel finishes; zero them first):
+ *   [0..2] shader-clock cycles of its prologue (first tiles in flight), k loop, epilogue
+ *   [3..5] the same three spans in ticks of the constant 100 MHz counter
+ *   [6]    workgroups in the launch                        [7] k-tiles (32 deep) in the loop
+ * counters[1] / counters[4] * 100 is the shader clock in MHz that the power management grants
+ * under this kernel; 1024 * counters[7] / counters[1] is the matrix pipe's busy fraction in the
+ * loop.  y_bf16 receives the ordinary result.  SL_EINVAL for shapes the thick kernel does not take. */
+int sl_linear_clock_probe(void *stream, const void *x, int32_t x_tiled, const void *w_packed, const int32_t *m_dev,
+                          int32_t m_upper, int32_t n, int32_t k, void *y_bf16, const int32_t *row_map,
+                          int64_t *counters);
+
 /* ---- measurement support ------------------------------------------------------------
  * Per-kernel timing of the step's launches with HIP events on the step's own stream.
  * Between sl_profile_begin and sl_profile_end every kernel the library launches for this

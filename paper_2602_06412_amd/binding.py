@@ -55,6 +55,7 @@ _SIGS = {
     "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
     "sl_linear_splits": [_I, _I, _I],
     "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
+    "sl_linear_clock_probe": [_P, _P, _I, _P, _P, _I, _I, _I, _P, _P, _P],
     "sl_profile_begin": [_P, _I],
     "sl_profile_end": [_P, C.POINTER(C.c_float), C.POINTER(_I)],
     "sl_lock_test": [_P, _P, _I, _P, _I, _I, _P, _P, _P, _P, _P, _I, _P, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P],
@@ -251,6 +252,12 @@ def sl_linear_forward(x, packed, m_dev, m_upper, n, k, splits=0, y_f32=None, y_b
     _check("sl_linear_forward", lib().sl_linear_forward(_stream(), _ptr(x), int(x_tiled), _ptr(packed), _ptr(m_dev),
                                                         m_upper, n, k, splits, _ptr(y_f32), _ptr(y_bf16),
                                                         _ptr(row_map)))
+
+
+def sl_linear_clock_probe(x, packed, m_dev, m_upper, n, k, y_bf16, counters, row_map=None, x_tiled=0):
+    """counters: 8 x int64 on the device (see the header for their meaning)."""
+    _check("sl_linear_clock_probe", lib().sl_linear_clock_probe(_stream(), _ptr(x), int(x_tiled), _ptr(packed), _ptr(m_dev),
+                                                                m_upper, n, k, _ptr(y_bf16), _ptr(row_map), _ptr(counters)))
 
 
 def tile_activations(x):

@@ -410,6 +410,15 @@ extern "C" int sl_linear_forward(void* stream, const void* x, int32_t x_tiled, c
   return slk_gemm_mfma((hipStream_t)stream, x, x_tiled ? 1 : 0, packed, m_dev, m_upper, n, k, splits, y_f32, y_bf16, row_map, n);
 }
 
+extern "C" int sl_linear_clock_probe(void* stream, const void* x, int32_t x_tiled, const void* packed, const int32_t* m_dev,
+                                     int32_t m_upper, int32_t n, int32_t k, void* y_bf16, const int32_t* row_map,
+                                     int64_t* counters) {
+  if (!x || !packed || !m_dev || !y_bf16 || !counters || m_upper < 65 || n < 32 || k < 256 || n % 32 || k % 64) return SL_EINVAL;
+  if ((uintptr_t)x % 16 || (uintptr_t)packed % 16 || (uintptr_t)y_bf16 % 16 || (uintptr_t)counters % 8) return SL_EINVAL;
+  return slk_gemm_mfma256_probe((hipStream_t)stream, x, x_tiled ? 1 : 0, packed, m_dev, m_upper, n, k, y_bf16, row_map, n,
+                                (long long*)counters);
+}
+
 // ---- the step --------------------------------------------------------------------------------------
 extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
                                 const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,

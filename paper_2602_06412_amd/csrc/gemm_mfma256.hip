@@ -38,11 +38,14 @@ constexpr int BK2 = 32;                   // k per stage: two MFMA k-steps
 constexpr int TILE = 256;
 constexpr int STAGE = 32 * 64;            // Frag elements per stage: 16 A + 16 B fragments (32 KiB)
 
-template <int OUT, int NS>
+// PROBE: one workgroup in the middle of the grid also records shader-clock cycles and 100 MHz
+// wall ticks of its prologue, k loop and epilogue into probe[0..7] (a measurement aid: the
+// clock under this kernel is set by the chip's power management, not by the nominal 2.4 GHz).
+template <int OUT, int NS, bool PROBE = false>
 __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe = nullptr) {
   extern __shared__ Frag lds[];           // [NS stages][A: 8 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
 
   const int M = min(*m_dev, m_upper);
@@ -157,16 +160,21 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // complete in order, 4 per tile per wave)
 #define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (NS - 2)) : "memory")
 
-  // NR LDS reads slotted one behind each of the first MFMAs of a group of 16: the wave's issue
-  // slot is blocked while the MFMA pipe is busy anyway, so the reads issue for free
+  // NR LDS reads slotted behind the first MFMAs of a group of 16, MPR MFMAs apart: the wave's
+  // issue slot is blocked while the MFMA pipe is busy anyway, so the reads issue for free
+#ifndef SL_MPR
+#define SL_MPR 1
+#endif
 #define SL_INTERLEAVE(NR)                                                                  \
   do {                                                                                     \
     _Pragma("unroll") for (int q_ = 0; q_ < (NR); ++q_) {                                  \
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   \
+      __builtin_amdgcn_sched_group_barrier(0x008, SL_MPR, 0);                              \
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
     }                                                                                      \
-    __builtin_amdgcn_sched_group_barrier(0x008, 16 - (NR), 0);                             \
+    __builtin_amdgcn_sched_group_barrier(0x008, 16 - (NR) * SL_MPR, 0);                    \
   } while (0)
+  long long pc0 = 0, pw0 = 0, pc1 = 0, pw1 = 0, pc2 = 0, pw2 = 0;
+  if (PROBE) { pc0 = clock64(); pw0 = wall_clock64(); }
   // prologue: tiles 0 .. NS-2 in flight, tile 0 landed and published, its first fragments read
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t) issue(t, t);
@@ -178,6 +186,7 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // barrier, multiply rows 0..63 of the sub-tile while reading the A fragments of rows 64..127,
   // wait for tile kt+1 and publish it, multiply rows 64..127 while reading the first fragments
   // of tile kt+1.  B fragments alternate between two register sets, hence two steps per trip.
+  if (PROBE) { pc1 = clock64(); pw1 = wall_clock64(); }
   int st = 0;                                         // stage of tile kt
   auto step = [&](int kt, Frag (&b_cur)[4], Frag (&b_next)[4]) {
     const int st_prev = st == 0 ? NS - 1 : st - 1;
@@ -201,6 +210,7 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     step(kt + 1, b_odd, b_even);
   }
   if (kt < ktiles) step(kt, b_even, b_odd);
+  if (PROBE) { pc2 = clock64(); pw2 = wall_clock64(); }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // drain the (unused) tail re-fetches
 #undef SL_WAIT_RING
 #undef SL_INTERLEAVE
@@ -234,6 +244,15 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
       if (row < M && col < n) {
         const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
         *reinterpret_cast<Frag*>(Cb + orow * ldc + col) = val;
+      }
+    }
+    if (PROBE) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 // the stores have left
+      const long long pc3 = clock64(), pw3 = wall_clock64();
+      if (blockIdx.x == ((gridDim.x >> 1) & ~7u) && threadIdx.x == 0) {
+        probe[0] = pc1 - pc0; probe[1] = pc2 - pc1; probe[2] = pc3 - pc2;
+        probe[3] = pw1 - pw0; probe[4] = pw2 - pw1; probe[5] = pw3 - pw2;
+        probe[6] = gridDim.x; probe[7] = ktiles;
       }
     }
     return;
@@ -293,7 +312,7 @@ static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
-                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
+                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, (long long*)nullptr);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -307,6 +326,24 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   return Cf ? launch256<0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
             : launch256<1, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
+}
+
+// The LM-head launch (bf16 rows, no split) with the cycle probe switched on; probe = 8 int64 on the device.
+int slk_gemm_mfma256_probe(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                           int k, void* Cb, const int32_t* row_map, size_t ldc, long long* probe) {
+  if (mu <= 0 || !probe || !Cb) return SL_EINVAL;
+  if (n % 32 || k % BK2 || k / BK2 < 8) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
+  const size_t sh = (size_t)5 * STAGE * 16;
+  auto kern = gemm_mfma256_kernel<1, 5, true>;
+  static unsigned long long lds_ok = 0;
+  SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
+  dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), 1), block(512);
+  hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k, m_dev, mu,
+                     (float*)nullptr, (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, probe);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
 }
 
 int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,

@@ -207,6 +207,8 @@ int slk_gemm_unsplit_thick(int mu, int n, int k);
 int slk_gemm_splits_gate_up(int mu, int n, int k);
 // gate|up projection with interleaved 32-column blocks (gate j, up j, gate j+1, ..) and SwiGLU in the
 // epilogue: a[row, c] = silu(g) * u as bf16 in the fragment-tiled layout; no k-split
+int slk_gemm_mfma256_probe(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                           int k, void* Cb, const int32_t* row_map, size_t ldc, long long* probe);
 int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
                             void* a);
 int slk_gemm_splits(int mu, int n, int k);

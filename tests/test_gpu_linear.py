@@ -96,3 +96,34 @@ def test_linear_argument_errors():
         B.sl_linear_forward(x, packed, m_dev, 32, 64, 48, 1, y_f32=y)
     with pytest.raises(B.SureLockError):                      # bf16 output with a k-split
         B.sl_linear_forward(x, packed, m_dev, 32, 64, 64, 2, y_bf16=yb)
+
+
+@pytest.mark.gpu
+def test_clock_probe_matches_plain_launch_and_reports_sane_counters():
+    """sl_linear_clock_probe: same bf16 result as sl_linear_forward, counters within physical bounds
+    (a 32-deep k-tile cannot take fewer than 1024 cycles: 2 waves x 32 MFMAs x 16 cycles per SIMD)."""
+    import torch
+    from paper_2602_06412_amd import binding as B
+    dev = "cuda:0"
+    M, n, k = 300, 1024 + 32, 1024
+    g = torch.Generator(device="cpu").manual_seed(5)
+    w = (torch.randn(n, k, generator=g) * 0.02).to(torch.bfloat16).to(dev)
+    x = torch.randn(M, k, generator=g).to(torch.bfloat16).to(dev)
+    packed = torch.empty_like(w)
+    B.sl_linear_pack(w, packed)
+    m_dev = torch.tensor([M], dtype=torch.int32, device=dev)
+    y0 = torch.zeros(M, n, dtype=torch.bfloat16, device=dev)
+    y1 = torch.zeros(M, n, dtype=torch.bfloat16, device=dev)
+    B.sl_linear_forward(x, packed, m_dev, M, n, k, 1, None, y0)
+    counters = torch.zeros(8, dtype=torch.int64, device=dev)
+    B.sl_linear_clock_probe(x, packed, m_dev, M, n, k, y1, counters)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    c = [int(v) for v in counters.cpu()]
+    assert c[7] == k // 32
+    assert c[1] >= 1024 * c[7] and c[1] < 40 * 1024 * c[7]
+    assert all(v > 0 for v in c[:6]) and c[6] == 16
+    mhz = c[1] / c[4] * 100.0
+    assert 500.0 < mhz < 3000.0
+    with pytest.raises(B.SureLockError):
+        B.sl_linear_clock_probe(x, packed, m_dev, 64, n, k, y1, counters)     # thin launches have no probe
