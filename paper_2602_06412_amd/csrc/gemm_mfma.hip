@@ -340,10 +340,14 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // ---- host side ------------------------------------------------------------------------------
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
+#ifndef SL_THIN_MAX
+#define SL_THIN_MAX 32
+#endif
+constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many rows take the thin (weight-stream) kernels
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
 // Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
-//  * thin launches (mu <= 64) are weight-stream bound: one BM x 256 tile per 256 columns, k
+//  * thin launches (mu <= kThinMax) are weight-stream bound: one BM x 256 tile per 256 columns, k
 //    split until there are about two workgroups per CU, with the fp32 partial traffic capped
 //    at a fraction of the weight bytes (k >= 32*S*mu);
 //  * thick launches pick, by a small cost model calibrated on measured launches, between the
@@ -360,7 +364,7 @@ struct GemmPlan {
 // planes that a second kernel reads back.
 static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
   GemmPlan p{0, 1};
-  if (mu <= 64) {
+  if (mu <= kThinMax) {
     const int tiles = sl_cdiv(n, 256);
     int s = 1;
     while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
@@ -392,7 +396,7 @@ int slk_gemm_splits(int mu, int n, int k) { return gemm_plan(mu, n, k).splits; }
 // 1 if the launch plan for (mu, n, k) is the 256 x 256 ring kernel without a k-split (the only
 // form whose epilogue can apply SwiGLU to finished sums)
 int slk_gemm_unsplit_thick(int mu, int n, int k) {
-  if (mu <= 64 || k < 256) return 0;
+  if (mu <= kThinMax || k < 256) return 0;
   const GemmPlan p = gemm_plan(mu, n, k, true);
   return p.thick256 && p.splits == 1;
 }
@@ -424,7 +428,7 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
 #define GO(BM)                                                                                             \
   return Cf ? launch_gemm<BM, 2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
             : launch_gemm<BM, 2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  if (mu > 64 && k / splits >= 256) {
+  if (mu > kThinMax && k / splits >= 256) {
     const GemmPlan plan = gemm_plan(mu, n, k);
     const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
     if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
