@@ -29,6 +29,8 @@ constexpr int kMaxBatch = 255;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+constexpr float kMaxLag = 8.0f;   // probabilities may exceed 1 by up to 2^8 before the reference moves
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t PFrag __attribute__((ext_vector_type(4)));   // eight bf16 probabilities, packed in pairs
 
 // SPLIT: the key tiles are divided over gridDim.z workgroups (thin launches would otherwise
@@ -205,10 +207,18 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc_cur[kb][v]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one real key
+    // The reference point of the exponentials follows the running max only in jumps of more than
+    // kMaxLag (in the exp2 domain): a stale reference is exact mathematics (numerator and
+    // denominator carry the same factor, at most 2^kMaxLag), and O is then rescaled on a tile only
+    // when some query of the wave really jumped.  With near-uniform scores the max of 32 queries
+    // creeps up on almost every tile, and rescaling 64 accumulators each time cost a quarter of
+    // the kernel.  First tile: m_run = -inf, so every query jumps (alpha = 0 on a zero O).
+    const float m_cand = fmaxf(m_run, mx);    // finite: every tile holds at least one real key
+    const float m_new = (m_cand - m_run) * sc > kMaxLag ? m_cand : m_run;
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
     const float mb_ = m_new * sc;
-    float psum = 0.f;
+    float psum = 0.f, pa = 0.f, pb = 0.f;
+    uint32_t hw = 0u;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 48; ++i) {
@@ -239,22 +249,31 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
           sc_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], sc_next[kb], 0, 0, 0);
         }
       }
-      if (i % 3 == 0) {
-        // probabilities 2pr, 2pr+1 of this lane: register v of block kb, for P^T step 2*kb + v/8
-        const int pr = i / 3;
+      // Softmax of tile t, one pair of probabilities (2pr, 2pr+1 of this lane: register v of block
+      // kb, for P^T step 2*kb + v/8) per three slots, its dependent chain cut in three so that no
+      // slot carries more than five vector-ALU instructions behind its MFMA: exponentials, then
+      // sum + high halves, then low halves.  The empty asm statements tie each piece to its slot:
+      // without them the compiler sinks the whole softmax below the last MFMA.
+      {
+        const int pr = i / 3, ph = i % 3;
         const int x = 2 * pr, kb = x >> 4, v = x & 15, stp = 2 * kb + (v >> 3), e = v & 7;
-        float pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
-        float pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
-        psum += pa + pb;
-        const __bf16 ha = (__bf16)pa, hb = (__bf16)pb;
-        bf16x2 hpk = {ha, hb};
-        bf16x2 lpk = {(__bf16)(pa - (float)ha), (__bf16)(pb - (float)hb)};
-        uint32_t hw = __builtin_bit_cast(uint32_t, hpk), lw = __builtin_bit_cast(uint32_t, lpk);
-        // the empty asm ties these values to this slot: without it the compiler sinks the whole
-        // softmax below the last MFMA, where nothing overlaps it
-        asm volatile("" : "+v"(hw), "+v"(lw), "+v"(psum));
-        pnh[stp][e >> 1] = hw;
-        pnl[stp][e >> 1] = lw;
+        if (ph == 0) {
+          pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
+          pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
+          asm volatile("" : "+v"(pa), "+v"(pb));
+        } else if (ph == 1) {
+          psum += pa + pb;
+          const f32x2 pp = {pa, pb};
+          hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+          asm volatile("" : "+v"(hw), "+v"(psum));
+          pnh[stp][e >> 1] = hw;
+        } else {
+          // the bf16 halves are widened back with a shift / a mask
+          const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
+          uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
+          asm volatile("" : "+v"(lw));
+          pnl[stp][e >> 1] = lw;
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
