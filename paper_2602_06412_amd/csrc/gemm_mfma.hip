@@ -269,11 +269,13 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   // each k-step issues 2 + MB of them, so the operands of a step have landed once at most
   // (DEPTH-1)(2+MB) younger loads are outstanding.  The waits name the registers they release,
   // which keeps the MFMAs behind them.
+  // The weight loads carry the non-temporal hint: every weight byte is used once per launch, and
+  // streaming them past the caches measured 191 -> 165 us on the LM head at M = 16 (6.3 TB/s).
   Frag fa[DEPTH][MB], fb[DEPTH][2];
   auto fetch = [&](int step, int slot) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
       asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
@@ -341,7 +343,7 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
 #ifndef SL_THIN_MAX
-#define SL_THIN_MAX 32
+#define SL_THIN_MAX 64
 #endif
 constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many rows take the thin (weight-stream) kernels
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
@@ -433,11 +435,14 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
     const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
     if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
   }
-  // at most 32 rows: the barrier-free weight stream (measured a few per cent ahead of the LDS kernel
-  // there, behind it at 64 rows)
+  // at most 64 rows: the barrier-free weight stream with one or two 32-row blocks (with streaming
+  // weight loads it is ahead of both LDS kernels there: 0.42 -> 0.39 ms on the step at 64 rows)
   if (mu <= 32 && (k / splits) % 128 == 0)
     return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
               : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
+  if (mu <= 64 && (k / splits) % 128 == 0)
+    return Cf ? launch_stream<2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+              : launch_stream<2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
   const int bm = pick_bm(mu);
   if (bm == 32) { GO(32); }
   if (bm == 64) { GO(64); }
