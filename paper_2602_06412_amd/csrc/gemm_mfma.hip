@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
 #pragma unroll
     for (int i = 0; i < WNB; ++i)
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) b[i][kb] = base[b_off[i] + kb * 64];
+      for (int kb = 0; kb < 4; ++kb) b[i][kb] = __builtin_nontemporal_load(&base[b_off[i] + kb * 64]);   // streamed once
   };
   // One k-tile: A fragments are read one k-step ahead of the MFMAs that use them.
   auto compute = [&](const Frag* stage, const Frag (&b)[WNB][4]) {
