@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
   }
 }
 
-// ---- thin launches (at most 32 rows; the kernel itself handles 32 MB): a pure weight stream ------------------------------------
+// ---- thin launches (at most 32 MB rows, MB = 1 or 2): a pure weight stream ---------------------
 // Below ~300 rows the projection is bound by reading the weights once (2 n k bytes), so the only
 // thing that matters is keeping enough loads in flight.  Here every wave streams its own 64
 // columns with no LDS and no barrier: operand fragments go global -> registers, DEPTH k-steps

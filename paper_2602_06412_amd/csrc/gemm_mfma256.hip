@@ -13,8 +13,9 @@
 //    rate, half of what the 128-row kernel needs);
 //  * k-tiles are 32 deep (32 KiB per stage), five stages fill the 160 KiB LDS, so four tiles
 //    (128 KiB per CU, 32 MiB chip-wide) are in flight while one is multiplied;
-//  * one barrier per k-tile, placed between the two MFMA k-steps, so the LDS reads on either
-//    side of it are covered by MFMAs; fragments are read one k-step ahead.
+//  * one barrier per k-tile, placed between the two halves of its MFMAs (rows 0..63 / 64..127 of
+//    a wave's sub-tile), so the LDS reads on either side of it are covered by MFMAs; fragments
+//    are read half a tile ahead.
 // Operands land in LDS as 32 x 16 blocks of 1 KiB (activation rows gathered 32 x 16 per
 // instruction, pre-tiled weights copied linearly): element (r, k) of a block sits in the 16-byte
 // slot (r % 32) + 32 * ((k % 16) / 8).
@@ -34,7 +35,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef bf16x8 Frag;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BK2 = 32;                   // k per stage: two MFMA k-steps
+constexpr int BK2 = 32;                   // k per stage: one 16x16x32 MFMA k-step
 constexpr int TILE = 256;
 constexpr int STAGE = 32 * 64;            // Frag elements per stage: 16 A + 16 B fragments (32 KiB)
 
