@@ -340,6 +340,200 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
   }
 }
 
+// Second form of the same product for launches with at least two workgroups per CU: the wave
+// does not pipeline its own tile steps (scores, softmax, P.V in sequence), needs half the
+// registers and a two-slot ring, and two workgroups share a CU, so that one's softmax runs under
+// the other's MFMAs and barrier waits.  Same fragment layouts, same arithmetic per tile.
+template <bool SPLIT>
+__global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __restrict__ q,
+                                                                const bf16_t* __restrict__ kc,
+                                                                const bf16_t* __restrict__ vc,
+                                                                const int32_t* __restrict__ active_idx,
+                                                                const int32_t* __restrict__ m_dev, int m_upper, int B,
+                                                                int H, int N, int n_pad, bf16_t* __restrict__ o,
+                                                                int tiles_per_split, float* __restrict__ part_o,
+                                                                float* __restrict__ part_ml) {
+  extern __shared__ FragA lds[];             // K ring [2][16 KiB] | V ring [2][16 KiB]
+  __shared__ int cu[kMaxBatch + 2];
+  constexpr int TILE_F = KT * DH / 8;
+  FragA* const ldsK = lds;
+  FragA* const ldsV = lds + 2 * TILE_F;
+  const int M = min(*m_dev, m_upper);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hh = blockIdx.x;
+  if (B == 1) {
+    if (tid <= 1) cu[tid] = tid ? M : 0;
+  } else if (tid <= B) {
+    int lo = 0, hi = M;
+    const long long key = (long long)tid * N;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((long long)active_idx[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    cu[tid] = lo;
+  }
+  __syncthreads();
+  int b = 0, tile = blockIdx.y, row0 = -1, row_end = 0;
+  for (; b < B; ++b) {
+    const int cnt = cu[b + 1] - cu[b];
+    const int nt = (cnt + QT - 1) / QT;
+    if (tile < nt) { row0 = cu[b] + tile * QT; row_end = cu[b + 1]; break; }
+    tile -= nt;
+  }
+  if (row0 < 0) return;                       // uniform across the workgroup
+
+  const size_t head_base = ((size_t)b * H + hh) * n_pad * DH;
+  const FragA* kg = reinterpret_cast<const FragA*>(kc + head_base);
+  const FragA* vg = reinterpret_cast<const FragA*>(vc + head_base);
+  const int kt_lo = SPLIT ? blockIdx.z * tiles_per_split : 0;
+  const int kt_hi = SPLIT ? min(n_pad / KT, kt_lo + tiles_per_split) : n_pad / KT;
+  const int T = kt_hi - kt_lo;               // >= 1 tiles for this workgroup
+
+  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) FragA*)(lds + wave * 4 * 64));
+  const uint32_t lane_voff = (uint32_t)((wave * 4 * 64 + lane) * 16);
+  auto load_tile = [&](const FragA* g, const FragA* l) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t laddr = lds_wave + (uint32_t)((l - lds) + c * 64) * 16u;
+      const uint64_t gbase = (uint64_t)(uintptr_t)g + (uint64_t)(c * 1024);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                   :
+                   : "v"(lane_voff), "s"(gbase), "s"(laddr)
+                   : "memory", "m0");
+    }
+  };
+  load_tile(kg + (size_t)kt_lo * TILE_F, ldsK);
+  load_tile(vg + (size_t)kt_lo * TILE_F, ldsV);
+
+  const int my_row = row0 + wave * 32 + (lane & 31);
+  const int ld_row = my_row < row_end ? my_row : row_end - 1;
+  FragA qf[8];
+  {
+    const bf16_t* qp = q + ((size_t)ld_row * H + hh) * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const FragA*>(qp + ks * 16);
+  }
+  f32x16 acc_o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc_o[i][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(d_h)
+
+  for (int t = 0; t < T; ++t) {
+    const int slot = t & 1;
+    // tile t has landed (it was requested one iteration ago) ...
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();       // ... for everyone, and everyone is done with tile t-1: its slot is free
+    if (t + 1 < T) {
+      load_tile(kg + (size_t)(kt_lo + t + 1) * TILE_F, ldsK + (slot ^ 1) * TILE_F);
+      load_tile(vg + (size_t)(kt_lo + t + 1) * TILE_F, ldsV + (slot ^ 1) * TILE_F);
+    }
+    // S^T = K Q^T: two 32-key blocks; register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
+    f32x16 sv[2];
+    const FragA* kt_lds = ldsK + slot * TILE_F + lane;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[kb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        sv[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_lds[(kb * 8 + ks) * 64], qf[ks], sv[kb], 0, 0, 0);
+    }
+    if ((kt_lo + t + 1) * KT > N) {
+      const int kbase = (kt_lo + t) * KT + 4 * (lane >> 5);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) sv[kb][v] = -INFINITY;
+    }
+    float mx = sv[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sv[kb][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // the reference of the exponentials follows the running max only in jumps (see kMaxLag)
+    const float m_cand = fmaxf(m_run, mx);
+    const float m_new = (m_cand - m_run) * sc > kMaxLag ? m_cand : m_run;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+    const float mb_ = m_new * sc;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
+    }
+    // P = hi + lo in bf16; pair (v, v+1) of block kb belongs to P^T step 2*kb + v/8
+    PFrag ph[4], pl[4];
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+        const float pa = __builtin_amdgcn_exp2f(fmaf(sv[kb][v], sc, -mb_));
+        const float pb = __builtin_amdgcn_exp2f(fmaf(sv[kb][v + 1], sc, -mb_));
+        psum += pa + pb;
+        const f32x2 pp = {pa, pb};
+        const uint32_t hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+        const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
+        const uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
+        ph[2 * kb + (v >> 3)][(v & 7) >> 1] = hw;
+        pl[2 * kb + (v >> 3)][(v & 7) >> 1] = lw;
+      }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    // O^T += V^T P^T
+    const FragA* vt_lds = ldsV + slot * TILE_F + (lane >> 5) * DH + (lane & 31);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      FragA a[4];
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) a[mb] = vt_lds[(2 * st) * DH + mb * 32];
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+    }
+  }
+
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (SPLIT) {
+    if (my_row < row_end) {
+      const size_t slot = ((size_t)blockIdx.z * m_upper + my_row) * H + hh;
+      float* po = part_o + slot * DH + 4 * (lane >> 5);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4*>(po + mb * 32 + 8 * g) =
+              make_float4(acc_o[mb][4 * g], acc_o[mb][4 * g + 1], acc_o[mb][4 * g + 2], acc_o[mb][4 * g + 3]);
+      if (lane < 32) {
+        part_ml[slot * 2] = m_run * sc;
+        part_ml[slot * 2 + 1] = l_tot;
+      }
+    }
+    return;
+  }
+  const float inv = 1.0f / l_tot;
+  if (my_row < row_end) {
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc_o[mb][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(o + afrag_index(my_row, hh * DH + mb * 32 + 8 * g + 4 * (lane >> 5), H * DH)) = w;
+      }
+  }
+}
+
 // o[row, h, :] = sum_z 2^(m_z - m) O_z / sum_z 2^(m_z - m) l_z over the key splits z
 __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __restrict__ part_o,
                                                               const float* __restrict__ part_ml,
@@ -360,14 +554,20 @@ __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __res
   o[afrag_index(row, hh * DH + dd, H * DH)] = (bf16_t)(num / den);
 }
 
-// Key-split plan for a launch bounded by m_upper rows.  One workgroup occupies a CU (LDS rings,
-// 390 registers per lane), so the keys are split just far enough to give every CU one workgroup;
-// splitting further only adds partial-result traffic and a second round of workgroups.
-// Returns Z (1 = no split) and the tiles per split.
+// Which kernel a launch of `blocks` (row tile, head) workgroups takes: the paired kernel as soon as
+// there is more than one workgroup per CU (measured on 32 layers at N = 2048: attention 3.5 -> 3.0
+// ms per step at 512 workgroups, 3.1 -> 2.5 ms at 288), the pipelined one otherwise (34 vs 51 us
+// at 256 workgroups, where the paired kernel would need a key split and a merge to fill the CUs).
+static bool attention_use_pair(int blocks) { return blocks > 256; }
+
+// Key-split plan for a launch bounded by m_upper rows: the keys are split just far enough to
+// give every CU one workgroup of the pipelined kernel (LDS rings, 390 registers per lane: one per
+// CU) or two of the paired kernel; splitting further only adds partial-result traffic and more
+// rounds of workgroups.  Returns Z (1 = no split) and the tiles per split.
 int slk_attention_splits(int m_upper, int B, int H, int n_pad, int* tiles_per_split) {
   const int n_tiles = n_pad / KT;
   const int blocks = (sl_cdiv(m_upper, QT) + B - 1) * H;
-  int Z = 256 / blocks;
+  int Z = (attention_use_pair(blocks) ? 512 : 256) / blocks;
   if (Z < 1) Z = 1;
   if (Z > n_tiles) Z = n_tiles;
   const int tps = sl_cdiv(n_tiles, Z);
@@ -393,20 +593,25 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   int tps;
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
   dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
-  const size_t sh = 6 * (size_t)KT * DH * 2;           // K and V rings, three 16 KiB slots each
-  static unsigned long long lds_ok[2] = {0, 0};
-  SL_ALLOW_DYNAMIC_LDS(lds_ok[0], attention_mfma_kernel<false>, sh);
-  SL_ALLOW_DYNAMIC_LDS(lds_ok[1], attention_mfma_kernel<true>, sh);
+  const bool pair = attention_use_pair((int)(grid.x * grid.y));
+  const size_t sh = (pair ? 4 : 6) * (size_t)KT * DH * 2;   // K and V rings of 16 KiB slots: two or three each
+  static unsigned long long lds_ok[4] = {0, 0, 0, 0};
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[0], attention_mfma_kernel<false>, 6 * (size_t)KT * DH * 2);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[1], attention_mfma_kernel<true>, 6 * (size_t)KT * DH * 2);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[2], attention_pair_kernel<false>, 4 * (size_t)KT * DH * 2);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[3], attention_pair_kernel<true>, 4 * (size_t)KT * DH * 2);
   if (Z == 1) {
-    hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, sh, s, (const bf16_t*)q, (const bf16_t*)kc,
-                       (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, 0, nullptr, nullptr);
+    hipLaunchKernelGGL(pair ? attention_pair_kernel<false> : attention_mfma_kernel<false>, grid, block, sh, s,
+                       (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad,
+                       (bf16_t*)o, 0, nullptr, nullptr);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)Z * m_upper * H * DH;
-  hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, block, sh, s, (const bf16_t*)q, (const bf16_t*)kc,
-                     (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o, tps, part_o, part_ml);
+  hipLaunchKernelGGL(pair ? attention_pair_kernel<true> : attention_mfma_kernel<true>, grid, block, sh, s,
+                     (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad,
+                     (bf16_t*)o, tps, part_o, part_ml);
   SL_LAUNCH_CHECK();
   hipLaunchKernelGGL(attention_merge_kernel, dim3(m_upper, H), dim3(DH), 0, s, part_o, part_ml, m_dev, m_upper, H, Z,
                      (bf16_t*)o);
