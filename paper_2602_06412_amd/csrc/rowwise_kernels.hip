@@ -363,6 +363,121 @@ __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __r
   }
 }
 
+// Thick-launch variant: one workgroup per 16 consecutive packed rows, one head at a time.
+// Loads are 16 bytes per thread and contiguous along a row; q leaves directly (8-byte stores);
+// K and V of the head are staged in LDS as bf16 and leave in the order of the cache layouts:
+//   K: a thread writes the 16-byte unit (slot, 8 dims); the 16 rows of a unit column are 16
+//      lanes, so consecutive slots give 256 contiguous bytes;
+//   V: the cache puts eight SLOTS side by side per dim (slots 16A + 4c + {0..3} and 16A + 8 + 4c +
+//      {0..3} form the 16-byte group c of block A).  When the 16 rows are the 16 consecutive
+//      slots of one aligned block (the common case while large parts of a sequence are still
+//      active) a thread writes one group as a 16-byte store, a wave 1 KiB contiguous; otherwise V
+//      falls back to 2-byte stores.
+// Requires d_h = 128 (256 threads = 16 rows x 16 chunks of four rotation pairs).
+__global__ __launch_bounds__(256) void rope_kv_write_block_kernel(const float* __restrict__ qkv, int S, size_t sstride,
+                                                                  const int32_t* __restrict__ active_idx,
+                                                                  const int32_t* __restrict__ m_dev, int m_upper, int H,
+                                                                  int N, int n_pad, const float2* __restrict__ rope_tab,
+                                                                  bf16_t* __restrict__ q, bf16_t* __restrict__ kc,
+                                                                  bf16_t* __restrict__ vc) {
+  constexpr int RB = 16, dh = 128, half = 64;
+  const int M = min(*m_dev, m_upper);
+  const int r0 = blockIdx.x * RB;
+  if (r0 >= M) return;
+  const int nrows = min(RB, M - r0);
+  __shared__ int slot_sh[RB];
+  __shared__ int dense_sh;
+  __shared__ __align__(16) bf16_t kbuf[RB][dh + 8];     // +8: rows 272 bytes apart, 16-byte aligned, banks spread
+  __shared__ __align__(16) bf16_t vbuf[RB][dh + 8];
+  if (threadIdx.x < RB) slot_sh[threadIdx.x] = threadIdx.x < nrows ? active_idx[r0 + threadIdx.x] : -1;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int g0 = slot_sh[0];
+    bool dense = nrows == RB && (g0 % N) % RB == 0 && (g0 % N) + RB <= N;
+    for (int j = 1; j < RB && dense; ++j) dense = slot_sh[j] == g0 + j;
+    dense_sh = dense;
+  }
+  __syncthreads();
+  const bool dense = dense_sh != 0;
+  const int hd = H * dh;
+  // compute role: row j, rotation pairs jj .. jj+3
+  const int j = threadIdx.x >> 4, jj = (threadIdx.x & 15) * 4;
+  const bool live = j < nrows;
+  const int g = live ? slot_sh[j] : 0;
+  const int b = g / N, i = g - b * N;
+  float cs0[4] = {0.f, 0.f, 0.f, 0.f}, cs1[4] = {0.f, 0.f, 0.f, 0.f};
+  if (live) {
+    const float* tab = reinterpret_cast<const float*>(rope_tab + (size_t)i * half + jj);   // (cos, sin) x 4
+    ld4f(tab, cs0); ld4f(tab + 4, cs1);
+  }
+  // K store role: unit (slot js, dims 8 dg .. 8 dg + 7); V store role: group vcg of the block, dim vdim
+  const int js = threadIdx.x & 15, dg = threadIdx.x >> 4;
+  const int vcg = threadIdx.x >> 7, vdim = threadIdx.x & 127;
+  const int gs = js < nrows ? slot_sh[js] : -1;
+  const int g0 = slot_sh[0];
+  // the heads are divided over gridDim.y workgroups (thin launches would otherwise leave CUs idle)
+  const int h_per = H / gridDim.y;
+  for (int hh = blockIdx.y * h_per; hh < (blockIdx.y + 1) * h_per; ++hh) {
+    if (live) {
+      const float* row = qkv + (size_t)(r0 + j) * 3 * hd;
+      const int c0 = hh * dh + jj, c1 = c0 + half;
+      float q0[4], q1[4], k0[4], k1[4], v0[4], v1[4];
+      ld4f(row + c0, q0); ld4f(row + c1, q1);
+      ld4f(row + hd + c0, k0); ld4f(row + hd + c1, k1);
+      ld4f(row + 2 * hd + c0, v0); ld4f(row + 2 * hd + c1, v1);
+      for (int sp = 1; sp < S; ++sp) {                     // k-split partials, fixed order
+        const float* pr = row + sp * sstride;
+        float p[4];
+#define SL_ACC4(dst, src) do { ld4f(src, p); _Pragma("unroll") for (int e = 0; e < 4; ++e) dst[e] += p[e]; } while (0)
+        SL_ACC4(q0, pr + c0); SL_ACC4(q1, pr + c1);
+        SL_ACC4(k0, pr + hd + c0); SL_ACC4(k1, pr + hd + c1);
+        SL_ACC4(v0, pr + 2 * hd + c0); SL_ACC4(v1, pr + 2 * hd + c1);
+#undef SL_ACC4
+      }
+      float qa[4], qb[4], ka[4], kb[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)], sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
+        qa[e] = q0[e] * c - q1[e] * sn;
+        qb[e] = q1[e] * c + q0[e] * sn;
+        ka[e] = k0[e] * c - k1[e] * sn;
+        kb[e] = k1[e] * c + k0[e] * sn;
+      }
+      st4(q + (size_t)(r0 + j) * hd + c0, qa);
+      st4(q + (size_t)(r0 + j) * hd + c1, qb);
+      st4(&kbuf[j][jj], ka);
+      st4(&kbuf[j][jj + half], kb);
+      st4(&vbuf[j][jj], v0);
+      st4(&vbuf[j][jj + half], v1);
+    }
+    __syncthreads();
+    if (gs >= 0) {
+      const int bs = gs / N, is = gs - bs * N;
+      const size_t head_base = ((size_t)bs * H + hh) * n_pad * dh;
+      *reinterpret_cast<bf16x8_t*>(kc + head_base + kc_index(is, dg * 8, dh)) =
+          *reinterpret_cast<const bf16x8_t*>(&kbuf[js][dg * 8]);
+    }
+    if (dense) {
+      const int bb = g0 / N, i0 = g0 - bb * N;
+      const size_t head_base = ((size_t)bb * H + hh) * n_pad * dh;
+      bf16x8_t out;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = vbuf[(e >> 2) * 8 + 4 * vcg + (e & 3)][vdim];
+      *reinterpret_cast<bf16x8_t*>(vc + head_base + vc_index(i0 + 4 * vcg, vdim, dh)) = out;
+    } else {
+      // 16 rows x 128 dims as 2-byte stores, eight per thread
+      for (int u = threadIdx.x; u < RB * dh; u += blockDim.x) {
+        const int jr = u >> 7, dd = u & 127;
+        if (jr < nrows) {
+          const int gr = slot_sh[jr], br = gr / N, ir = gr - br * N;
+          vc[((size_t)br * H + hh) * n_pad * dh + vc_index(ir, dd, dh)] = vbuf[jr][dd];
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 // ---- launchers ---------------------------------------------------------------------------------
 static inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -450,6 +565,15 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
   if (m_upper <= 256 && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
     hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
                        m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
+  if (dtype == SL_BF16 && dh == 128 && sstride % 4 == 0 && N % 16 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
+    const int row_blocks = sl_cdiv(m_upper, 16);
+    int hs = 1;                                          // head groups: aim at two workgroups per CU
+    while (hs < H && H % (hs * 2) == 0 && row_blocks * hs < 512) hs *= 2;
+    hipLaunchKernelGGL(rope_kv_write_block_kernel, dim3(row_blocks, hs), dim3(256), 0, s, qkv, S, sstride, active_idx,
+                       m_dev, m_upper, H, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
