@@ -36,49 +36,65 @@ typedef bf16x8 Frag;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK2 = 32;                   // k per stage: one 16x16x32 MFMA k-step
-constexpr int TILE = 256;
-constexpr int STAGE = 32 * 64;            // Frag elements per stage: 16 A + 16 B fragments (32 KiB)
+constexpr int TILE = 256;                 // columns per tile, and rows of the full-height tile
+// Rows per tile TM is 256 or 128.  The half-height tile (waves own 64 x 64, six ring stages of
+// 24 KiB) costs about a tenth more per FLOP (more LDS reads and operand traffic per MFMA) and is
+// used where it saves rounds of workgroups: 384 full tiles on 256 CUs take two rounds, 768 half
+// tiles take three half rounds.
+template <int TM> struct TileCfg {
+  static constexpr int A_FR = TM / 16;              // A fragments (32 x 16, 1 KiB) per stage
+  static constexpr int STAGE = (A_FR + 16) * 64;    // Frag elements per stage: A, then 16 B fragments
+  static constexpr int NA = TM / 32;                // 16-row accumulator blocks per wave (sub-tile TM/2 x 64)
+  static constexpr int HA = NA / 2;                 // ... per half of a k-tile step
+  static constexpr int DMA = TM == 256 ? 4 : 3;     // direct-to-LDS loads per wave and k-tile
+  static constexpr int NS = TM == 256 ? 5 : 6;      // ring stages
+};
 
 // PROBE: one workgroup in the middle of the grid also records shader-clock cycles and 100 MHz
 // wall ticks of its prologue, k loop and epilogue into probe[0..7] (a measurement aid: the
 // clock under this kernel is set by the chip's power management, not by the nominal 2.4 GHz).
-template <int OUT, int NS, bool PROBE = false>
+template <int OUT, int TM, bool PROBE = false>
 __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
     const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe = nullptr) {
-  extern __shared__ Frag lds[];           // [NS stages][A: 8 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
+  typedef TileCfg<TM> TC;
+  constexpr int STAGE = TC::STAGE, NA = TC::NA, HA = TC::HA, NS = TC::NS;
+  extern __shared__ Frag lds[];           // [NS stages][A: TM/32 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
 
   const int M = min(*m_dev, m_upper);
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
   if (tn >= tiles_n) return;
-  const int m0 = tm * TILE;
+  const int m0 = tm * TM;
   if (m0 >= M) return;
   const int n0 = tn * TILE;
   const int kbeg = blockIdx.y * k_per_split;
   const int ktiles = k_per_split / BK2;
   const int last = ktiles - 1;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = wave >> 2, wn = wave & 3;          // this wave's 128 x 64 sub-tile
+  const int wm = wave >> 2, wn = wave & 3;          // this wave's (TM/2) x 64 sub-tile
   const int K16 = k / 16, NB32 = n / 32;
 
-  // global -> LDS: 32 fragments per k-tile, 4 per wave: wave w moves the two A fragments of
-  // row block w and the two B fragments of column block w.
+  // global -> LDS: wave w moves the two B fragments of column block w and, of A, the two
+  // fragments of row block w (TM = 256) or the one fragment (row block w / 2, k half w % 2) (128).
   // A is row-major [m_upper, k] (a 32 x 16 fragment is gathered from 32 rows) or already
   // fragment-tiled (one contiguous 1 KiB block per fragment, rows padded to 32).
   const bf16_t* Ab = a_tiled ? A : A + kbeg;
   const int a_kt_stride = a_tiled ? 2 * 512 : BK2, a_kb_stride = a_tiled ? 512 : 16;   // elements
   uint32_t a_off;
+  const int a_mb = TM == 256 ? wave : wave >> 1;      // 32-row block of the tile this wave fetches
+  const int a_kb = TM == 256 ? 0 : wave & 1;          // ... and its k half (TM = 128: one fragment only)
   if (a_tiled) {
-    int mbg = m0 / 32 + wave;
+    int mbg = m0 / 32 + a_mb;
     const int mb_last = (m_upper + 31) / 32 - 1;
     mbg = mbg < mb_last ? mbg : mb_last;              // row tail: stay inside the buffer
-    a_off = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u;
+    a_off = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u +
+            (uint32_t)(a_kb * a_kb_stride);
   } else {
-    int row = m0 + wave * 32 + (lane & 31);
+    int row = m0 + a_mb * 32 + (lane & 31);
     row = row < m_upper ? row : m_upper - 1;          // row tail: stay inside the buffer
-    a_off = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8);
+    a_off = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8) + (uint32_t)(a_kb * a_kb_stride);
   }
   const Frag* Wf = reinterpret_cast<const Frag*>(Wp) + (size_t)(kbeg / 16) * 64;
   uint32_t b_off;
@@ -96,8 +112,11 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // address is a 32-bit byte offset computed once, the per-tile part a 64-bit scalar base
   // (instruction form "vgpr offset + sgpr base"), and the LDS destination a scalar sum on a
   // base read once per wave.
-  const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)(lds + (wave * 2) * 64));
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)lds);
+  const uint32_t wave_u = __builtin_amdgcn_readfirstlane((uint32_t)wave);
+  const uint32_t lds_a = lds_base + (TM == 256 ? wave_u * 2048u : wave_u * 1024u);          // this wave's A slot(s)
+  const uint32_t lds_b = lds_base + (uint32_t)TC::A_FR * 1024u + wave_u * 2048u;            // ... and B slots
   const uint32_t a_voff0 = a_off * 2u, a_voff1 = a_voff0 + (uint32_t)a_kb_stride * 2u;   // bytes
   const uint32_t b_voff0 = b_off * 16u, b_voff1 = b_voff0 + 1024u;
   const uint64_t a_base = (uint64_t)(uintptr_t)Ab, b_base = (uint64_t)(uintptr_t)Wf;
@@ -113,20 +132,20 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
                : "memory", "m0")
   auto issue = [&](int kt, int st) {
     kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
-    const uint32_t la = lds_wave + (uint32_t)(st * STAGE) * 16u, lb = la + 16u * 64u * 16u;
+    const uint32_t so = (uint32_t)(st * STAGE) * 16u, la = lds_a + so, lb = lds_b + so;
     const uint64_t ga = a_base + (uint64_t)kt * a_kt_bytes, gb = b_base + (uint64_t)kt * (128u * 16u);
     SL_DMA(a_voff0, ga, la, "");
     SL_DMA(b_voff0, gb, lb, " nt");
-    SL_DMA(a_voff1, ga, la + 1024u, "");
+    if (TM == 256) SL_DMA(a_voff1, ga, la + 1024u, "");
     SL_DMA(b_voff1, gb, lb + 1024u, " nt");
   };
 #undef SL_DMA
 
-  // acc[a][b]: rows 16a .. 16a+15, columns 16b .. 16b+15 of this wave's 128 x 64 sub-tile; lane l
+  // acc[a][b]: rows 16a .. 16a+15, columns 16b .. 16b+15 of this wave's sub-tile; lane l
   // holds row l % 16, columns 4 * (l / 16) .. +3
-  f32x4 acc[8][4];
+  f32x4 acc[NA][4];
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
+  for (int a = 0; a < NA; ++a)
 #pragma unroll
     for (int b = 0; b < 4; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
@@ -134,37 +153,37 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   // group g = l / 16, i.e. slot (l % 16) + 32 * (g % 2) of k-block g / 2; a second 16-row half
   // of a block is 16 slots further on
   const int frag_lane = (lane >> 5) * 64 + ((lane >> 4) & 1) * 32 + (lane & 15);
-  const Frag* sa0 = lds + wm * 4 * 128 + frag_lane;                 // 32-row block 4*wm + i at i * 128
-  const Frag* sb0 = lds + 16 * 64 + wn * 2 * 128 + frag_lane;       // 32-column block 2*wn + i
+  const Frag* sa0 = lds + wm * (TM / 64) * 128 + frag_lane;         // 32-row block (TM/64)*wm + i at i * 128
+  const Frag* sb0 = lds + TC::A_FR * 64 + wn * 2 * 128 + frag_lane; // 32-column block 2*wn + i
   auto a_frag = [&](int st, int a) { return sa0[st * STAGE + (a >> 1) * 128 + (a & 1) * 16]; };
   auto b_frag = [&](int st, int b) { return sb0[st * STAGE + (b >> 1) * 128 + (b & 1) * 16]; };
-  // A fragments of rows 0..63 (lo) / 64..127 (hi) of the sub-tile, B fragments of two successive k-tiles
-  Frag a_lo[4], a_hi[4], b_even[4], b_odd[4];
+  // A fragments of the lower / upper half of the sub-tile's rows, B fragments of two successive k-tiles
+  Frag a_lo[HA], a_hi[HA], b_even[4], b_odd[4];
   // in the order the MFMAs consume them: (a0,b0) (a0,b1) (a0,b2) (a0,b3) (a1,*) ...
-  auto read_tile_head = [&](int st, Frag (&af)[4], Frag (&bf)[4]) {
+  auto read_tile_head = [&](int st, Frag (&af)[HA], Frag (&bf)[4]) {
     bf[0] = b_frag(st, 0);
     af[0] = a_frag(st, 0);
 #pragma unroll
     for (int b = 1; b < 4; ++b) bf[b] = b_frag(st, b);
 #pragma unroll
-    for (int a = 1; a < 4; ++a) af[a] = a_frag(st, a);
+    for (int a = 1; a < HA; ++a) af[a] = a_frag(st, a);
   };
-  auto read_tile_rest = [&](int st, Frag (&af)[4]) {
+  auto read_tile_rest = [&](int st, Frag (&af)[HA]) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) af[a] = a_frag(st, 4 + a);
+    for (int a = 0; a < HA; ++a) af[a] = a_frag(st, HA + a);
   };
-  auto mma = [&](int a_base, const Frag (&af)[4], const Frag (&bf)[4]) {
+  auto mma = [&](int a_base, const Frag (&af)[HA], const Frag (&bf)[4]) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < HA; ++a)
 #pragma unroll
       for (int b = 0; b < 4; ++b)
         acc[a_base + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[b], af[a], acc[a_base + a][b], 0, 0, 0);
   };
-  // "s_waitcnt vmcnt(4*(NS-2))": all but this wave's newest NS-2 tiles have landed (loads
-  // complete in order, 4 per tile per wave)
-#define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (NS - 2)) : "memory")
+  // "s_waitcnt vmcnt(DMA*(NS-2))": all but this wave's newest NS-2 tiles have landed (loads
+  // complete in order, DMA per tile per wave)
+#define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TC::DMA * (NS - 2)) : "memory")
 
-  // NR LDS reads slotted behind the first MFMAs of a group of 16, MPR MFMAs apart: the wave's
+  // NR LDS reads slotted behind the first MFMAs of a group of 4 * HA, MPR MFMAs apart: the wave's
   // issue slot is blocked while the MFMA pipe is busy anyway, so the reads issue for free
 #ifndef SL_MPR
 #define SL_MPR 1
@@ -175,7 +194,7 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
       __builtin_amdgcn_sched_group_barrier(0x008, SL_MPR, 0);                              \
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
     }                                                                                      \
-    __builtin_amdgcn_sched_group_barrier(0x008, 16 - (NR) * SL_MPR, 0);                    \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4 * HA - (NR) * SL_MPR, 0);                \
   } while (0)
   long long pc0 = 0, pw0 = 0, pc1 = 0, pw1 = 0, pc2 = 0, pw2 = 0;
   if (PROBE) { pc0 = clock64(); pw0 = wall_clock64(); }
@@ -187,9 +206,9 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   read_tile_head(0, a_lo, b_even);
 
   // One k-tile per step: refill the stage every wave finished reading before the previous
-  // barrier, multiply rows 0..63 of the sub-tile while reading the A fragments of rows 64..127,
-  // wait for tile kt+1 and publish it, multiply rows 64..127 while reading the first fragments
-  // of tile kt+1.  B fragments alternate between two register sets, hence two steps per trip.
+  // barrier, multiply the lower half of the sub-tile's rows while reading the A fragments of
+  // the upper half, wait for tile kt+1 and publish it, multiply the upper half while reading the
+  // first fragments of tile kt+1.  B fragments alternate between two register sets, hence two steps per trip.
   if (PROBE) { pc1 = clock64(); pw1 = wall_clock64(); }
   int st = 0;                                         // stage of tile kt
   auto step = [&](int kt, Frag (&b_cur)[4], Frag (&b_next)[4]) {
@@ -198,13 +217,13 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     issue(kt + NS - 1, st_prev);
     read_tile_rest(st, a_hi);
     mma(0, a_lo, b_cur);
-    SL_INTERLEAVE(4);
+    SL_INTERLEAVE(HA);
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
     __syncthreads();                                  // ... and so has everyone else's
     read_tile_head(st_next, a_lo, b_next);
-    mma(4, a_hi, b_cur);
-    SL_INTERLEAVE(8);
+    mma(HA, a_hi, b_cur);
+    SL_INTERLEAVE(4 + HA);
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
   };
@@ -227,9 +246,9 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     // row segment.
     __syncthreads();                                  // every wave is done reading operand stages
     constexpr int RS = 72;                            // bf16 elements per staged row
-    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
+    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * (TM / 2) * RS;
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         bf16x4 v4;
@@ -241,9 +260,9 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const int chunk = lane & 7, rsub = lane >> 3;
     const int col = n0 + wn * 64 + chunk * 8;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < TM / 16; ++it) {
       const int r = it * 8 + rsub;
-      const int row = m0 + wm * 128 + r;
+      const int row = m0 + wm * (TM / 2) + r;
       const Frag val = *reinterpret_cast<const Frag*>(stage + r * RS + chunk * 8);
       if (row < M && col < n) {
         const size_t orow = row_map ? (size_t)row_map[row] : (size_t)row;
@@ -272,9 +291,9 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     // are contiguous in the fragment-tiled layout.
     __syncthreads();
     constexpr int RS = 40;
-    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * 128 * RS;
+    bf16_t* stage = reinterpret_cast<bf16_t*>(lds) + (size_t)wave * (TM / 2) * RS;
 #pragma unroll
-    for (int a = 0; a < 8; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         bf16x4 v4;
@@ -288,9 +307,9 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const int chunk = lane & 3, rsub = lane >> 2;
     const int c = (n0 / 64 + wn) * 32 + chunk * 8;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < TM / 32; ++it) {
       const int r = it * 16 + rsub;
-      const int row = m0 + wm * 128 + r;
+      const int row = m0 + wm * (TM / 2) + r;
       const Frag val = *reinterpret_cast<const Frag*>(stage + r * RS + chunk * 8);
       if (row < M && c < (n >> 1)) *reinterpret_cast<Frag*>(Cb + afrag_index(row, c, (int)ldc)) = val;
     }
@@ -298,8 +317,8 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   }
   // fp32 partial plane of this k-split: 16 bytes per lane, 64 contiguous bytes per row
 #pragma unroll
-  for (int a = 0; a < 8; ++a) {
-    const int row = m0 + wm * 128 + a * 16 + row_in;
+  for (int a = 0; a < NA; ++a) {
+    const int row = m0 + wm * (TM / 2) + a * 16 + row_in;
     if (row >= M) continue;
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
@@ -309,12 +328,12 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   }
 }
 
-template <int OUT, int NS>
-static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
-                     int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
-  const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
-  const size_t sh = (size_t)NS * STAGE * 16;
-  auto kern = gemm_mfma256_kernel<OUT, NS>;
+template <int OUT, int TM>
+static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                       int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  const int tiles_m = sl_cdiv(mu, TM), tiles_n = sl_cdiv(n, TILE);
+  const size_t sh = (size_t)TileCfg<TM>::NS * TileCfg<TM>::STAGE * 16;
+  auto kern = gemm_mfma256_kernel<OUT, TM>;
   static unsigned long long lds_ok = 0;              // one per kernel instantiation
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
@@ -324,6 +343,35 @@ static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   return SL_OK;
 }
 
+// Tile height of a launch.  Cost model in units of one full tile's time on 256 CUs: a full round
+// of workgroups costs 1, a last partial round 0.9 whatever its fill (measured: the busy CUs of a
+// partial round run at a higher clock), a half-height tile 0.565 of a full one (1.13 per FLOP:
+// LM head 823 -> 925 us when forced).  The half-height tile is taken when it is ahead by more
+// than 5 % (measured where it is: gate|up at 1024 rows 188 -> 176 us, at 768 rows 175 -> 167 us,
+// Q|K|V at 2048 rows 180 -> 169 us).
+#ifndef SL_TM_FORCE
+#define SL_TM_FORCE 0
+#endif
+static double ring_rounds_cost(int workgroups) {
+  return workgroups / 256 + (workgroups % 256 ? 0.9 : 0.0);
+}
+static bool ring_use_half(int mu, int n, int splits) {
+  if (SL_TM_FORCE == 128) return true;
+  if (SL_TM_FORCE == 256) return false;
+  const int tn = sl_cdiv(n, TILE);
+  const double full = ring_rounds_cost(sl_cdiv(mu, 256) * tn * splits);
+  const double half = 0.565 * ring_rounds_cost(sl_cdiv(mu, 128) * tn * splits);
+  return half < 0.95 * full;
+}
+
+template <int OUT>
+static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                     int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  return ring_use_half(mu, n, splits)
+             ? launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc)
+             : launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+}
+
 int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
                      int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   if (mu <= 0) return SL_OK;
@@ -331,8 +379,8 @@ int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, 
   if (!Cf && splits != 1) return SL_EINVAL;
   if (Cf && ((uintptr_t)Cf % 16 || ldc % 4)) return SL_EINVAL;       // 16-byte fp32 stores
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
-  return Cf ? launch256<0, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
-            : launch256<1, 5>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
+  return Cf ? launch256<0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+            : launch256<1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
 }
 
 // The LM-head launch (bf16 rows, no split) with the cycle probe switched on; probe = 8 int64 on the device.
@@ -342,8 +390,8 @@ int slk_gemm_mfma256_probe(hipStream_t s, const void* A, int a_tiled, const void
   if (n % 32 || k % BK2 || k / BK2 < 8) return SL_EINVAL;
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
-  const size_t sh = (size_t)5 * STAGE * 16;
-  auto kern = gemm_mfma256_kernel<1, 5, true>;
+  const size_t sh = (size_t)TileCfg<256>::NS * TileCfg<256>::STAGE * 16;
+  auto kern = gemm_mfma256_kernel<1, 256, true>;
   static unsigned long long lds_ok = 0;
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), 1), block(512);
@@ -359,5 +407,5 @@ int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const 
   const int n = 2 * dff;
   if (dff % 32 || k % BK2 || k / BK2 < 8) return SL_EINVAL;
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
-  return launch256<2, 5>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
+  return launch256<2>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
 }
