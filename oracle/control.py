@@ -61,7 +61,8 @@ def percentile_nearest_rank(values, m):
     return v[rank - 1]
 
 
-def lock_rule(lock, masked_for_candidates, pos, D, u, eps, first_step, gate_m=None):
+def lock_rule(lock, masked_for_candidates, pos, D, u, eps, first_step, gate_m=None,
+              relocked=None, cool_until=None, rho=1.0, t=None):
     """Z_t = active and unmasked; F_t = {i in Z_t : u_i <= theta_m and D_i <= eps}.
 
     pos / D / u are parallel arrays over the active rows of one sequence.
@@ -69,6 +70,9 @@ def lock_rule(lock, masked_for_candidates, pos, D, u, eps, first_step, gate_m=No
     built from (Alg. 1 places UpdateMASK before the candidate line, so the
     literal reading passes the post-update flags).  At the first step D is
     +inf, so nothing locks.  gate_m=None disables the optional confidence gate.
+    With relocked / cool_until given (App. 'Optional Unlocking'): a position that
+    was unlocked before needs D_i <= rho * eps (the product formed in fp32, like
+    the comparison) and cannot lock while t <= cool_until_i.
     Returns the sorted list of positions to lock (F_t); lock is not modified.
     """
     Z = [r for r in range(len(pos)) if not lock[pos[r]] and not masked_for_candidates[pos[r]]]
@@ -77,5 +81,30 @@ def lock_rule(lock, masked_for_candidates, pos, D, u, eps, first_step, gate_m=No
     theta = math.inf
     if gate_m is not None:
         theta = percentile_nearest_rank([u[r] for r in Z], gate_m)
-    F = [int(pos[r]) for r in Z if u[r] <= theta and D[r] <= eps]
+    def thresh(p):
+        if relocked is not None and relocked[p]:
+            return np.float32(rho) * np.float32(eps)
+        return eps
+
+    def cooled(p):
+        return cool_until is None or t > cool_until[p]
+
+    F = [int(pos[r]) for r in Z if u[r] <= theta and D[r] <= thresh(pos[r]) and cooled(pos[r])]
     return sorted(F)
+
+
+def unlock_rule(lock_step, pos_probe, u_probe, D_probe, u_active, m, eps_unlock, t, d_interval):
+    """The unlock condition of App. 'Optional Unlocking' (its displayed equation)
+    for one sequence: with theta_t the m-th percentile (nearest rank, as for the
+    gate) of the uncertainty u_t over the ACTIVE rows of step t, a probed locked
+    position i is unlocked iff
+        u~_i > theta_t  and  D~_i > eps_unlock  and  t - t*_i > D_interval,
+    all three strictly (the sentence before the equation says 'any', the
+    equation joins them with 'and'; the equation is followed).  With no active
+    row theta_t = -inf.  pos_probe / u_probe / D_probe are parallel arrays over
+    the probed rows, lock_step[i] = t*_i.  Returns the sorted positions to unlock.
+    """
+    theta = percentile_nearest_rank(u_active, m)
+    out = [int(p) for r, p in enumerate(pos_probe)
+           if u_probe[r] > theta and D_probe[r] > eps_unlock and t - int(lock_step[p]) > d_interval]
+    return sorted(out)

@@ -76,13 +76,16 @@ def attention_rows(q, K, V):
     return np.einsum("hmn,nhd->mhd", p, V)
 
 
-def layer_active(cfg, w, x, pos, Kc, Vc):
+def layer_active(cfg, w, x, pos, Kc, Vc, write_cache=True):
     """One Transformer block on the active rows only (Alg. 1, the loop body).
 
     x: [M, d] block input of the active rows; pos: [M] their slot indices;
     Kc, Vc: [N, H, d_h] this layer's key/value table, updated IN PLACE at the
     active slots (the 'assemble' line of Alg. 1: live K/V for active rows,
     cached K/V for locked rows, which this function never touches).
+    write_cache=False is the read-only probe of App. 'Optional Unlocking': the
+    rows' queries attend to the table as it stands (their own entries included)
+    and nothing is written.
     Returns the block output for the active rows.
     """
     rnd = cfg.rnd
@@ -95,8 +98,9 @@ def layer_active(cfg, w, x, pos, Kc, Vc):
     q = rnd(rope(q, pos, cfg.rope_theta))
     k = rnd(rope(k, pos, cfg.rope_theta))
     v = rnd(v)
-    Kc[pos] = k
-    Vc[pos] = v
+    if write_cache:
+        Kc[pos] = k
+        Vc[pos] = v
     o = rnd(attention_rows(q, Kc, Vc)).reshape(M, H * dh)
     x = rnd(x + o @ w["wo"].T)
     h2 = rnd(rmsnorm(x, w["ffn_norm"], cfg.rms_eps))
@@ -112,14 +116,15 @@ def lm_head(cfg, weights, x):
     return rnd(hf @ weights["lm_head"].T)
 
 
-def forward_active(cfg, weights, tokens, active_pos, Kc, Vc):
+def forward_active(cfg, weights, tokens, active_pos, Kc, Vc, write_cache=True):
     """Restricted forward of Alg. 1: embeddings of the active rows through all
     L blocks and the LM head.  Kc, Vc: lists (one per layer) of [N, H, d_h]
-    tables, updated in place at the active slots.  Returns logits [M, V].
+    tables, updated in place at the active slots (left untouched with
+    write_cache=False).  Returns logits [M, V].
     """
     x = weights["emb"][np.asarray(tokens)[active_pos]]
     for l in range(cfg.n_layers):
-        x = layer_active(cfg, weights["layers"][l], x, active_pos, Kc[l], Vc[l])
+        x = layer_active(cfg, weights["layers"][l], x, active_pos, Kc[l], Vc[l], write_cache)
     return lm_head(cfg, weights, x)
 
 

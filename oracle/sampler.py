@@ -24,6 +24,29 @@ class State:
     x_hat: np.ndarray             # [N, d] frozen block input (bookkeeping only)
     lock_step: np.ndarray         # [N] int64, step at which the slot locked (0 = never)
     t: int = 0
+    relocked: np.ndarray = None   # [N] uint8, 1 = was unlocked at least once (stricter re-lock)
+    cool_until: np.ndarray = None # [N] int64, the slot cannot lock while t <= cool_until
+
+
+@dataclass(frozen=True)
+class UnlockParams:
+    """Parameters of App. 'Optional Unlocking'."""
+    period: int                   # P: the probe runs after every P-th step
+    m: float                      # theta_t = m-th percentile of u over the active rows
+    eps_unlock: float
+    d_interval: int               # a slot stays locked for more than this many steps
+    d_cool: int                   # steps after an unlock during which the slot cannot re-lock
+    rho: float = 1.0              # re-lock threshold rho * eps, rho <= 1
+
+
+@dataclass
+class ProbeRecord:
+    pos: np.ndarray               # probed (locked) positions, ascending
+    logits: np.ndarray            # [R, V] proxy logits
+    u: np.ndarray                 # proxy uncertainty 1 - max p^
+    conf: np.ndarray
+    D: np.ndarray                 # KL(p^_t || p_{t*})
+    unlocked: list                # positions the rule unlocks
 
 
 @dataclass
@@ -38,6 +61,7 @@ class StepRecord:
     unmasked: list                # positions unmasked at this step, selection order
     F: list                       # positions the KL rule locks at this step
     forced: list = field(default_factory=list)   # positions locked by a forced schedule
+    probe: ProbeRecord = None     # set on the steps where the unlock probe ran
 
 
 def init_state(cfg, weights, prompt_tokens, n_gen):
@@ -56,18 +80,22 @@ def init_state(cfg, weights, prompt_tokens, n_gen):
                  Kc=[np.full(shape, np.nan) for _ in range(cfg.n_layers)],
                  Vc=[np.full(shape, np.nan) for _ in range(cfg.n_layers)],
                  prev_lp=np.full((N, cfg.vocab), np.nan), x_hat=x_hat,
-                 lock_step=np.zeros(N, dtype=np.int64))
+                 lock_step=np.zeros(N, dtype=np.int64), relocked=np.zeros(N, dtype=np.uint8),
+                 cool_until=np.zeros(N, dtype=np.int64))
 
 
 def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
                   gate_m=None, candidates_pre_update=False, forced_lock=None,
-                  kl_drives_lock=True):
+                  kl_drives_lock=True, unlock=None):
     """One iteration of the loop of Alg. 1, in the paper's order.
 
     eps < 0 can never be met by a KL (>= 0), which turns locking off.
     forced_lock(st, record) -> list of positions, if given, is a workload hook
     (not part of the method) that locks further positions after the rule ran;
     with kl_drives_lock=False the rule's F_t is recorded but not applied.
+    unlock: UnlockParams or None.  When given, re-locking obeys the cool-down and
+    the stricter threshold, and after every unlock.period-th step the read-only
+    probe and the unlock rule of App. 'Optional Unlocking' run (unlock_probe).
     """
     st.t += 1
     t = st.t
@@ -92,7 +120,10 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
     # candidates and lock rule
     m_for_Z = masked_before if candidates_pre_update else st.masked
     F = control.lock_rule(st.lock, m_for_Z, A, D.astype(np.float32), u.astype(np.float32),
-                          np.float32(eps), first_step=(t == 1), gate_m=gate_m)
+                          np.float32(eps), first_step=(t == 1), gate_m=gate_m,
+                          relocked=st.relocked if unlock is not None else None,
+                          cool_until=st.cool_until if unlock is not None else None,
+                          rho=unlock.rho if unlock is not None else 1.0, t=t)
     rec = StepRecord(t=t, active_pos=A, logits=z, kl=D, u=u, conf=conf, argmax=amax,
                      unmasked=unmasked, F=F)
     # posteriors of the active rows become p_{t-1}; locked rows keep p_{t*}
@@ -107,7 +138,43 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
         st.lock[p] = 1
         st.lock_step[p] = t
         st.x_hat[p] = weights["emb"][tokens_in[p]]
+    if unlock is not None and t % unlock.period == 0:
+        rec.probe = unlock_probe(cfg, weights, st, unlock, u.astype(np.float32))
     return rec
+
+
+def unlock_probe(cfg, weights, st, prm, u_active):
+    """App. 'Optional Unlocking', run after step st.t is complete.
+
+    The proxy is the network itself restricted to the locked rows: their
+    current tokens go through all blocks with queries only (keys and values of
+    every slot, their own included, are read from the cache and nothing is
+    written, so the step just taken is unchanged), then the LM head.  This
+    gives u~ = 1 - max p^ and D~ = KL(p^_t || p_{t*}) against the posterior
+    kept from the step the slot locked at.  The unlock rule then clears the
+    lock of the chosen slots, marks them for the stricter re-lock threshold and
+    starts their cool-down; they are active again from step t + 1, where their
+    K/V rows are overwritten (that is the invalidation) and their KL is taken
+    against the last posterior kept for them, p_{t*}.
+    u_active: fp32 uncertainties of this step's active rows (theta_t is their
+    percentile).  Values that decide are rounded to fp32 first.
+    """
+    t = st.t
+    Lpos = np.flatnonzero(st.lock == 1)
+    if len(Lpos) == 0:
+        return ProbeRecord(pos=Lpos, logits=np.zeros((0, cfg.vocab)), u=np.zeros(0), conf=np.zeros(0),
+                           D=np.zeros(0), unlocked=[])
+    z = model.forward_active(cfg, weights, st.tokens, Lpos, st.Kc, st.Vc, write_cache=False)
+    lp = posterior.log_softmax(z)
+    u = posterior.uncertainty(lp)
+    D = posterior.kl_rows(lp, st.prev_lp[Lpos])
+    unlocked = control.unlock_rule(st.lock_step, Lpos, u.astype(np.float32), D.astype(np.float32), u_active,
+                                   prm.m, np.float32(prm.eps_unlock), t, prm.d_interval)
+    for p in unlocked:
+        st.lock[p] = 0
+        st.relocked[p] = 1
+        st.cool_until[p] = t + prm.d_cool
+    return ProbeRecord(pos=Lpos, logits=z, u=u, conf=posterior.max_prob(lp), D=D, unlocked=unlocked)
 
 
 def baseline_step(cfg, weights, tokens, masked, block_lo, block_hi, k):
