@@ -126,7 +126,8 @@ int sl_kv_cache_read(const sl_ctx *ctx, void *stream, int32_t layer, void *k_out
 /* Previous posteriors p_{t-1} (Alg. 1 state; Sec. 2.1: a locked row keeps p_{t*}).
  * Stored in factored form as the rows' logits (type T): log p = z - logsumexp(z) is
  * recomputed on the fly by the KL pass, which needs both rows anyway.  Two buffers
- * [2][B*N][vocab] alternate: step t writes the logits of its active rows into buffer
+ * [2][R][vocab] alternate (R = B*N rounded up so that a buffer is a multiple of 256 bytes;
+ * sl_posterior_bytes / 2 apart): step t writes the logits of its active rows into buffer
  * t & 1 (rows by flat id) and reads p_{t-1} from buffer (t-1) & 1. */
 int sl_posterior_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
 int sl_posterior_bind(sl_ctx *ctx, void *store, size_t bytes);
@@ -208,6 +209,60 @@ int sl_lock_rule_gated(void *stream, const uint8_t *lock, const uint8_t *masked,
                        const int32_t *active_idx, const int32_t *cu_active, int32_t m_upper,
                        const float *kl, const float *conf, const float *eps, float gate_percentile,
                        int32_t batch, int32_t n_seq, int32_t first_step, uint8_t *new_lock);
+
+/* ---- optional unlocking (appendix 'Optional Unlocking') --------------------------------------
+ * Per-position state, device arrays [B*N] owned by the caller and zero-initialised:
+ *   t_lock     i32  the step at which the position locked (t*_i); written by
+ *                   sl_lock_rule_relock, read by the probe and the unlock rule
+ *   relocked   u8   1 = the position has been unlocked before: it re-locks only on
+ *                   D <= rho * eps (product formed in fp32)
+ *   cool_until i32  the position cannot lock while t <= cool_until (= unlock step + D_cool)
+ * A run with unlocking calls, per step t: sl_surelock_step (its new_lock output pointed at
+ * scratch), sl_lock_rule_relock (the rule that counts), and after every P-th step
+ * sl_unlock_probe then sl_unlock_rule.  All three leave the K/V cache untouched; an unlocked
+ * position is simply active again at step t + 1, whose forward overwrites its K/V rows. */
+
+/* The lock rule with the re-lock state: F_t = {i in Z_t : [u_i <= theta_b] and
+ * D_i <= (relocked_i ? rho * eps_b : eps_b) and t > cool_until_i}; new_lock = lock | F_t (may
+ * alias lock); t_lock[i] = t for i in F_t.  gate_percentile <= 0 switches the bracketed gate off,
+ * otherwise it is sl_lock_rule_gated's.  t = 1 locks nothing.  0 < rho <= 1; n_seq <= 15360. */
+int sl_lock_rule_relock(void *stream, const uint8_t *lock, const uint8_t *masked,
+                        const int32_t *active_idx, const int32_t *cu_active, int32_t m_upper,
+                        const float *kl, const float *conf, const float *eps, float gate_percentile,
+                        const uint8_t *relocked, const int32_t *cool_until, float rho, int32_t t,
+                        int32_t batch, int32_t n_seq, uint8_t *new_lock, int32_t *t_lock);
+
+/* The budgeted proxy on the locked rows: their current tokens run through all layers and the
+ * LM head with queries only (keys and values of every slot, their own included, are read from
+ * the cache; nothing is written to it or to the posterior store).  Outputs, packed in the order
+ * of probe_idx:
+ *   probe_idx [>= m_upper] i32  flat ids of the locked rows, ascending; cu_probe [B+1] their
+ *                               per-sequence prefix sums ([B] = count)
+ *   probe_logits [m_upper, vocab] T  proxy logits (16-byte aligned, caller's scratch)
+ *   conf, argmax                max and argmax of the proxy posterior (u~ = 1 - conf)
+ *   kl                          D~ = KL(p^_t || p_{t*}) against the row the store kept from
+ *                               step t_lock (buffer t_lock & 1)
+ * m_upper bounds the number of locked rows (B*N is always valid); workspace as for the step. */
+int sl_unlock_probe(sl_ctx *ctx, void *stream, const int32_t *tokens, const uint8_t *lock,
+                    const int32_t *t_lock, int32_t m_upper, int32_t *probe_idx, int32_t *cu_probe,
+                    void *probe_logits, float *kl, float *conf, int32_t *argmax,
+                    void *workspace, size_t workspace_bytes);
+
+/* The unlock rule (the appendix's displayed condition, a conjunction): per sequence, theta =
+ * the percentile-th percentile (nearest rank, as for the gate) of u = max(0, 1 - conf_active)
+ * over ALL active rows of step t (cu_active / conf_active as the step left them; no active row:
+ * the first test passes); a probed position g unlocks iff
+ *   u~ > theta  and  D~ > eps_unlock  and  t - t_lock[g] > d_interval      (all strict).
+ * Then lock[g] = 0, relocked[g] = 1, cool_until[g] = t + d_cool, unlocked[r] = 1 (else 0; r the
+ * probe row), and if the row's kept posterior lies in the buffer step t + 1 will not read
+ * (t_lock and t of different parity) it is copied to the other, so that D_{t+1} is taken
+ * against p_{t*}.  lock is updated in place. */
+int sl_unlock_rule(sl_ctx *ctx, void *stream, uint8_t *lock, uint8_t *relocked, int32_t *cool_until,
+                   const int32_t *t_lock, const int32_t *probe_idx, const int32_t *cu_probe,
+                   int32_t m_upper_probe, const float *kl_probe, const float *conf_probe,
+                   const int32_t *cu_active, int32_t m_upper_active, const float *conf_active,
+                   float percentile, float eps_unlock, int32_t t, int32_t d_interval, int32_t d_cool,
+                   uint8_t *unlocked);
 
 /* lock_test(eps): Alg. 1 from 'Unmasking' to 'Lock' on given logits = score ->
  * UpdateMASK -> candidates -> lock rule, in that order. */

@@ -52,6 +52,9 @@ _SIGS = {
     "sl_unmask_topk": [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I],
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
     "sl_lock_rule_gated": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _I, _I, _I, _P],
+    "sl_lock_rule_relock": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _P, _P, C.c_float, _I, _I, _I, _P, _P],
+    "sl_unlock_probe": [_P, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
+    "sl_unlock_rule": [_P, _P, _P, _P, _P, _P, _P, _P, _I, _P, _P, _P, _I, _P, C.c_float, C.c_float, _I, _I, _I, _P],
     "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
     "sl_linear_splits": [_I, _I, _I],
     "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
@@ -227,6 +230,28 @@ def sl_lock_rule_gated(lock, masked, active_idx, cu_active, m_upper, kl, conf, e
         C.c_float(gate_percentile), batch, n_seq, int(first_step), _ptr(new_lock)))
 
 
+def sl_lock_rule_relock(lock, masked, active_idx, cu_active, m_upper, kl, conf, eps, gate_percentile, relocked,
+                        cool_until, rho, t, batch, n_seq, new_lock, t_lock):
+    _check("sl_lock_rule_relock", lib().sl_lock_rule_relock(
+        _stream(), _ptr(lock), _ptr(masked), _ptr(active_idx), _ptr(cu_active), m_upper, _ptr(kl), _ptr(conf), _ptr(eps),
+        C.c_float(gate_percentile), _ptr(relocked), _ptr(cool_until), C.c_float(rho), t, batch, n_seq, _ptr(new_lock),
+        _ptr(t_lock)))
+
+
+def sl_unlock_probe(ctx, tokens, lock, t_lock, m_upper, probe_idx, cu_probe, probe_logits, kl, conf, argmax, workspace):
+    _check("sl_unlock_probe", lib().sl_unlock_probe(
+        ctx, _stream(), _ptr(tokens), _ptr(lock), _ptr(t_lock), m_upper, _ptr(probe_idx), _ptr(cu_probe),
+        _ptr(probe_logits), _ptr(kl), _ptr(conf), _ptr(argmax), _ptr(workspace), workspace.numel()))
+
+
+def sl_unlock_rule(ctx, lock, relocked, cool_until, t_lock, probe_idx, cu_probe, m_upper_probe, kl_probe, conf_probe,
+                   cu_active, m_upper_active, conf_active, percentile, eps_unlock, t, d_interval, d_cool, unlocked):
+    _check("sl_unlock_rule", lib().sl_unlock_rule(
+        ctx, _stream(), _ptr(lock), _ptr(relocked), _ptr(cool_until), _ptr(t_lock), _ptr(probe_idx), _ptr(cu_probe),
+        m_upper_probe, _ptr(kl_probe), _ptr(conf_probe), _ptr(cu_active), m_upper_active, _ptr(conf_active),
+        C.c_float(percentile), C.c_float(eps_unlock), t, d_interval, d_cool, _ptr(unlocked)))
+
+
 def sl_lock_test(logits_cur, cur_packed, logits_prev, dtype, vocab, tokens, masked, lock, active_idx, cu_active,
                  m_upper, eps, batch, n_seq, first_step, block_lo, block_hi, k, kl, conf, argmax, new_lock):
     _check("sl_lock_test", lib().sl_lock_test(
@@ -326,6 +351,50 @@ class Session:
         sl_surelock_step(self.ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, self.active_idx,
                          self.cu_active, self.kl, self.conf, self.argmax, new_lock, self.workspace)
         return new_lock
+
+    # -- optional unlocking: per-position state and probe outputs, allocated on first use --
+    def unlock_state(self):
+        if not hasattr(self, "t_lock"):
+            dev, R = self.device, self.B * self.N
+            self.t_lock = torch.zeros(R, dtype=torch.int32, device=dev)
+            self.cool_until = torch.zeros(R, dtype=torch.int32, device=dev)
+            self.relocked = torch.zeros(R, dtype=torch.uint8, device=dev)
+            self.probe_idx = torch.zeros(R, dtype=torch.int32, device=dev)
+            self.cu_probe = torch.zeros(self.B + 1, dtype=torch.int32, device=dev)
+            self.probe_logits = torch.zeros(R, self.shape.vocab, dtype=self.T, device=dev)
+            self.probe_kl = torch.zeros(R, dtype=torch.float32, device=dev)
+            self.probe_conf = torch.zeros(R, dtype=torch.float32, device=dev)
+            self.probe_argmax = torch.zeros(R, dtype=torch.int32, device=dev)
+            self.unlocked = torch.zeros(R, dtype=torch.uint8, device=dev)
+            self.rule_scratch = torch.zeros(R, dtype=torch.uint8, device=dev)
+        return self
+
+    def step_unlockable(self, tokens, masked, lock, eps, t, block_lo, block_hi, k, rho, gate_percentile=0.0,
+                        m_upper=None):
+        """One step whose lock rule obeys the cool-down and the stricter re-lock threshold and
+        records the lock time: the step's own rule output is discarded, sl_lock_rule_relock decides
+        (on the masked flags UpdateMASK left, the default candidate reading).  lock is updated in place."""
+        self.unlock_state()
+        m_upper = self.B * self.N if m_upper is None else m_upper
+        sl_surelock_step(self.ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, self.active_idx,
+                         self.cu_active, self.kl, self.conf, self.argmax, self.rule_scratch, self.workspace)
+        sl_lock_rule_relock(lock, masked, self.active_idx, self.cu_active, m_upper, self.kl, self.conf, eps,
+                            gate_percentile, self.relocked, self.cool_until, rho, t, self.B, self.N, lock, self.t_lock)
+        return lock
+
+    def unlock_probe(self, tokens, lock, t, percentile, eps_unlock, d_interval, d_cool, m_upper_probe=None,
+                     m_upper_active=None):
+        """The read-only probe on the locked rows followed by the unlock rule, after step t."""
+        self.unlock_state()
+        R = self.B * self.N
+        mp = R if m_upper_probe is None else m_upper_probe
+        ma = R if m_upper_active is None else m_upper_active
+        sl_unlock_probe(self.ctx, tokens, lock, self.t_lock, mp, self.probe_idx, self.cu_probe, self.probe_logits,
+                        self.probe_kl, self.probe_conf, self.probe_argmax, self.workspace)
+        sl_unlock_rule(self.ctx, lock, self.relocked, self.cool_until, self.t_lock, self.probe_idx, self.cu_probe, mp,
+                       self.probe_kl, self.probe_conf, self.cu_active, ma, self.conf, percentile, eps_unlock, t,
+                       d_interval, d_cool, self.unlocked)
+        return lock
 
     def logits_view(self, t):
         """[B*N, V] tensor view of the posterior buffer step t writes (rows by flat id)."""

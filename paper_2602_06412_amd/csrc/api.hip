@@ -186,9 +186,19 @@ extern "C" int sl_kv_cache_read(const sl_ctx* ctx, void* stream, int32_t layer, 
 }
 
 // ---- posterior store -----------------------------------------------------------------------------
+// Rows per buffer: B*N rounded up until a buffer is a whole number of 256-byte units, so that the
+// second buffer starts aligned AND a whole number of rows after the first (row index B*N' + g of
+// the first buffer is row g of the second).
+static size_t post_rows(const sl_ctx* ctx, int32_t batch, int32_t n_seq) {
+  const size_t row_bytes = (size_t)ctx->cfg.vocab * sl_tsize(ctx->cfg.dtype);
+  size_t unit = 256;
+  while (unit > 1 && row_bytes % unit) unit >>= 1;          // largest power of two <= 256 dividing a row
+  return sl_align_up((size_t)batch * n_seq, 256 / unit);
+}
+
 extern "C" int sl_posterior_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
   if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
-  *out = 2 * sl_align_up((size_t)batch * n_seq * ctx->cfg.vocab * sl_tsize(ctx->cfg.dtype), 256);
+  *out = 2 * post_rows(ctx, batch, n_seq) * ctx->cfg.vocab * sl_tsize(ctx->cfg.dtype);
   return SL_OK;
 }
 
@@ -199,7 +209,7 @@ extern "C" int sl_posterior_bind(sl_ctx* ctx, void* store, size_t bytes) {
   sl_posterior_bytes(ctx, ctx->batch, ctx->n_seq, &need);
   if (bytes < need) return SL_ENOSPC;
   ctx->post = store;
-  ctx->post_buf_elems = need / 2 / sl_tsize(ctx->cfg.dtype);
+  ctx->post_buf_elems = post_rows(ctx, ctx->batch, ctx->n_seq) * ctx->cfg.vocab;
   return SL_OK;
 }
 
@@ -280,7 +290,8 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_generic(s, dt, ws.h, L.wv, m_dev, mu, hd, d, ws.f32 + 2 * hd, nullptr, nullptr, 3 * (size_t)hd));
     // RoPE; live K/V overwrite the rows' own cache slots (locked slots are never touched)
     SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, dt, ws.f32, 1, 0, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
-                             kv_k_layer(ctx, l), kv_v_layer(ctx, l)));
+                             ctx->probe_read_only ? nullptr : kv_k_layer(ctx, l),
+                             ctx->probe_read_only ? nullptr : kv_v_layer(ctx, l)));
     SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
                                  ctx->n_seq, ctx->n_pad, ws.o));
     SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));
@@ -368,6 +379,19 @@ extern "C" int sl_lock_rule_gated(void* stream, const uint8_t* lock, const uint8
   if (!(gate_percentile > 0.f) || gate_percentile > 100.f) return SL_EINVAL;
   return slk_lock_rule_gated((hipStream_t)stream, lock, masked, active_idx, cu_active, m_upper, kl, conf, eps,
                              gate_percentile, batch, n_seq, first_step, new_lock);
+}
+
+extern "C" int sl_lock_rule_relock(void* stream, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                                   const int32_t* cu_active, int32_t m_upper, const float* kl, const float* conf,
+                                   const float* eps, float gate_percentile, const uint8_t* relocked,
+                                   const int32_t* cool_until, float rho, int32_t t, int32_t batch, int32_t n_seq,
+                                   uint8_t* new_lock, int32_t* t_lock) {
+  if (!lock || !masked || !active_idx || !cu_active || !kl || !conf || !eps || !new_lock) return SL_EINVAL;
+  if (!relocked || !cool_until || !t_lock) return SL_EINVAL;
+  if (batch < 1 || n_seq < 1 || m_upper < 0 || t < 1) return SL_EINVAL;
+  if (gate_percentile > 100.f || !(rho > 0.f) || rho > 1.f) return SL_EINVAL;
+  return slk_lock_rule_relock((hipStream_t)stream, lock, masked, active_idx, cu_active, m_upper, kl, conf, eps,
+                              gate_percentile, relocked, cool_until, rho, t, batch, n_seq, new_lock, t_lock);
 }
 
 extern "C" int sl_lock_test(void* stream, const void* logits_cur, int32_t cur_packed, const void* logits_prev,
@@ -467,4 +491,64 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
   if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;
+}
+
+// ---- optional unlocking ------------------------------------------------------------------------------
+extern "C" int sl_unlock_probe(sl_ctx* ctx, void* stream, const int32_t* tokens, const uint8_t* lock,
+                               const int32_t* t_lock, int32_t m_upper, int32_t* probe_idx, int32_t* cu_probe,
+                               void* probe_logits, float* kl, float* conf, int32_t* argmax, void* workspace,
+                               size_t workspace_bytes) {
+  SL_TRY(check_ready(ctx, true));
+  if (!tokens || !lock || !t_lock || !probe_idx || !cu_probe || !probe_logits || !kl || !conf || !argmax || !workspace)
+    return SL_EINVAL;
+  const int B = ctx->batch, N = ctx->n_seq;
+  if (m_upper < 1 || m_upper > B * N) return SL_EINVAL;
+  if ((uintptr_t)workspace % 256 || (uintptr_t)probe_logits % 16) return SL_EINVAL;
+  const Workspace ws = carve(ctx, workspace, m_upper, B, N);
+  if (workspace_bytes < ws.bytes) return SL_ENOSPC;
+  hipStream_t s = (hipStream_t)stream;
+  const sl_config& c = ctx->cfg;
+  const int32_t* m_dev = cu_probe + B;
+  // L_t, the rows the probe visits
+  SL_TRY(slk_compact_active(s, lock, B, N, probe_idx, cu_probe, 1));
+  SL_TRY(slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, probe_idx, m_dev, m_upper, c.d_model, c.vocab,
+                           ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
+  // queries only: keys and values of every slot come from the cache, nothing is written
+  ctx->probe_read_only = true;
+  const int rc = run_layers(ctx, s, ws, probe_idx, m_dev, m_upper, 0, c.n_layers);
+  ctx->probe_read_only = false;
+  SL_TRY(rc);
+  // proxy logits, packed in probe order
+  if (ctx->use_mfma)
+    SL_TRY(sl_mfma_lm_head(ctx, s, ws.h, nullptr, m_dev, m_upper, probe_logits));
+  else
+    SL_TRY(slk_gemm_generic(s, c.dtype, ws.h, ctx->plain.lm_head, m_dev, m_upper, c.vocab, c.d_model, nullptr,
+                            probe_logits, nullptr, c.vocab));
+  // u~ (as conf) and D~ = KL(p^_t || p_{t*}): the kept row of a position locked at t* lies in buffer t* & 1
+  int32_t* prev_rows = (int32_t*)ws.q;                   // the query buffer is free again
+  SL_TRY(slk_probe_prev_rows(s, probe_idx, m_dev, m_upper, t_lock, (int)(ctx->post_buf_elems / c.vocab), prev_rows));
+  return slk_score(s, probe_logits, 1, ctx->post, c.dtype, c.vocab, prev_rows, m_dev, m_upper, 0, kl, conf, argmax,
+                   ws.score);
+}
+
+extern "C" int sl_unlock_rule(sl_ctx* ctx, void* stream, uint8_t* lock, uint8_t* relocked, int32_t* cool_until,
+                              const int32_t* t_lock, const int32_t* probe_idx, const int32_t* cu_probe,
+                              int32_t m_upper_probe, const float* kl_probe, const float* conf_probe,
+                              const int32_t* cu_active, int32_t m_upper_active, const float* conf_active,
+                              float percentile, float eps_unlock, int32_t t, int32_t d_interval, int32_t d_cool,
+                              uint8_t* unlocked) {
+  SL_TRY(check_ready(ctx, true));
+  if (!lock || !relocked || !cool_until || !t_lock || !probe_idx || !cu_probe || !kl_probe || !conf_probe ||
+      !cu_active || !conf_active || !unlocked)
+    return SL_EINVAL;
+  const int B = ctx->batch, N = ctx->n_seq;
+  if (m_upper_probe < 1 || m_upper_probe > B * N || m_upper_active < 0 || m_upper_active > B * N) return SL_EINVAL;
+  if (!(percentile > 0.f) || percentile > 100.f || t < 1 || d_interval < 0 || d_cool < 0) return SL_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  SL_TRY(slk_unlock_rule(s, lock, relocked, cool_until, t_lock, probe_idx, cu_probe, m_upper_probe, kl_probe,
+                         conf_probe, cu_active, m_upper_active, conf_active, percentile, eps_unlock, t, d_interval,
+                         d_cool, B, N, unlocked));
+  const size_t ts = sl_tsize(ctx->cfg.dtype);
+  return slk_posterior_carry(s, ctx->post, ctx->post_buf_elems * ts, (size_t)ctx->cfg.vocab * ts, probe_idx,
+                             cu_probe + B, m_upper_probe, t_lock, unlocked, t);
 }

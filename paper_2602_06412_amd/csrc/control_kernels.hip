@@ -8,7 +8,7 @@
 // the rank inside a wave, an LDS scan over the 16 wave totals gives the rank inside the
 // chunk, a running base carries across chunks.  cu_active[b] is the rank of flat id b*N.
 __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __restrict__ lock, int B, int N,
-                                                              int32_t* __restrict__ active_idx,
+                                                              int select_locked, int32_t* __restrict__ active_idx,
                                                               int32_t* __restrict__ cu_active) {
   __shared__ int wave_tot[16];
   __shared__ int base_sh;
@@ -18,7 +18,7 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __r
   __syncthreads();
   for (int start = 0; start < total; start += 1024) {
     const int g = start + tid;
-    const bool act = (g < total) && (lock[g] == 0);
+    const bool act = (g < total) && ((lock[g] != 0) == (select_locked != 0));
     const unsigned long long bal = __ballot(act);
     const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
     if (lane == 0) wave_tot[wave] = __popcll(bal);
@@ -43,8 +43,10 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __r
   if (tid == 0) cu_active[B] = base_sh;
 }
 
-int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active) {
-  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, s, lock, B, N, active_idx, cu_active);
+// select_locked = 0: the unlocked positions (A_t); 1: the locked ones (L_t, the rows the unlock probe visits)
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active,
+                       int select_locked) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, s, lock, B, N, select_locked, active_idx, cu_active);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -174,30 +176,100 @@ int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, con
   return SL_OK;
 }
 
-// ---- lock rule with the confidence gate: theta_b = nearest-rank percentile of u over Z_t -----
-// One workgroup per sequence.  The candidates' u = max(0, 1 - conf) (non-negative floats, whose bit
-// patterns order like the values) are collected in LDS; the rank-th smallest is found by a 4-pass
-// radix select (thread b owns bin b, shuffle prefix sums); then F_t = {u <= theta and D <= eps}.
+// ---- nearest-rank selection over non-negative floats held in LDS as their bit patterns --------
+// The rank-th smallest of keys[0..n) (1 <= rank <= n) by a 4-pass radix select: thread b owns bin b,
+// a shuffle prefix sum over the histogram tells it how many keys sit in lower bins, exactly one thread
+// finds the wanted rank in its bin.  exact = false may stop early and return an upper bound of the
+// value that no larger key reaches (enough for "key <= result" tests on the keys themselves);
+// exact = true returns the value itself.  Called by all 256 threads of the workgroup.
+struct SelectShared {
+  int hist[256];
+  int wave_tot[4];
+  int want, done;
+  unsigned int prefix;
+};
+
+__device__ static unsigned int select_rank_smallest(const unsigned int* keys, int n, int rank, bool exact,
+                                                    SelectShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __syncthreads();
+  if (tid == 0) { sh.prefix = 0; sh.want = rank; sh.done = 0; }
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    sh.hist[tid] = 0;
+    __syncthreads();
+    const unsigned int prefix = sh.prefix;
+    const int want = sh.want;
+    const unsigned int himask = shift == 24 ? 0u : (~0u << (shift + 8));
+    for (int e = tid; e < n; e += 256) {
+      const unsigned int key = keys[e];
+      if ((key & himask) == prefix) atomicAdd(&sh.hist[(key >> shift) & 0xff], 1);
+    }
+    __syncthreads();
+    const int c = sh.hist[tid];
+    int incl = c;                                // keys in bins 64*wave .. tid
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += y;
+    }
+    if (lane == 63) sh.wave_tot[wave] = incl;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) incl += sh.wave_tot[w];      // keys in bins <= tid
+    const int below = incl - c;
+    if (below < want && want <= incl) {
+      sh.prefix = prefix | ((unsigned int)tid << shift);
+      sh.want = want - below;
+      // everything in this bin is still wanted: the bin's largest possible key is a valid bound and
+      // the remaining bytes need not be examined
+      if (!exact && want - below == c) {
+        sh.prefix = prefix | ((unsigned int)tid << shift) | (shift ? ((1u << shift) - 1u) : 0u);
+        sh.done = 1;
+      }
+    }
+    __syncthreads();
+    if (sh.done) break;
+  }
+  return sh.prefix;
+}
+
+__device__ static inline int nearest_rank(double m, int n) {
+  int rank = (int)ceil(m * (double)n / 100.0);
+  return rank < 1 ? 1 : (rank > n ? n : rank);
+}
+
+// ---- lock rule with the confidence gate and the re-lock state -------------------------------------
+// One workgroup per sequence.  Gate (gate_m > 0): the candidates' u = max(0, 1 - conf) (non-negative
+// floats, whose bit patterns order like the values) are collected in LDS, theta_b = their nearest-rank
+// percentile, F_t = {u <= theta and D <= eps}.  Re-lock state (relocked != null; optional unlocking):
+// a position unlocked before needs D <= rho * eps and cannot lock while t <= cool_until.  t_lock, if
+// given, receives t at the positions locked by this call.
+struct RelockArgs {
+  const uint8_t* relocked;
+  const int32_t* cool_until;
+  float rho;
+  int t;
+  int32_t* t_lock;
+};
+
 __global__ __launch_bounds__(256) void lock_rule_gated_kernel(const uint8_t* lock, const uint8_t* __restrict__ masked,
                                                               const int32_t* __restrict__ active_idx,
                                                               const int32_t* __restrict__ cu_active, int m_upper,
                                                               const float* __restrict__ kl,
                                                               const float* __restrict__ conf,
                                                               const float* __restrict__ eps, double gate_m, int N,
-                                                              int first_step, uint8_t* new_lock) {
+                                                              int first_step, uint8_t* new_lock, RelockArgs rs) {
   extern __shared__ unsigned int ukeys[];          // [N]
-  __shared__ int count, want_sh, done_sh;
-  __shared__ unsigned int prefix_sh;
-  __shared__ int hist[256];
-  __shared__ int wave_tot[4];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ int count;
+  __shared__ SelectShared sel;
+  const int b = blockIdx.x, tid = threadIdx.x;
   const int r0 = min(cu_active[b], m_upper), r1 = min(cu_active[b + 1], m_upper);
   // positions locked before stay locked (threads beyond the row range take no part in the rest)
   for (int p = tid; p < N; p += 256)
     if (lock[(size_t)b * N + p]) new_lock[(size_t)b * N + p] = 1;
   if (tid == 0) count = 0;
   __syncthreads();
-  if (!first_step) {
+  const bool gate = gate_m > 0.0;
+  if (!first_step && gate) {
     for (int r = r0 + tid; r < r1; r += 256) {
       if (masked[active_idx[r]] == 0) {
         const int slot = atomicAdd(&count, 1);
@@ -207,51 +279,22 @@ __global__ __launch_bounds__(256) void lock_rule_gated_kernel(const uint8_t* loc
   }
   __syncthreads();
   const int n = count;
-  unsigned int theta = 0;
-  if (n > 0) {
-    int rank = (int)ceil(gate_m * (double)n / 100.0);
-    rank = rank < 1 ? 1 : (rank > n ? n : rank);
-    if (tid == 0) { prefix_sh = 0; want_sh = rank; done_sh = 0; }
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      hist[tid] = 0;
-      __syncthreads();
-      const unsigned int prefix = prefix_sh;
-      const int want = want_sh;
-      const unsigned int himask = shift == 24 ? 0u : (~0u << (shift + 8));
-      for (int e = tid; e < n; e += 256) {
-        const unsigned int key = ukeys[e];
-        if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 0xff], 1);
-      }
-      __syncthreads();
-      const int c = hist[tid];
-      int incl = c;                                // keys in bins 64*wave .. tid
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const int y = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += y;
-      }
-      if (lane == 63) wave_tot[wave] = incl;
-      __syncthreads();
-      for (int w = 0; w < wave; ++w) incl += wave_tot[w];      // keys in bins <= tid
-      const int below = incl - c;
-      if (below < want && want <= incl) {
-        // everything in this bin that is still wanted: if that is the whole bin, the bin's largest
-        // possible key is a valid threshold and the remaining bytes need not be examined
-        prefix_sh = prefix | ((unsigned int)tid << shift);
-        want_sh = want - below;
-        if (want - below == c) { prefix_sh = prefix | ((unsigned int)tid << shift) | (shift ? ((1u << shift) - 1u) : 0u); done_sh = 1; }
-      }
-      __syncthreads();
-      if (done_sh) break;
-    }
-    theta = prefix_sh;
-  }
+  unsigned int theta = gate ? 0u : 0xffffffffu;
+  if (n > 0) theta = select_rank_smallest(ukeys, n, nearest_rank(gate_m, n), false, sel);
   for (int r = r0 + tid; r < r1; r += 256) {
     const int g = active_idx[r];
     bool F = false;
-    if (!first_step && masked[g] == 0)
-      F = __float_as_uint(fmaxf(0.f, 1.0f - conf[r])) <= theta && kl[r] <= eps[b];
+    if (!first_step && masked[g] == 0) {
+      float e = eps[b];
+      bool cooled = true;
+      if (rs.relocked != nullptr) {
+        if (rs.relocked[g]) e = rs.rho * e;
+        cooled = rs.t > rs.cool_until[g];
+      }
+      F = cooled && __float_as_uint(fmaxf(0.f, 1.0f - conf[r])) <= theta && kl[r] <= e;
+    }
     new_lock[g] = F ? 1 : 0;
+    if (F && rs.t_lock != nullptr) rs.t_lock[g] = rs.t;
   }
 }
 
@@ -260,7 +303,123 @@ int slk_lock_rule_gated(hipStream_t s, const uint8_t* lock, const uint8_t* maske
                         float gate_m, int B, int N, int first_step, uint8_t* new_lock) {
   if ((size_t)N * 4 > 60 * 1024) return SL_EINVAL;
   hipLaunchKernelGGL(lock_rule_gated_kernel, dim3(B), dim3(256), (size_t)N * 4, s, lock, masked, active_idx, cu_active,
-                     m_upper, kl, conf, eps, (double)gate_m, N, first_step, new_lock);
+                     m_upper, kl, conf, eps, (double)gate_m, N, first_step, new_lock,
+                     RelockArgs{nullptr, nullptr, 1.f, 0, nullptr});
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// gate_m <= 0: no gate
+int slk_lock_rule_relock(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                         const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
+                         float gate_m, const uint8_t* relocked, const int32_t* cool_until, float rho, int t, int B,
+                         int N, uint8_t* new_lock, int32_t* t_lock) {
+  if ((size_t)N * 4 > 60 * 1024) return SL_EINVAL;
+  hipLaunchKernelGGL(lock_rule_gated_kernel, dim3(B), dim3(256), (size_t)N * 4, s, lock, masked, active_idx, cu_active,
+                     m_upper, kl, conf, eps, (double)gate_m, N, t == 1 ? 1 : 0, new_lock,
+                     RelockArgs{relocked, cool_until, rho, t, t_lock});
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// ---- the unlock rule (optional unlocking): one workgroup per sequence -------------------------------
+// theta_b = nearest-rank percentile of u = max(0, 1 - conf) over ALL active rows of the sequence (exact
+// value: the probed rows compared with it are not among the keys); a probed locked position g unlocks iff
+//   u~ > theta  and  D~ > eps_unlock  and  t - t_lock[g] > d_interval.
+// An unlocked position gets lock = 0, relocked = 1, cool_until = t + d_cool; unlocked[r] flags the row.
+__global__ __launch_bounds__(256) void unlock_rule_kernel(uint8_t* lock, uint8_t* relocked, int32_t* cool_until,
+                                                          const int32_t* __restrict__ t_lock,
+                                                          const int32_t* __restrict__ probe_idx,
+                                                          const int32_t* __restrict__ cu_probe, int mp_upper,
+                                                          const float* __restrict__ kl_probe,
+                                                          const float* __restrict__ conf_probe,
+                                                          const int32_t* __restrict__ cu_active, int ma_upper,
+                                                          const float* __restrict__ conf_active, double m,
+                                                          float eps_unlock, int t, int d_interval, int d_cool,
+                                                          uint8_t* __restrict__ unlocked) {
+  extern __shared__ unsigned int ukeys[];          // [N]
+  __shared__ SelectShared sel;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int a0 = min(cu_active[b], ma_upper), a1 = min(cu_active[b + 1], ma_upper);
+  const int n = a1 - a0;
+  for (int r = tid; r < n; r += 256) ukeys[r] = __float_as_uint(fmaxf(0.f, 1.0f - conf_active[a0 + r]));
+  __syncthreads();
+  unsigned int theta = 0;
+  if (n > 0) theta = select_rank_smallest(ukeys, n, nearest_rank(m, n), true, sel);
+  const int p0 = min(cu_probe[b], mp_upper), p1 = min(cu_probe[b + 1], mp_upper);
+  for (int r = p0 + tid; r < p1; r += 256) {
+    const int g = probe_idx[r];
+    const unsigned int uk = __float_as_uint(fmaxf(0.f, 1.0f - conf_probe[r]));
+    const bool un = (n == 0 || uk > theta) && kl_probe[r] > eps_unlock && t - t_lock[g] > d_interval;
+    unlocked[r] = un ? 1 : 0;
+    if (un) {
+      lock[g] = 0;
+      relocked[g] = 1;
+      cool_until[g] = t + d_cool;
+    }
+  }
+}
+
+int slk_unlock_rule(hipStream_t s, uint8_t* lock, uint8_t* relocked, int32_t* cool_until, const int32_t* t_lock,
+                    const int32_t* probe_idx, const int32_t* cu_probe, int mp_upper, const float* kl_probe,
+                    const float* conf_probe, const int32_t* cu_active, int ma_upper, const float* conf_active, float m,
+                    float eps_unlock, int t, int d_interval, int d_cool, int B, int N, uint8_t* unlocked) {
+  if ((size_t)N * 4 > 60 * 1024) return SL_EINVAL;
+  hipLaunchKernelGGL(unlock_rule_kernel, dim3(B), dim3(256), (size_t)N * 4, s, lock, relocked, cool_until, t_lock,
+                     probe_idx, cu_probe, mp_upper, kl_probe, conf_probe, cu_active, ma_upper, conf_active, (double)m,
+                     eps_unlock, t, d_interval, d_cool, unlocked);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// ---- where a probed row's kept posterior lies ---------------------------------------------------------
+// The posterior store holds two buffers of buf_rows rows each; the step taken at time t writes buffer
+// t & 1, so a position locked at t* keeps p_{t*} in buffer t* & 1.  prev_rows[r] = that row's index
+// counted from the start of the first buffer.
+__global__ void probe_prev_rows_kernel(const int32_t* __restrict__ probe_idx, const int32_t* __restrict__ m_dev,
+                                       int m_upper, const int32_t* __restrict__ t_lock, int buf_rows,
+                                       int32_t* __restrict__ prev_rows) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= min(*m_dev, m_upper)) return;
+  const int g = probe_idx[r];
+  prev_rows[r] = (t_lock[g] & 1) * buf_rows + g;
+}
+
+int slk_probe_prev_rows(hipStream_t s, const int32_t* probe_idx, const int32_t* m_dev, int m_upper,
+                        const int32_t* t_lock, int buf_rows, int32_t* prev_rows) {
+  if (m_upper <= 0) return SL_OK;
+  hipLaunchKernelGGL(probe_prev_rows_kernel, dim3(sl_cdiv(m_upper, 256)), dim3(256), 0, s, probe_idx, m_dev, m_upper,
+                     t_lock, buf_rows, prev_rows);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// ---- carrying p_{t*} of an unlocked position to where step t + 1 looks for p_t -----------------------
+// Step t + 1 reads the previous posterior from buffer t & 1.  A position unlocked at t whose kept row
+// lies in the other buffer (t_lock and t of different parity) has it copied across; 16-byte units.
+__global__ __launch_bounds__(256) void posterior_carry_kernel(uint4* __restrict__ store, size_t buf_units,
+                                                              size_t row_units,
+                                                              const int32_t* __restrict__ probe_idx,
+                                                              const int32_t* __restrict__ m_dev, int m_upper,
+                                                              const int32_t* __restrict__ t_lock,
+                                                              const uint8_t* __restrict__ unlocked, int t) {
+  const int r = blockIdx.x;
+  if (r >= min(*m_dev, m_upper) || !unlocked[r]) return;
+  const int g = probe_idx[r];
+  const int from = t_lock[g] & 1, to = t & 1;
+  if (from == to) return;
+  const uint4* src = store + from * buf_units + (size_t)g * row_units;
+  uint4* dst = store + to * buf_units + (size_t)g * row_units;
+  for (size_t e = (size_t)blockIdx.y * 256 + threadIdx.x; e < row_units; e += (size_t)gridDim.y * 256) dst[e] = src[e];
+}
+
+int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const int32_t* probe_idx,
+                        const int32_t* m_dev, int m_upper, const int32_t* t_lock, const uint8_t* unlocked, int t) {
+  if (m_upper <= 0) return SL_OK;
+  if (row_bytes % 16 || buf_bytes % 16 || (uintptr_t)store % 16) return SL_EINVAL;
+  const int chunks = (int)((row_bytes / 16 + 2047) / 2048);
+  hipLaunchKernelGGL(posterior_carry_kernel, dim3(m_upper, chunks > 0 ? chunks : 1), dim3(256), 0, s, (uint4*)store,
+                     buf_bytes / 16, row_bytes / 16, probe_idx, m_dev, m_upper, t_lock, unlocked, t);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

@@ -105,6 +105,7 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restr
     }
     st<T>::stv(q + (size_t)r * hd + c0, q0 * cs.x - q1 * cs.y);
     st<T>::stv(q + (size_t)r * hd + c1, q1 * cs.x + q0 * cs.y);
+    if (kc == nullptr) continue;                         // read-only probe: queries only
     const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
     st<T>::stv(kc + head_base + kc_index(i, j, dh), k0 * cs.x - k1 * cs.y);
     st<T>::stv(kc + head_base + kc_index(i, j + half, dh), k1 * cs.x + k0 * cs.y);
@@ -352,6 +353,7 @@ __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __r
     }
     st4(q + (size_t)r * hd + c0, qa);
     st4(q + (size_t)r * hd + c1, qb);
+    if (kc == nullptr) continue;                         // read-only probe: queries only
     const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
     st4(kc + head_base + kc_index(i, j, dh), ka);
     st4(kc + head_base + kc_index(i, j + half, dh), kb);
@@ -560,15 +562,17 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
                       const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc,
                       void* vc) {
   if (m_upper <= 0) return SL_OK;
+  if ((kc == nullptr) != (vc == nullptr)) return SL_EINVAL;
+  // kc = vc = null: rotate and store the queries only (the row-per-workgroup kernels skip the cache stores)
   // thin launches are latency-bound (wide accesses, few instructions win); thick ones are bound by the
   // scattered 2-byte V stores, where the element-wise kernel's many threads per row do better
-  if (m_upper <= 256 && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
+  if ((m_upper <= 256 || kc == nullptr) && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
     hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
                        m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
-  if (dtype == SL_BF16 && dh == 128 && sstride % 4 == 0 && N % 16 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
+  if (kc != nullptr && dtype == SL_BF16 && dh == 128 && sstride % 4 == 0 && N % 16 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
     const int row_blocks = sl_cdiv(m_upper, 16);
     int hs = 1;                                          // head groups: aim at two workgroups per CU
     while (hs < H && H % (hs * 2) == 0 && row_blocks * hs < 512) hs *= 2;

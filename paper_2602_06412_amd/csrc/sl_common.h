@@ -141,6 +141,8 @@ struct sl_ctx {
   void* kv; int32_t batch, n_seq, n_pad; size_t kv_layer_elems;   // elements of T per layer per K (= per V)
   // posterior store
   void* post; size_t post_buf_elems;
+  // true while the read-only unlock probe runs: the forward stores queries only, no K/V
+  bool probe_read_only;
 };
 
 // Run one launcher call, bracketed by an event pair when profiling is on.
@@ -162,7 +164,20 @@ struct sl_ctx {
 int slk_lock_rule_gated(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                         const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
                         float gate_m, int B, int N, int first_step, uint8_t* new_lock);
-int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active);
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active,
+                       int select_locked = 0);
+int slk_lock_rule_relock(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
+                         const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
+                         float gate_m, const uint8_t* relocked, const int32_t* cool_until, float rho, int t, int B,
+                         int N, uint8_t* new_lock, int32_t* t_lock);
+int slk_unlock_rule(hipStream_t s, uint8_t* lock, uint8_t* relocked, int32_t* cool_until, const int32_t* t_lock,
+                    const int32_t* probe_idx, const int32_t* cu_probe, int mp_upper, const float* kl_probe,
+                    const float* conf_probe, const int32_t* cu_active, int ma_upper, const float* conf_active, float m,
+                    float eps_unlock, int t, int d_interval, int d_cool, int B, int N, uint8_t* unlocked);
+int slk_probe_prev_rows(hipStream_t s, const int32_t* probe_idx, const int32_t* m_dev, int m_upper,
+                        const int32_t* t_lock, int buf_rows, int32_t* prev_rows);
+int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const int32_t* probe_idx,
+                        const int32_t* m_dev, int m_upper, const int32_t* t_lock, const uint8_t* unlocked, int t);
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
                     const int32_t* cu_active, const float* conf, const int32_t* argmax,
                     int B, int N, int lo, int hi, int k);

@@ -115,3 +115,71 @@ def unmask_is_valid(step, N, tokens_gpu, masked_gpu, rel=1e-5):
         if left and took and min(took) < max(left) * (1 - rel):
             return False
     return True
+
+
+@dataclass
+class UnlockStep:
+    """One step of a run with optional unlocking, batched like BatchStep; *_in is the state before
+    the step, lock_mid the lock mask after the step's lock update (what the probe sees), *_out the
+    state after the probe and the unlock rule (equal to *_mid on steps without a probe)."""
+    base: BatchStep
+    t_lock_in: np.ndarray      # [B, N]
+    relocked_in: np.ndarray
+    cool_in: np.ndarray
+    lock_mid: np.ndarray
+    t_lock_mid: np.ndarray
+    probe: list                # per sequence ProbeRecord or None
+    lock_out: np.ndarray
+    relocked_out: np.ndarray
+    cool_out: np.ndarray
+
+
+def run_oracle_unlock(cfg, w64, prompts, n_gen, T, block_len, eps, prm, forced_M_end=None, seed=0):
+    """As run_oracle, with oracle.sampler.UnlockParams prm switched on."""
+    Bn = len(prompts)
+    n_p = len(prompts[0])
+    N = n_p + n_gen
+    sched = sampler.block_schedule(n_p, n_gen, block_len, T)
+    states = [sampler.init_state(cfg, w64, p, n_gen) for p in prompts]
+    hooks = [None] * Bn
+    mids = [None] * Bn
+    if forced_M_end is not None:
+        for b in range(Bn):
+            pri = np.random.default_rng(seed * 1000 + b).permutation(N)
+            target = wl.linear_m_schedule(N, forced_M_end[b], T)
+
+            def hook(st, rec, pri=pri, target=target):
+                nxt = target[st.t] if st.t < len(target) else target[-1]
+                return wl.forced_lock_positions(pri, st.lock, st.masked, int((st.lock == 0).sum()) - nxt)
+            hooks[b] = hook
+    out = []
+    for t in range(T):
+        lo, hi, k = sched[t]
+        pre = [(s.tokens.copy(), s.masked.copy(), s.lock.copy(), s.lock_step.copy(), s.relocked.copy(),
+                s.cool_until.copy()) for s in states]
+        recs = [sampler.surelock_step(cfg, w64, states[b], eps[b], lo, hi, k, forced_lock=hooks[b],
+                                      kl_drives_lock=forced_M_end is None, unlock=prm) for b in range(Bn)]
+        idx = np.concatenate([r.active_pos + b * N for b, r in enumerate(recs)])
+        cu = np.concatenate([[0], np.cumsum([len(r.active_pos) for r in recs])])
+        rule = np.stack([p[2].copy() for p in pre])
+        mid = np.stack([p[2].copy() for p in pre])
+        for b, r in enumerate(recs):
+            rule[b, r.F] = 1
+            mid[b, (r.F if forced_M_end is None else [])] = 1
+            mid[b, r.forced] = 1
+        base = BatchStep(
+            t=t + 1, tokens_in=np.stack([p[0] for p in pre]), masked_in=np.stack([p[1] for p in pre]),
+            lock_in=np.stack([p[2] for p in pre]), block=(lo, hi, k), active_idx=idx, cu_active=cu,
+            logits=np.concatenate([r.logits for r in recs]), kl=np.concatenate([r.kl for r in recs]),
+            conf=np.concatenate([r.conf for r in recs]), argmax=np.concatenate([r.argmax for r in recs]),
+            tokens_out=np.stack([s.tokens.copy() for s in states]),
+            masked_out=np.stack([s.masked.copy() for s in states]),
+            lock_rule_out=rule, lock_out=np.stack([s.lock.copy() for s in states]))
+        out.append(UnlockStep(
+            base=base, t_lock_in=np.stack([p[3] for p in pre]), relocked_in=np.stack([p[4] for p in pre]),
+            cool_in=np.stack([p[5] for p in pre]), lock_mid=mid,
+            t_lock_mid=np.stack([s.lock_step.copy() for s in states]), probe=[r.probe for r in recs],
+            lock_out=np.stack([s.lock.copy() for s in states]),
+            relocked_out=np.stack([s.relocked.copy() for s in states]),
+            cool_out=np.stack([s.cool_until.copy() for s in states])))
+    return out
