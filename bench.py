@@ -27,7 +27,7 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
 # WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
 # the copy-kernel calibration given there), keyed by M.
-LM_HEAD_TRAFFIC_BYTES = {1024: 1849523916, 16: 1044133785}
+LM_HEAD_TRAFFIC_BYTES = {1024: 1849332353, 16: 1044086008}
 
 
 def lm_head_clock_probe(B, torch, w_lm, M, V, d, seed, launches=12):
@@ -152,6 +152,27 @@ def main():
             "kernels_ms": {k: round(v, 4) for k, v in per.items()},
         })
 
+    # Optional unlocking (appendix): cost of one read-only probe + unlock rule over N/2 locked rows, to be
+    # amortised over the probe period P.  eps_unlock = +inf: nothing unlocks, the state stays as it is.
+    Mp = N // 2
+    active = wl.active_positions(args.seed + 100 + Mp, N, N - Mp)
+    lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
+    sess.unlock_state()
+    sess.t_lock.copy_(torch.as_tensor(rng.integers(1, 3, N), dtype=torch.int32, device=dev) * lock.to(torch.int32))
+    sess.step(tokens0.clone(), (1 - lock).clone(), lock, eps, t + 1, 0, N, 1, m_upper=N - Mp, new_lock=new_lock)
+    for _ in range(W):
+        sess.unlock_probe(tokens0, lock, t + 1, 20.0, float("inf"), 1, 2, m_upper_probe=Mp, m_upper_active=N - Mp)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(K):
+        sess.unlock_probe(tokens0, lock, t + 1, 20.0, float("inf"), 1, 2, m_upper_probe=Mp, m_upper_active=N - Mp)
+    e1.record()
+    torch.cuda.synchronize()
+    assert int(sess.cu_probe[-1].item()) == Mp and int(lock.sum().item()) == Mp
+    probe_ms = e0.elapsed_time(e1) / K
+    t += 1
+
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -166,7 +187,7 @@ def main():
     lm_ms = head["kernels_ms"]["lm_head"]
     if M0 >= 512:
         ach = M0 * lm_flops / (lm_ms * 1e-3) / 1e12
-        roof = {"kernel": "gemm_mfma256_kernel<1> (LM head, M=%d x V=%d x d=%d)" % (M0, V, d), "bound": "mfma",
+        roof = {"kernel": "gemm_mfma256_kernel<1, 256, false> (LM head, M=%d x V=%d x d=%d)" % (M0, V, d), "bound": "mfma",
                 "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                 "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
                 "launch_ms": round(lm_ms, 4), "algorithmic_flops_per_launch": M0 * lm_flops,
@@ -198,6 +219,8 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "sweep": results,
+        "unlock_probe": {"locked_rows": Mp, "ms": round(probe_ms, 4),
+                         "note": "read-only probe + unlock rule over the locked rows, once per P steps"},
     }
     print(json.dumps(out))
     sess.close()
