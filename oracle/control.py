@@ -108,3 +108,25 @@ def unlock_rule(lock_step, pos_probe, u_probe, D_probe, u_active, m, eps_unlock,
     out = [int(p) for r, p in enumerate(pos_probe)
            if u_probe[r] > theta and D_probe[r] > eps_unlock and t - int(lock_step[p]) > d_interval]
     return sorted(out)
+
+
+def select_rows(pos_active, masked, d_last, block_lo, block_hi, k_frac):
+    """Selection-based sparsification on top of the lock mask (Exp-5, the combined
+    setting: a fixed fraction k of the positions not yet locked is computed per step).
+
+    The paper's surrogate does not say which positions; the reading taken: of the n
+    active positions of a sequence, ceil(k * n) are computed.  The still-masked
+    positions of the current block always are (they must stay decodable; they may
+    exceed the budget); the rest of the budget goes to the other active positions in
+    decreasing order of the KL they scored when last computed (d_last, fp32, +inf
+    before any score), ties to the lower position.  Returns the sorted positions to
+    compute.
+    """
+    pos_active = [int(p) for p in pos_active]
+    n = len(pos_active)
+    budget = min(n, math.ceil(float(k_frac) * n))
+    must = [p for p in pos_active if masked[p] and block_lo <= p < block_hi]
+    must_set = set(must)
+    rest = sorted((p for p in pos_active if p not in must_set), key=lambda p: (-float(d_last[p]), p))
+    take = must + rest[:max(0, budget - len(must))]
+    return sorted(take)

@@ -26,6 +26,7 @@ class State:
     t: int = 0
     relocked: np.ndarray = None   # [N] uint8, 1 = was unlocked at least once (stricter re-lock)
     cool_until: np.ndarray = None # [N] int64, the slot cannot lock while t <= cool_until
+    d_last: np.ndarray = None     # [N] float32, the KL the slot scored when last computed (+inf before)
 
 
 @dataclass(frozen=True)
@@ -81,12 +82,12 @@ def init_state(cfg, weights, prompt_tokens, n_gen):
                  Vc=[np.full(shape, np.nan) for _ in range(cfg.n_layers)],
                  prev_lp=np.full((N, cfg.vocab), np.nan), x_hat=x_hat,
                  lock_step=np.zeros(N, dtype=np.int64), relocked=np.zeros(N, dtype=np.uint8),
-                 cool_until=np.zeros(N, dtype=np.int64))
+                 cool_until=np.zeros(N, dtype=np.int64), d_last=np.full(N, np.inf, dtype=np.float32))
 
 
 def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
                   gate_m=None, candidates_pre_update=False, forced_lock=None,
-                  kl_drives_lock=True, unlock=None):
+                  kl_drives_lock=True, unlock=None, select_k=None):
     """One iteration of the loop of Alg. 1, in the paper's order.
 
     eps < 0 can never be met by a KL (>= 0), which turns locking off.
@@ -96,11 +97,17 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
     unlock: UnlockParams or None.  When given, re-locking obeys the cool-down and
     the stricter threshold, and after every unlock.period-th step the read-only
     probe and the unlock rule of App. 'Optional Unlocking' run (unlock_probe).
+    select_k: None or the fraction k of Exp-5's combined setting: from step 2 on
+    only control.select_rows' choice among the non-locked positions is computed;
+    a skipped position keeps its K/V, its posterior and its lock state, and its
+    next KL is taken against the posterior of the step it was last computed at.
     """
     st.t += 1
     t = st.t
     # active / locked sets
     A = np.flatnonzero(st.lock == 0)
+    if select_k is not None and t > 1:
+        A = np.asarray(control.select_rows(A, st.masked, st.d_last, block_lo, block_hi, select_k), dtype=np.int64)
     tokens_in = st.tokens.copy()
     # restricted forward on the active rows; live K/V overwrite their cache rows
     z = model.forward_active(cfg, weights, st.tokens, A, st.Kc, st.Vc)
@@ -128,6 +135,7 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
                      unmasked=unmasked, F=F)
     # posteriors of the active rows become p_{t-1}; locked rows keep p_{t*}
     st.prev_lp[A] = lp
+    st.d_last[A] = np.maximum(D, 0.0).astype(np.float32)       # KL >= 0; rounding may leave -1e-17
     to_lock = list(F) if kl_drives_lock else []
     if forced_lock is not None:
         rec.forced = [int(p) for p in forced_lock(st, rec)]

@@ -193,3 +193,4 @@ def test_unlocking_run_invariants(tiny):
     tokens_changed = not np.array_equal(snaps[t_u - 1][2], snaps[max(t_u - 2, 0)][2])
     assert K_after.shape == K_before.shape and np.isfinite(K_after).all()
     assert tokens_changed or np.allclose(K_after, K_before)
+
