@@ -173,6 +173,22 @@ def main():
     probe_ms = e0.elapsed_time(e1) / K
     t += 1
 
+    # Selection hybrid (Exp-5, combined setting): the step that computes ceil(0.8 n) of the n = N non-locked
+    # rows, chosen on the device by their last KL; skipped rows have their posterior row carried over.
+    k_sel = 0.8
+    M_sel = int(np.ceil(float(np.float32(k_sel)) * N))
+    sel_masked = zero_mask.clone()
+    for i in range(W + K):
+        if i == W:
+            torch.cuda.synchronize()
+            e0.record()
+        t += 1
+        sess.step_selected(tokens0, sel_masked, zero_mask, eps, t, 0, N, 0, k_sel, m_upper=M_sel, new_lock=new_lock)
+    e1.record()
+    torch.cuda.synchronize()
+    assert int(sess.cu_active[-1].item()) == M_sel
+    sel_ms = e0.elapsed_time(e1) / K
+
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -219,6 +235,8 @@ def main():
         "roofline": roof,
         "cpu_baseline": cpu,
         "sweep": results,
+        "selected_step": {"k": k_sel, "non_locked_rows": N, "computed_rows": M_sel, "ms": round(sel_ms, 4),
+                          "note": "step with on-device selection of ceil(k n) rows + posterior carry of the skipped ones"},
         "unlock_probe": {"locked_rows": Mp, "ms": round(probe_ms, 4),
                          "note": "read-only probe + unlock rule over the locked rows, once per P steps"},
     }

@@ -160,6 +160,28 @@ int sl_surelock_step(sl_ctx *ctx, void *stream, int32_t *tokens, uint8_t *masked
                      int32_t *active_idx, int32_t *cu_active, float *kl, float *conf,
                      int32_t *argmax, uint8_t *new_lock, void *workspace, size_t workspace_bytes);
 
+/* The step combined with selection-based sparsification (Exp-5, the setting that selects a fixed
+ * fraction k of the positions not yet locked): from t = 2 on, per sequence only ceil(k n) of the n
+ * non-locked positions are computed: the still-masked positions inside [block_lo, block_hi)
+ * always, the rest of the budget in decreasing order of d_last, ties to the lower position (the
+ * paper's surrogate names no order; this one recomputes what moved most).  A skipped position
+ * keeps its K/V, its posterior, its d_last and its lock state; its next KL is taken against the
+ * posterior of the step it was last computed at.
+ *   select_fraction    host    k, 0 < k <= 1
+ *   d_last   [B*N] f32 in/out  the KL each position scored when last computed; the caller fills
+ *                              it with +inf before step 1 (every step overwrites the computed rows)
+ *   compute_mask [B*N] u8 out  0 = computed at this step, 1 = locked or skipped (must not alias
+ *                              lock / new_lock)
+ *   m_upper                    bounds the number of COMPUTED rows; n_seq <= 7680
+ * active_idx / cu_active / kl / conf / argmax describe the computed rows.  Everything else as
+ * sl_surelock_step.  Not meant to be mixed with the unlocking entry points in one run. */
+int sl_surelock_step_selected(sl_ctx *ctx, void *stream, int32_t *tokens, uint8_t *masked,
+                              const uint8_t *lock, const float *eps, int32_t t,
+                              int32_t block_lo, int32_t block_hi, int32_t k, float select_fraction,
+                              float *d_last, uint8_t *compute_mask, int32_t m_upper,
+                              int32_t *active_idx, int32_t *cu_active, float *kl, float *conf,
+                              int32_t *argmax, uint8_t *new_lock, void *workspace, size_t workspace_bytes);
+
 /* The restricted forward alone (Alg. 1, 'Compute on active positions'), layers
  * [layer_lo, layer_hi) on given block inputs: x_in [m_upper, d] (type T, packed in
  * active order) -> x_out [m_upper, d].  Writes the active rows' K/V into the cache.
@@ -209,6 +231,14 @@ int sl_lock_rule_gated(void *stream, const uint8_t *lock, const uint8_t *masked,
                        const int32_t *active_idx, const int32_t *cu_active, int32_t m_upper,
                        const float *kl, const float *conf, const float *eps, float gate_percentile,
                        int32_t batch, int32_t n_seq, int32_t first_step, uint8_t *new_lock);
+
+/* The selection of sl_surelock_step_selected alone: compute_mask[g] = 0 for the ceil(k n) non-locked
+ * positions of each sequence that are computed (still-masked ones inside [block_lo, block_hi)
+ * always, then by decreasing d_last, ties to the lower position), 1 for locked and skipped ones.
+ * 0 < select_fraction <= 1; n_seq <= 7680; compute_mask must not alias lock. */
+int sl_select_rows(void *stream, const uint8_t *lock, const uint8_t *masked, const float *d_last,
+                   int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi,
+                   float select_fraction, uint8_t *compute_mask);
 
 /* ---- optional unlocking (appendix 'Optional Unlocking') --------------------------------------
  * Per-position state, device arrays [B*N] owned by the caller and zero-initialised:

@@ -46,12 +46,15 @@ _SIGS = {
     "sl_logits_ptr": [_P, _I, C.POINTER(_P)],
     "sl_workspace_bytes": [_P, _I, _I, C.POINTER(_Z)],
     "sl_surelock_step": [_P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
+    "sl_surelock_step_selected": [_P, _P, _P, _P, _P, _P, _I, _I, _I, _I, C.c_float, _P, _P, _I, _P, _P, _P, _P, _P, _P,
+                                  _P, _Z],
     "sl_forward_layers": [_P, _P, _P, _P, _P, _P, _I, _I, _I, _P, _Z],
     "sl_compact_active": [_P, _P, _I, _I, _P, _P],
     "sl_score_posteriors": [_P, _P, _I, _P, _I, _I, _P, _P, _I, _I, _P, _P, _P],
     "sl_unmask_topk": [_P, _P, _P, _P, _P, _P, _P, _I, _I, _I, _I, _I],
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
     "sl_lock_rule_gated": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _I, _I, _I, _P],
+    "sl_select_rows": [_P, _P, _P, _P, _I, _I, _I, _I, C.c_float, _P],
     "sl_lock_rule_relock": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _P, _P, C.c_float, _I, _I, _I, _P, _P],
     "sl_unlock_probe": [_P, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
     "sl_unlock_rule": [_P, _P, _P, _P, _P, _P, _P, _P, _I, _P, _P, _P, _I, _P, C.c_float, C.c_float, _I, _I, _I, _P],
@@ -193,6 +196,14 @@ def sl_surelock_step(ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m
         workspace.numel()))
 
 
+def sl_surelock_step_selected(ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, select_fraction, d_last,
+                              compute_mask, m_upper, active_idx, cu_active, kl, conf, argmax, new_lock, workspace):
+    _check("sl_surelock_step_selected", lib().sl_surelock_step_selected(
+        ctx, _stream(), _ptr(tokens), _ptr(masked), _ptr(lock), _ptr(eps), t, block_lo, block_hi, k,
+        C.c_float(select_fraction), _ptr(d_last), _ptr(compute_mask), m_upper, _ptr(active_idx), _ptr(cu_active),
+        _ptr(kl), _ptr(conf), _ptr(argmax), _ptr(new_lock), _ptr(workspace), workspace.numel()))
+
+
 def sl_forward_layers(ctx, x_in, x_out, active_idx, m_dev, m_upper, layer_lo, layer_hi, workspace):
     _check("sl_forward_layers", lib().sl_forward_layers(
         ctx, _stream(), _ptr(x_in), _ptr(x_out), _ptr(active_idx), _ptr(m_dev), m_upper, layer_lo, layer_hi,
@@ -228,6 +239,11 @@ def sl_lock_rule_gated(lock, masked, active_idx, cu_active, m_upper, kl, conf, e
     _check("sl_lock_rule_gated", lib().sl_lock_rule_gated(
         _stream(), _ptr(lock), _ptr(masked), _ptr(active_idx), _ptr(cu_active), m_upper, _ptr(kl), _ptr(conf), _ptr(eps),
         C.c_float(gate_percentile), batch, n_seq, int(first_step), _ptr(new_lock)))
+
+
+def sl_select_rows(lock, masked, d_last, batch, n_seq, block_lo, block_hi, select_fraction, compute_mask):
+    _check("sl_select_rows", lib().sl_select_rows(_stream(), _ptr(lock), _ptr(masked), _ptr(d_last), batch, n_seq,
+                                                  block_lo, block_hi, C.c_float(select_fraction), _ptr(compute_mask)))
 
 
 def sl_lock_rule_relock(lock, masked, active_idx, cu_active, m_upper, kl, conf, eps, gate_percentile, relocked,
@@ -350,6 +366,21 @@ class Session:
         new_lock = lock if new_lock is None else new_lock
         sl_surelock_step(self.ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, self.active_idx,
                          self.cu_active, self.kl, self.conf, self.argmax, new_lock, self.workspace)
+        return new_lock
+
+    def step_selected(self, tokens, masked, lock, eps, t, block_lo, block_hi, k, select_fraction, m_upper=None,
+                      new_lock=None):
+        """The step on the fraction of the non-locked rows the selection keeps (d_last and compute_mask
+        are owned here; d_last starts at +inf)."""
+        if not hasattr(self, "d_last"):
+            R = self.B * self.N
+            self.d_last = torch.full((R,), float("inf"), dtype=torch.float32, device=self.device)
+            self.compute_mask = torch.zeros(R, dtype=torch.uint8, device=self.device)
+        m_upper = self.B * self.N if m_upper is None else m_upper
+        new_lock = lock if new_lock is None else new_lock
+        sl_surelock_step_selected(self.ctx, tokens, masked, lock, eps, t, block_lo, block_hi, k, select_fraction,
+                                  self.d_last, self.compute_mask, m_upper, self.active_idx, self.cu_active, self.kl,
+                                  self.conf, self.argmax, new_lock, self.workspace)
         return new_lock
 
     # -- optional unlocking: per-position state and probe outputs, allocated on first use --

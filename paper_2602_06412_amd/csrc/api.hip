@@ -381,6 +381,16 @@ extern "C" int sl_lock_rule_gated(void* stream, const uint8_t* lock, const uint8
                              gate_percentile, batch, n_seq, first_step, new_lock);
 }
 
+extern "C" int sl_select_rows(void* stream, const uint8_t* lock, const uint8_t* masked, const float* d_last,
+                             int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi, float select_fraction,
+                             uint8_t* compute_mask) {
+  if (!lock || !masked || !d_last || !compute_mask || batch < 1 || n_seq < 1) return SL_EINVAL;
+  if (block_lo < 0 || block_hi > n_seq || block_lo > block_hi) return SL_EINVAL;
+  if (!(select_fraction > 0.f) || select_fraction > 1.f || compute_mask == lock) return SL_EINVAL;
+  return slk_select_rows((hipStream_t)stream, lock, masked, d_last, batch, n_seq, block_lo, block_hi, select_fraction,
+                         compute_mask);
+}
+
 extern "C" int sl_lock_rule_relock(void* stream, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                                    const int32_t* cu_active, int32_t m_upper, const float* kl, const float* conf,
                                    const float* eps, float gate_percentile, const uint8_t* relocked,
@@ -444,10 +454,13 @@ extern "C" int sl_linear_clock_probe(void* stream, const void* x, int32_t x_tile
 }
 
 // ---- the step --------------------------------------------------------------------------------------
-extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
-                                const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,
-                                int32_t m_upper, int32_t* active_idx, int32_t* cu_active, float* kl, float* conf,
-                                int32_t* argmax, uint8_t* new_lock, void* workspace, size_t workspace_bytes) {
+// compute_mask / d_last: null for the plain step; otherwise the step computes only the rows the selection
+// keeps (Exp-5, combined setting) and maintains d_last and the posterior buffers for the skipped ones.
+static int step_impl(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
+                     const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,
+                     int32_t m_upper, int32_t* active_idx, int32_t* cu_active, float* kl, float* conf,
+                     int32_t* argmax, uint8_t* new_lock, void* workspace, size_t workspace_bytes,
+                     float select_fraction, float* d_last, uint8_t* compute_mask) {
   SL_TRY(check_ready(ctx, true));
   if (!tokens || !masked || !lock || !eps || !active_idx || !cu_active || !kl || !conf || !argmax || !new_lock ||
       !workspace)
@@ -462,8 +475,17 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   hipStream_t s = (hipStream_t)stream;
   const sl_config& c = ctx->cfg;
   const int32_t* m_dev = cu_active + B;
-  // A_t
-  SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, lock, B, N, active_idx, cu_active));
+  // A_t (with selection: the rows of A_t the selection keeps; from step 2 on, once scores exist)
+  const uint8_t* rows_mask = lock;
+  if (compute_mask != nullptr) {
+    SL_RUN(ctx, s, SL_PROF_COMPACT, slk_select_rows(s, lock, masked, d_last, B, N, block_lo, block_hi,
+                                                    t == 1 ? 1.0f : select_fraction, compute_mask));
+    const size_t ts = sl_tsize(c.dtype);
+    SL_RUN(ctx, s, SL_PROF_COMPACT, slk_posterior_carry_skipped(s, ctx->post, ctx->post_buf_elems * ts,
+                                                                (size_t)c.vocab * ts, lock, compute_mask, B * N, t));
+    rows_mask = compute_mask;
+  }
+  SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, rows_mask, B, N, active_idx, cu_active));
   // block input of the active rows + first LN
   SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model, c.vocab,
                            ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
@@ -479,9 +501,14 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
                             active_idx, c.vocab));
   // score -> UpdateMASK -> candidates -> lock
   SL_RUN(ctx, s, SL_PROF_SCORE, slk_score(s, cur, 0, prev, c.dtype, c.vocab, active_idx, m_dev, m_upper, t == 1, kl, conf, argmax, ws.score));
+  if (d_last != nullptr) SL_RUN(ctx, s, SL_PROF_SCORE, slk_scatter_rows_f32(s, active_idx, m_dev, m_upper, kl, d_last));
   // (with candidates_pre_update the lock rule simply runs first: it then sees `masked` as it
   // was before UpdateMASK, and neither kernel reads what the other writes)
   auto lock_rule = [&]() -> int {
+    // the rule kernels write the locked positions and the computed rows; skipped rows (selection) are
+    // neither, so a separate output starts as a copy of the input mask
+    if (compute_mask != nullptr && new_lock != lock)
+      SL_HIP(hipMemcpyAsync(new_lock, lock, (size_t)B * N, hipMemcpyDeviceToDevice, s));
     if (c.gate_percentile > 0.f)
       return slk_lock_rule_gated(s, lock, masked, active_idx, cu_active, m_upper, kl, conf, eps, c.gate_percentile, B, N,
                                  t == 1, new_lock);
@@ -491,6 +518,27 @@ extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
   if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;
+}
+
+extern "C" int sl_surelock_step(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked, const uint8_t* lock,
+                                const float* eps, int32_t t, int32_t block_lo, int32_t block_hi, int32_t k,
+                                int32_t m_upper, int32_t* active_idx, int32_t* cu_active, float* kl, float* conf,
+                                int32_t* argmax, uint8_t* new_lock, void* workspace, size_t workspace_bytes) {
+  return step_impl(ctx, stream, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, active_idx, cu_active, kl,
+                   conf, argmax, new_lock, workspace, workspace_bytes, 1.0f, nullptr, nullptr);
+}
+
+extern "C" int sl_surelock_step_selected(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked,
+                                         const uint8_t* lock, const float* eps, int32_t t, int32_t block_lo,
+                                         int32_t block_hi, int32_t k, float select_fraction, float* d_last,
+                                         uint8_t* compute_mask, int32_t m_upper, int32_t* active_idx,
+                                         int32_t* cu_active, float* kl, float* conf, int32_t* argmax,
+                                         uint8_t* new_lock, void* workspace, size_t workspace_bytes) {
+  if (!d_last || !compute_mask || !(select_fraction > 0.f) || select_fraction > 1.f) return SL_EINVAL;
+  if (compute_mask == lock || compute_mask == new_lock) return SL_EINVAL;
+  if (ctx && ctx->kv && (size_t)ctx->n_seq * 8 > 60 * 1024) return SL_EINVAL;
+  return step_impl(ctx, stream, tokens, masked, lock, eps, t, block_lo, block_hi, k, m_upper, active_idx, cu_active, kl,
+                   conf, argmax, new_lock, workspace, workspace_bytes, select_fraction, d_last, compute_mask);
 }
 
 // ---- optional unlocking ------------------------------------------------------------------------------

@@ -423,3 +423,143 @@ int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
+
+// ---- selection on top of the lock mask (Exp-5, combined setting): which non-locked rows to compute ----
+// One workgroup per sequence.  Of the n non-locked positions, ceil(k n) are computed: the still-masked
+// positions of the current block always, the rest of the budget by decreasing d_last (the KL a position
+// scored when last computed; non-negative floats order like their bit patterns), ties to the lower
+// position.  Keys (d_last bits << 32) | ~position are distinct; the (budget - #must)-th largest is found by
+// an 8-pass radix select in LDS.  compute_mask[g] = 0 for the rows to compute, 1 for locked and skipped ones.
+struct Select64Shared {
+  int hist[256];
+  int wave_tot[4];
+  int want, done;
+  unsigned long long prefix;
+};
+
+// the k-th largest of n distinct keys (1 <= k <= n), or a lower bound of it that no smaller key reaches
+__device__ static unsigned long long select_kth_largest(const unsigned long long* keys, int n, int k,
+                                                        Select64Shared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __syncthreads();
+  if (tid == 0) { sh.prefix = 0; sh.want = k; sh.done = 0; }
+  for (int shift = 56; shift >= 0; shift -= 8) {
+    sh.hist[tid] = 0;
+    __syncthreads();
+    const unsigned long long prefix = sh.prefix;
+    const int want = sh.want;
+    const unsigned long long himask = shift == 56 ? 0ull : (~0ull << (shift + 8));
+    for (int e = tid; e < n; e += 256) {
+      const unsigned long long key = keys[e];
+      if ((key & himask) == prefix) atomicAdd(&sh.hist[(int)((key >> shift) & 0xff)], 1);
+    }
+    __syncthreads();
+    const int c = sh.hist[tid];
+    int incl = c;                                // keys in bins tid .. 64*wave+63
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_down(incl, o, 64);
+      if (lane + o < 64) incl += y;
+    }
+    if (lane == 0) sh.wave_tot[wave] = incl;
+    __syncthreads();
+    for (int w = wave + 1; w < 4; ++w) incl += sh.wave_tot[w];      // keys in bins >= tid
+    const int above = incl - c;                  // keys in bins > tid
+    if (above < want && want <= incl) {
+      sh.prefix = prefix | ((unsigned long long)tid << shift);
+      sh.want = want - above;
+      if (want - above == c) sh.done = 1;          // the whole bin is wanted: its lowest possible key will do
+    }
+    __syncthreads();
+    if (sh.done) break;
+  }
+  return sh.prefix;
+}
+
+__global__ __launch_bounds__(256) void select_rows_kernel(const uint8_t* __restrict__ lock,
+                                                          const uint8_t* __restrict__ masked,
+                                                          const float* __restrict__ d_last, int N, int lo, int hi,
+                                                          double k_frac, uint8_t* __restrict__ compute_mask) {
+  extern __shared__ unsigned long long skeys[];    // [N]
+  __shared__ int n_active, n_must, count;
+  __shared__ Select64Shared sel;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  if (tid == 0) { n_active = 0; n_must = 0; count = 0; }
+  __syncthreads();
+  for (int p = tid; p < N; p += 256) {
+    const size_t g = (size_t)b * N + p;
+    if (lock[g]) { compute_mask[g] = 1; continue; }
+    atomicAdd(&n_active, 1);
+    if (masked[g] && p >= lo && p < hi) {
+      compute_mask[g] = 0;
+      atomicAdd(&n_must, 1);
+    } else {
+      const int slot = atomicAdd(&count, 1);
+      skeys[slot] = ((unsigned long long)__float_as_uint(d_last[g]) << 32) | (unsigned)(~(unsigned)p);
+    }
+  }
+  __syncthreads();
+  const int n = n_active, cnt = count;
+  int budget = (int)ceil(k_frac * (double)n);
+  budget = budget > n ? n : budget;
+  const int want = budget - n_must;
+  unsigned long long thresh = 0;                   // want >= cnt: every other row is computed too
+  bool none = want <= 0;
+  if (!none && want < cnt) thresh = select_kth_largest(skeys, cnt, want, sel);
+  for (int e = tid; e < cnt; e += 256) {
+    const unsigned long long key = skeys[e];
+    const unsigned p = ~(unsigned)(key & 0xffffffffu);
+    compute_mask[(size_t)b * N + p] = (!none && key >= thresh) ? 0 : 1;
+  }
+}
+
+int slk_select_rows(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const float* d_last, int B, int N,
+                    int lo, int hi, float k_frac, uint8_t* compute_mask) {
+  if ((size_t)N * 8 > 60 * 1024) return SL_EINVAL;
+  hipLaunchKernelGGL(select_rows_kernel, dim3(B), dim3(256), (size_t)N * 8, s, lock, masked, d_last, N, lo, hi,
+                     (double)k_frac, compute_mask);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// A skipped position (not locked, not computed at step t) has its newest posterior row copied from the
+// buffer step t - 1 wrote to the one step t writes, so that the next step that computes it finds the
+// posterior of the step it was last computed at where every step looks for p_{t-1}.  16-byte units.
+__global__ __launch_bounds__(256) void posterior_carry_skipped_kernel(uint4* __restrict__ store, size_t buf_units,
+                                                                      size_t row_units,
+                                                                      const uint8_t* __restrict__ lock,
+                                                                      const uint8_t* __restrict__ compute_mask,
+                                                                      int total, int t) {
+  const int g = blockIdx.x;
+  if (g >= total || lock[g] || !compute_mask[g]) return;
+  const uint4* src = store + (size_t)((t - 1) & 1) * buf_units + (size_t)g * row_units;
+  uint4* dst = store + (size_t)(t & 1) * buf_units + (size_t)g * row_units;
+  for (size_t e = (size_t)blockIdx.y * 256 + threadIdx.x; e < row_units; e += (size_t)gridDim.y * 256) dst[e] = src[e];
+}
+
+int slk_posterior_carry_skipped(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const uint8_t* lock,
+                                const uint8_t* compute_mask, int total, int t) {
+  if (total <= 0 || t < 2) return SL_OK;
+  if (row_bytes % 16 || buf_bytes % 16 || (uintptr_t)store % 16) return SL_EINVAL;
+  const int chunks = (int)((row_bytes / 16 + 2047) / 2048);
+  hipLaunchKernelGGL(posterior_carry_skipped_kernel, dim3(total, chunks > 0 ? chunks : 1), dim3(256), 0, s,
+                     (uint4*)store, buf_bytes / 16, row_bytes / 16, lock, compute_mask, total, t);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// d_last[active_idx[r]] = kl[r] for the computed rows
+__global__ void scatter_rows_f32_kernel(const int32_t* __restrict__ active_idx, const int32_t* __restrict__ m_dev,
+                                        int m_upper, const float* __restrict__ src, float* __restrict__ dst) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < min(*m_dev, m_upper)) dst[active_idx[r]] = src[r];
+}
+
+int slk_scatter_rows_f32(hipStream_t s, const int32_t* active_idx, const int32_t* m_dev, int m_upper, const float* src,
+                         float* dst) {
+  if (m_upper <= 0) return SL_OK;
+  hipLaunchKernelGGL(scatter_rows_f32_kernel, dim3(sl_cdiv(m_upper, 256)), dim3(256), 0, s, active_idx, m_dev, m_upper,
+                     src, dst);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}

@@ -174,6 +174,12 @@ int slk_unlock_rule(hipStream_t s, uint8_t* lock, uint8_t* relocked, int32_t* co
                     const int32_t* probe_idx, const int32_t* cu_probe, int mp_upper, const float* kl_probe,
                     const float* conf_probe, const int32_t* cu_active, int ma_upper, const float* conf_active, float m,
                     float eps_unlock, int t, int d_interval, int d_cool, int B, int N, uint8_t* unlocked);
+int slk_select_rows(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const float* d_last, int B, int N,
+                    int lo, int hi, float k_frac, uint8_t* compute_mask);
+int slk_posterior_carry_skipped(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const uint8_t* lock,
+                                const uint8_t* compute_mask, int total, int t);
+int slk_scatter_rows_f32(hipStream_t s, const int32_t* active_idx, const int32_t* m_dev, int m_upper, const float* src,
+                         float* dst);
 int slk_probe_prev_rows(hipStream_t s, const int32_t* probe_idx, const int32_t* m_dev, int m_upper,
                         const int32_t* t_lock, int buf_rows, int32_t* prev_rows);
 int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const int32_t* probe_idx,

@@ -1,0 +1,147 @@
+"""GPU parity of the step combined with selection-based sparsification (Exp-5, the combined
+setting) against the oracle.
+
+Kernel level (bit-exact): sl_select_rows against oracle.control.select_rows on synthetic masks
+and scores (ties, +inf scores, must rows beyond the budget, k = 1, empty active sets, the largest
+n_seq the kernel takes).
+Run level, teacher-forced: every step receives the oracle's state (tokens, masked, lock, d_last);
+the set of computed rows must equal the oracle's exactly; logits within the logit tolerance; KL in
+situ against the device's own logits of the step each row was last computed at (this is what the
+posterior carry of skipped rows is for); lock rule in situ; d_last, compute_mask and the lock output
+of skipped rows checked exactly."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import control, posterior
+from paper_2602_06412_amd import binding as B
+from paper_2602_06412_amd import workloads as wl
+from tests.gpu_util import DEV, check_logits, dev, oracle_cfg, weights_to_device
+from tests.trajectory import run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("Bn,N,lo,hi,k,ties,p_lock", [
+    (1, 128, 32, 128, 0.8, False, 0.3), (3, 333, 100, 164, 0.5, True, 0.5), (8, 1024, 512, 544, 0.8, True, 0.2),
+    (2, 64, 0, 64, 0.1, False, 0.1), (2, 200, 50, 60, 1.0, True, 0.4), (2, 96, 10, 20, 0.8, False, 1.0),
+    (1, 7680, 4096, 4160, 0.8, False, 0.5), (4, 777, 0, 0, 0.33, True, 0.6)])
+def test_select_rows(Bn, N, lo, hi, k, ties, p_lock):
+    rng = np.random.default_rng(N * 7 + int(k * 100))
+    lock = (rng.random((Bn, N)) < p_lock).astype(np.uint8)
+    masked = ((rng.random((Bn, N)) < 0.5) & (lock == 0)).astype(np.uint8)
+    d = rng.random((Bn, N)).astype(np.float32)
+    if ties:
+        d = (np.floor(d * 6) / 6).astype(np.float32)
+    d[rng.random((Bn, N)) < 0.15] = np.inf
+    k32 = np.float32(k)
+    want = np.ones((Bn, N), dtype=np.uint8)
+    for b in range(Bn):
+        A = np.flatnonzero(lock[b] == 0)
+        want[b, control.select_rows(A, masked[b], d[b], lo, hi, float(k32))] = 0
+    out = torch.full((Bn * N,), 7, dtype=torch.uint8, device=DEV)
+    B.sl_select_rows(dev(lock.reshape(-1)), dev(masked.reshape(-1)), dev(d.reshape(-1)), Bn, N, lo, hi, float(k32), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().reshape(Bn, N), want)
+    if 0 < p_lock < 1 and k < 1:
+        assert ((want == 1) & (lock == 0)).sum() > 0, "the case should skip some rows"
+
+
+def test_select_argument_errors():
+    z8 = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    o8 = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    zf = torch.zeros(64, device=DEV)
+    for frac in (0.0, -0.5, 1.5):
+        with pytest.raises(B.SureLockError):
+            B.sl_select_rows(z8, z8, zf, 1, 64, 0, 64, frac, o8)
+    with pytest.raises(B.SureLockError):
+        B.sl_select_rows(z8, z8, zf, 1, 64, 0, 65, 0.8, o8)                   # block beyond the sequence
+    with pytest.raises(B.SureLockError):
+        B.sl_select_rows(z8, z8, zf, 1, 64, 0, 64, 0.8, z8)                   # output aliases lock
+    with pytest.raises(B.SureLockError):
+        B.sl_select_rows(z8, z8, zf, 1, 8000, 0, 64, 0.8, o8)                 # n_seq beyond the LDS budget
+
+
+def _check_selected_run(shape, w, steps, Bn, N, eps, k_frac):
+    V = shape.vocab
+    sess = B.Session(shape, weights_to_device(w), Bn, N)
+    n_skipped = 0
+    try:
+        eps_d = dev(np.asarray(eps, dtype=np.float32))
+        last_logits = np.zeros((Bn * N, V))                  # the device's own logits of each row's last computed step
+        for st in steps:
+            lo, hi, k = st.block
+            tokens = dev(st.tokens_in.reshape(-1), torch.int32)
+            masked = dev(st.masked_in.reshape(-1).astype(np.uint8))
+            lock = dev(st.lock_in.reshape(-1).astype(np.uint8))
+            new_lock = torch.full_like(lock, 9)
+            if st.t == 1:
+                sess.step_selected(tokens, masked, lock, eps_d, 1, lo, hi, k, k_frac, new_lock=new_lock)   # allocates d_last
+            else:
+                sess.d_last.copy_(dev(st.d_last_in.reshape(-1)))
+                sess.step_selected(tokens, masked, lock, eps_d, st.t, lo, hi, k, k_frac, new_lock=new_lock)
+            torch.cuda.synchronize()
+            M = int(sess.cu_active[-1].item())
+            idx = sess.active_idx[:M].cpu().numpy()
+            assert np.array_equal(idx, st.active_idx), f"t={st.t}: the computed set must equal the oracle's"
+            assert np.array_equal(sess.cu_active.cpu().numpy(), st.cu_active)
+            cm = sess.compute_mask.cpu().numpy()
+            want_cm = np.ones(Bn * N, dtype=np.uint8); want_cm[st.active_idx] = 0
+            assert np.array_equal(cm, want_cm)
+            skipped = np.flatnonzero((st.lock_in.reshape(-1) == 0) & (want_cm == 1))
+            n_skipped += len(skipped)
+            z_gpu = sess.logits_view(st.t)[torch.as_tensor(idx, device=DEV, dtype=torch.long)].double().cpu().numpy()
+            check_logits(z_gpu, st.logits, shape.storage, f"t={st.t}")
+            kl, conf, am = sess.kl[:M].cpu().numpy(), sess.conf[:M].cpu().numpy(), sess.argmax[:M].cpu().numpy()
+            if st.t == 1:
+                assert np.all(np.isinf(kl))
+            else:
+                want = posterior.kl_rows(posterior.log_softmax(z_gpu), posterior.log_softmax(last_logits[idx]))
+                assert np.all(np.abs(kl - want) <= 1e-4 * want + 2e-7), f"t={st.t}"
+            last_logits[idx] = z_gpu
+            # the score memory: computed rows take their KL, the others keep theirs
+            d_now = sess.d_last.cpu().numpy()
+            d_want = st.d_last_in.reshape(-1).copy() if st.t > 1 else np.full(Bn * N, np.inf, dtype=np.float32)
+            d_want[idx] = kl
+            assert np.array_equal(d_now, d_want)
+            # lock rule in situ; skipped and locked rows carry their state over into the separate output
+            want_msk, want_tok, want_lock = st.masked_in.copy().astype(np.uint8), st.tokens_in.copy(), st.lock_in.copy()
+            for b in range(Bn):
+                r0, r1 = st.cu_active[b], st.cu_active[b + 1]
+                pos = st.active_idx[r0:r1] - b * N
+                control.update_mask(want_msk[b], want_tok[b], pos, conf[r0:r1], am[r0:r1], lo, hi, k)
+                F = control.lock_rule(st.lock_in[b], want_msk[b], pos, kl[r0:r1], np.zeros(r1 - r0, np.float32),
+                                      np.float32(eps[b]), st.t == 1)
+                want_lock[b, F] = 1
+            assert np.array_equal(new_lock.cpu().numpy().reshape(Bn, N), want_lock), f"t={st.t}"
+            assert np.array_equal(masked.cpu().numpy().reshape(Bn, N), want_msk)
+            assert np.array_equal(tokens.cpu().numpy().reshape(Bn, N), want_tok)
+    finally:
+        sess.close()
+    return n_skipped
+
+
+def test_c1_fp32_run_with_selection():
+    shape = wl.C1
+    w = wl.make_weights(shape, seed=1, std=0.2, norm_gain_jitter=0.05)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    eps = [1e-3]
+    prompts = [wl.prompt_uniform(7, 32, shape.vocab, shape.mask_id)]
+    steps = run_oracle(cfg, w64, prompts, 96, 32, 96, eps, select_k=float(np.float32(0.8)))   # the C ABI carries k as fp32
+    plain = run_oracle(cfg, w64, prompts, 96, 32, 96, eps)
+    assert sum(len(s.active_idx) for s in steps) < sum(len(s.active_idx) for s in plain)
+    assert steps[-1].masked_out.sum() == 0
+    assert _check_selected_run(shape, w, steps, 1, 128, eps, 0.8) > 100
+
+
+@pytest.mark.parametrize("Bn,n_p,n_gen,T,block,M_end,k_frac", [(1, 72, 128, 16, 64, [24], 0.8),
+                                                               (3, 40, 96, 12, 96, [16, 50, 100], 0.5)])
+def test_bf16_run_with_selection_forced_schedule(Bn, n_p, n_gen, T, block, M_end, k_frac):
+    shape = wl.S_BF16
+    w = wl.make_weights(shape, seed=3, norm_gain_jitter=0.05)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    prompts = [wl.prompt_zipf(20 + b, n_p, shape.vocab, shape.mask_id) for b in range(Bn)]
+    eps = [[1e-4, 1e-3, 1e-2][b % 3] for b in range(Bn)]
+    steps = run_oracle(cfg, w64, prompts, n_gen, T, block, eps, forced_M_end=M_end, seed=4,
+                       select_k=float(np.float32(k_frac)))
+    assert _check_selected_run(shape, w, steps, Bn, n_p + n_gen, eps, k_frac) > 50

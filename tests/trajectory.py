@@ -28,10 +28,11 @@ class BatchStep:
     masked_out: np.ndarray
     lock_rule_out: np.ndarray  # lock_in | F_t  (what the KL rule alone gives)
     lock_out: np.ndarray       # lock mask carried to the next step (rule and/or forced)
+    d_last_in: np.ndarray = None   # [B, N] fp32, only for runs with selection
 
 
 def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, seed=0, keep_states=False,
-               candidates_pre_update=False, gate_m=None):
+               candidates_pre_update=False, gate_m=None, select_k=None):
     """prompts: list of B int arrays (same length); eps: list of B thresholds.
     forced_M_end: None -> the KL rule drives the mask; else a list of per-sequence final
     active counts: a seeded priority force-locks eligible rows so M falls linearly, and the
@@ -55,9 +56,11 @@ def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, s
     for t in range(T):
         lo, hi, k = sched[t]
         pre = [(s.tokens.copy(), s.masked.copy(), s.lock.copy()) for s in states]
+        d_last_in = np.stack([s.d_last.copy() for s in states])
         recs = [sampler.surelock_step(cfg, w64, states[b], eps[b], lo, hi, k, forced_lock=hooks[b],
                                       kl_drives_lock=forced_M_end is None,
-                                      candidates_pre_update=candidates_pre_update, gate_m=gate_m) for b in range(Bn)]
+                                      candidates_pre_update=candidates_pre_update, gate_m=gate_m,
+                                      select_k=select_k) for b in range(Bn)]
         idx = np.concatenate([r.active_pos + b * N for b, r in enumerate(recs)])
         cu = np.concatenate([[0], np.cumsum([len(r.active_pos) for r in recs])])
         rule = np.stack([p[2].copy() for p in pre])
@@ -70,7 +73,7 @@ def run_oracle(cfg, w64, prompts, n_gen, T, block_len, eps, forced_M_end=None, s
             conf=np.concatenate([r.conf for r in recs]), argmax=np.concatenate([r.argmax for r in recs]),
             tokens_out=np.stack([s.tokens.copy() for s in states]),
             masked_out=np.stack([s.masked.copy() for s in states]),
-            lock_rule_out=rule, lock_out=np.stack([s.lock.copy() for s in states])))
+            lock_rule_out=rule, lock_out=np.stack([s.lock.copy() for s in states]), d_last_in=d_last_in))
     return (steps, states) if keep_states else steps
 
 
