@@ -343,7 +343,7 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
 #ifndef SL_THIN_MAX
-#define SL_THIN_MAX 64
+#define SL_THIN_MAX 32
 #endif
 constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many rows take the thin (weight-stream) kernels
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
@@ -352,11 +352,13 @@ static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 //  * thin launches (mu <= kThinMax) are weight-stream bound: one BM x 256 tile per 256 columns, k
 //    split until there are about two workgroups per CU, with the fp32 partial traffic capped
 //    at a fraction of the weight bytes (k >= 32*S*mu);
-//  * thick launches pick, by a small cost model calibrated on measured launches, between the
-//    256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep k-tile and wave of
-//    workgroups) and the 128 x 256 kernel (two per CU, ~1.8 us per 64-deep k-tile and wave),
-//    each with the split count that minimises  waves * (k-tiles per split + fixed) * t_tile
-//    + bytes of fp32 partials written and read back / 5 TB/s.
+//  * thicker launches take the 256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep
+//    k-tile and wave of workgroups; its half-height variant is chosen inside that launcher) with the
+//    split count that minimises  waves * (k-tiles per split + fixed) * t_tile + bytes of fp32
+//    partials written and read back / 5 TB/s; reductions too short for its ring (fewer than 8
+//    k-tiles per split) go to the 128 x 256 LDS kernel (two per CU, ~1.8 us per 64-deep k-tile).
+//  The thin limit is 32 rows: from 33 rows on the ring's half-height tile is ahead of the two-block
+//  weight-stream kernel (whole step at 64 rows 0.39 -> 0.36 ms, at 33 rows 0.365 -> 0.337 ms).
 struct GemmPlan {
   int thick256;   // 1: gemm_mfma256_kernel
   int splits;
@@ -375,21 +377,28 @@ static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
     p.splits = s;
     return p;
   }
+  // The ring kernel wherever its k loop is long enough (at least 8 k-tiles per split); its half-height
+  // variant covers ragged and small row counts.  Measured over ragged row counts at the LLaDA-8B shapes
+  // the 128 x 256 LDS kernel never won where the ring was eligible (LM head at 820 rows: 1.19 ms
+  // against 0.79 ms), so it is kept for short reductions only.
   double best = 1e30;
   const int t256 = sl_cdiv(mu, 256) * sl_cdiv(n, 256), t128 = sl_cdiv(mu, 128) * sl_cdiv(n, 256);
   for (int s = 1; s <= 8; s *= 2) {
     if (k % (2 * BK * s)) break;
+    if (k / (32 * s) < 8) break;
     const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
-    if (k / (32 * s) >= 8) {
-      const double fused_us = (double)mu * n / 5.0e6;      // bf16 activations of half the width, written once
-      const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 +
-                       (swiglu_consumer && s == 1 ? fused_us : traffic_us);
-      if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
-    }
-    if (k / (BK * s) >= 4) {
-      const double t = sl_cdiv(t128 * s, 512) * (k / (64.0 * s) + 3.0) * 1.8 + traffic_us;
-      if (t < best) { best = t; p.thick256 = 0; p.splits = s; }
-    }
+    const double fused_us = (double)mu * n / 5.0e6;      // bf16 activations of half the width, written once
+    const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 +
+                     (swiglu_consumer && s == 1 ? fused_us : traffic_us);
+    if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
+  }
+  if (p.thick256) return p;
+  for (int s = 1; s <= 8; s *= 2) {
+    if (k % (2 * BK * s)) break;
+    if (k / (BK * s) < 4) break;
+    const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
+    const double t = sl_cdiv(t128 * s, 512) * (k / (64.0 * s) + 3.0) * 1.8 + traffic_us;
+    if (t < best) { best = t; p.thick256 = 0; p.splits = s; }
   }
   return p;
 }
@@ -435,8 +444,8 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
     const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
     if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
   }
-  // at most 64 rows: the barrier-free weight stream with one or two 32-row blocks (with streaming
-  // weight loads it is ahead of both LDS kernels there: 0.42 -> 0.39 ms on the step at 64 rows)
+  // the barrier-free weight stream with one 32-row block (at most 32 rows) or two (33..64 rows, reached
+  // only where the reduction is too short for the ring kernel)
   if (mu <= 32 && (k / splits) % 128 == 0)
     return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
               : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);

@@ -53,21 +53,16 @@ template <int TM> struct TileCfg {
 // PROBE: one workgroup in the middle of the grid also records shader-clock cycles and 100 MHz
 // wall ticks of its prologue, k loop and epilogue into probe[0..7] (a measurement aid: the
 // clock under this kernel is set by the chip's power management, not by the nominal 2.4 GHz).
-template <int OUT, int TM, bool PROBE = false>
-__global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
+// One TM x 256 output tile (rows m0 .., column tile tn) by the whole 512-thread workgroup.
+template <int OUT, int TM, bool PROBE>
+__device__ __forceinline__ void ring_tile(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
-    const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe = nullptr) {
+    const int M, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
+    const int32_t* __restrict__ row_map, size_t ldc, const int m0, const int tn, long long* __restrict__ probe) {
   typedef TileCfg<TM> TC;
   constexpr int STAGE = TC::STAGE, NA = TC::NA, HA = TC::HA, NS = TC::NS;
   extern __shared__ Frag lds[];           // [NS stages][A: TM/32 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
 
-  const int M = min(*m_dev, m_upper);
-  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
-  if (tn >= tiles_n) return;
-  const int m0 = tm * TM;
-  if (m0 >= M) return;
   const int n0 = tn * TILE;
   const int kbeg = blockIdx.y * k_per_split;
   const int ktiles = k_per_split / BK2;
@@ -87,13 +82,14 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   const int a_kb = TM == 256 ? 0 : wave & 1;          // ... and its k half (TM = 128: one fragment only)
   if (a_tiled) {
     int mbg = m0 / 32 + a_mb;
-    const int mb_last = (m_upper + 31) / 32 - 1;
-    mbg = mbg < mb_last ? mbg : mb_last;              // row tail: stay inside the buffer
+    // row tail: stay inside the buffer (blocks past the end read valid blocks; their products are never stored)
+    const int n_mb = (m_upper + 31) / 32;
+    mbg = mbg < n_mb ? mbg : mbg % n_mb;
     a_off = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u +
             (uint32_t)(a_kb * a_kb_stride);
   } else {
     int row = m0 + a_mb * 32 + (lane & 31);
-    row = row < m_upper ? row : m_upper - 1;          // row tail: stay inside the buffer
+    row = row < m_upper ? row : row % m_upper;        // row tail: stay inside the buffer
     a_off = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8) + (uint32_t)(a_kb * a_kb_stride);
   }
   const Frag* Wf = reinterpret_cast<const Frag*>(Wp) + (size_t)(kbeg / 16) * 64;
@@ -328,6 +324,37 @@ __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
   }
 }
 
+// Workgroup -> tile: blockIdx.x = 8 * j + xcd; the row tiles of one column tile are consecutive j on
+// one XCD (they share the weight slab in that XCD's L2).
+template <int OUT, int TM, bool PROBE = false>
+__global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
+    const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
+    const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe = nullptr) {
+  const int M = min(*m_dev, m_upper);
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
+  if (tn >= tiles_n || tm * TM >= M) return;
+  ring_tile<OUT, TM, PROBE>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TM, tn, probe);
+}
+
+// Full-height row tiles followed by ONE half-height tile for a row tail of at most 128 rows
+// (tiles_m counts both kinds): the tail then costs 0.565 of a full tile instead of a whole one.
+template <int OUT>
+__global__ __launch_bounds__(512, 2) void gemm_mfma256_tail_kernel(
+    const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
+    const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
+  const int M = min(*m_dev, m_upper);
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
+  if (tn >= tiles_n || tm * TILE >= M) return;
+  if (tm == tiles_m - 1)
+    ring_tile<OUT, 128, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr);
+  else
+    ring_tile<OUT, 256, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr);
+}
+
 template <int OUT, int TM>
 static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                        int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
@@ -355,21 +382,51 @@ static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp
 static double ring_rounds_cost(int workgroups) {
   return workgroups / 256 + (workgroups % 256 ? 0.9 : 0.0);
 }
-static bool ring_use_half(int mu, int n, int splits) {
-  if (SL_TM_FORCE == 128) return true;
-  if (SL_TM_FORCE == 256) return false;
-  const int tn = sl_cdiv(n, TILE);
-  const double full = ring_rounds_cost(sl_cdiv(mu, 256) * tn * splits);
-  const double half = 0.565 * ring_rounds_cost(sl_cdiv(mu, 128) * tn * splits);
-  return half < 0.95 * full;
+#ifndef SL_TAIL_TILE
+#define SL_TAIL_TILE 1
+#endif
+template <int OUT>
+static int launch_ring_tail(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
+                            int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+  const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
+  const size_t sh = (size_t)TileCfg<256>::NS * TileCfg<256>::STAGE * 16;       // the larger of the two rings
+  auto kern = gemm_mfma256_tail_kernel<OUT>;
+  static unsigned long long lds_ok = 0;
+  SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
+  dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
+  hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
+                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
+}
+
+// 0: full-height tiles, 1: half-height tiles, 2: full-height tiles + one half-height tail tile
+static int ring_tile_mode(int mu, int n, int splits) {
+  if (SL_TM_FORCE == 128) return 1;
+  if (SL_TM_FORCE == 256) return 0;
+  const int tn = sl_cdiv(n, TILE) * splits;
+  const int t_full = sl_cdiv(mu, 256);
+  const double full = ring_rounds_cost(t_full * tn);
+  const double half = 0.565 * ring_rounds_cost(sl_cdiv(mu, 128) * tn);
+  int mode = half < 0.95 * full ? 1 : 0;
+  const double best = mode ? half : full;
+  const int tail = mu - (t_full - 1) * 256;          // rows of the last full-height tile
+  if (SL_TAIL_TILE && t_full > 1 && tail <= 128) {
+    // work in units of full tiles, spread over 256 CUs like any other launch
+    const double mixed = ring_rounds_cost((int)ceil(((t_full - 1) + 0.565) * tn));
+    if (mixed < 0.95 * best) mode = 2;
+  }
+  return mode;
 }
 
 template <int OUT>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                      int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
-  return ring_use_half(mu, n, splits)
-             ? launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc)
-             : launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+  switch (ring_tile_mode(mu, n, splits)) {
+    case 1: return launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+    case 2: return launch_ring_tail<OUT>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+    default: return launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+  }
 }
 
 int slk_gemm_mfma256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,

@@ -31,7 +31,8 @@ def test_c2_full_size_sampled_rows():
         rng = np.random.default_rng(0)
         prev_rows = {}
         active = np.arange(N)
-        for t, M in ((1, 1024), (2, 256), (3, 16)):
+        # 820 and 300 rows: a ragged last row tile (full-height tiles + one half-height tail tile in the LM head)
+        for t, M in ((1, 1024), (2, 820), (3, 300), (4, 16)):
             # the active set only ever shrinks (locks are permanent): nested subsets
             active = active if M == len(active) else active[wl.active_positions(50 + M, len(active), M)]
             lock = dev(wl.lock_mask_from_active(N, active))
@@ -44,7 +45,7 @@ def test_c2_full_size_sampled_rows():
             # oracle: block output of the active rows (tokens index w64['emb'] by position)
             x = w64["emb"][active]
             x = model.layer_active(cfg, w64["layers"][0], x, active, Kc[0], Vc[0])
-            sample = np.sort(rng.choice(M, size=min(M, 6), replace=False))
+            sample = np.unique(np.concatenate([rng.choice(M, size=min(M, 5), replace=False), [M - 1, max(0, M - 40)]]))
             hf = cfg.rnd(model.rmsnorm(x[sample], w64["final_norm"], cfg.rms_eps))
             z = cfg.rnd(hf @ lm64.T)
             rows = torch.as_tensor(active[sample], device=DEV, dtype=torch.long)

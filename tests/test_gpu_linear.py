@@ -21,6 +21,7 @@ CASES = [
     (4160, 512, 96, 70),
     (4160, 1024, 320, 300),       # one full 256-row tile and a ragged one
     (2048, 2048, 384, 200),       # the second row tile lies wholly beyond the device-side row count
+    (32768, 512, 300, 290),       # 128 column tiles: one full-height row tile + a half-height tail tile
     (12288, 1536, 704, 700),
     (8192, 4096, 1024, 1000),
     (4096, 12288, 1024, 1024),
@@ -59,7 +60,7 @@ def test_linear_fp32_partials(n, k, m_upper, m, x_tiled):
     assert np.all(np.abs(got - ref) <= _bound(x64, w64, k))
 
 
-@pytest.mark.parametrize("n,k,m_upper,m", CASES[1:8])
+@pytest.mark.parametrize("n,k,m_upper,m", CASES[1:9])
 def test_linear_bf16_row_map(n, k, m_upper, m):
     w, x = _inputs(7 * n + k + m, n, k, m_upper)
     wd, xd = w.to(DEV), x.to(DEV)

@@ -282,17 +282,22 @@ def _check_unlock_run(shape, w, steps, Bn, N, eps, prm, strict):
             assert np.array_equal(sess.relocked.cpu().numpy().reshape(Bn, N), want_rel)
             assert np.array_equal(sess.cool_until.cpu().numpy().reshape(Bn, N), want_cool)
             n_events += int(want_flag.sum())
-            # the posterior store: only carried rows change, and they now hold the kept row
-            per = sess.post.view(sess.T).numel() // 2
-            now, was = sess.post.view(sess.T).view(2, per), post_before.view(sess.T).view(2, per)
+            # the posterior store: only carried rows change, and they now hold the kept row (compared as bytes:
+            # rows no step has written yet hold whatever the allocator left, NaN patterns included)
+            per = sess.post.numel() // 2
+            rb = V * sess.post.view(sess.T).element_size()
+            now, was = sess.post.view(2, per), post_before.view(2, per)
             want_store = was.clone()
             for r in np.flatnonzero(want_flag):
                 g = int(p_idx[r])
                 src, dst = int(us.t_lock_mid.reshape(-1)[g]) & 1, st.t & 1
                 if src != dst:
-                    want_store[dst, g * V:(g + 1) * V] = was[src, g * V:(g + 1) * V]
+                    want_store[dst, g * rb:(g + 1) * rb] = was[src, g * rb:(g + 1) * rb]
                     n_carried += 1
-            assert torch.equal(now, want_store)
+            if not torch.equal(now, want_store):
+                diff = (now != want_store)[:, :Bn * N * rb].view(2, -1, rb).any(dim=2).nonzero().cpu().numpy()
+                raise AssertionError(f"probe t={st.t}: posterior rows changed beyond the carried ones: (buffer, row) "
+                                     f"{diff[:10].tolist()} of {len(diff)}; probed rows {p_idx[:10].tolist()}")
     finally:
         sess.close()
     return n_probes, n_events, n_carried
