@@ -53,12 +53,24 @@ template <int TM> struct TileCfg {
 // PROBE: one workgroup in the middle of the grid also records shader-clock cycles and 100 MHz
 // wall ticks of its prologue, k loop and epilogue into probe[0..7] (a measurement aid: the
 // clock under this kernel is set by the chip's power management, not by the nominal 2.4 GHz).
+// OUT = 3: the Q|K|V projection with RoPE and the scatter into q / the K and V caches in its epilogue
+// (the launch then replaces the projection's fp32 output and the separate RoPE + cache-write kernel).
+struct RopeScatter {
+  const int32_t* active_idx;   // [M] flat row ids
+  const float2* rope_tab;      // [n_pad][64] (cos, sin)
+  bf16_t* q;                   // [M, H*128] packed
+  bf16_t* kc;                  // this layer's K cache, or null (queries only)
+  bf16_t* vc;                  // this layer's V cache, or null
+  int N, n_pad, H;
+};
+
 // One TM x 256 output tile (rows m0 .., column tile tn) by the whole 512-thread workgroup.
 template <int OUT, int TM, bool PROBE>
 __device__ __forceinline__ void ring_tile(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int M, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, const int m0, const int tn, long long* __restrict__ probe) {
+    const int32_t* __restrict__ row_map, size_t ldc, const int m0, const int tn, long long* __restrict__ probe,
+    const RopeScatter& rs) {
   typedef TileCfg<TM> TC;
   constexpr int STAGE = TC::STAGE, NA = TC::NA, HA = TC::HA, NS = TC::NS;
   extern __shared__ Frag lds[];           // [NS stages][A: TM/32 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
@@ -311,6 +323,107 @@ __device__ __forceinline__ void ring_tile(
     }
     return;
   }
+  if (OUT == 3) {
+    // n = 3 H 128 columns = [q | k | v], each a whole number of 256-column tiles: this tile holds two
+    // heads of one of the three.  RoPE pairs dims j and j + 64 of a head, which sit in two different
+    // waves, and the caches want 16-byte units along dims (K) or along slots (V): the fp32 sums go
+    // through LDS 128 rows at a time (the drained ring's space), then all 512 threads rotate, round
+    // and store.  RoPE is applied to the unrounded sums, like the stand-alone kernel does.
+    constexpr int RSf = 260;                          // floats per staged row (16-byte aligned, banks spread)
+    float* stage = reinterpret_cast<float*>(lds);
+    int* slot_sh = reinterpret_cast<int*>(stage + 128 * RSf);      // [128] flat ids of the staged rows, -1 past M
+    int* dense_sh = slot_sh + 128;                                 // [8] per 16-row group (V stores)
+    const int hd = rs.H * 128;
+    const int sec = n0 / hd;                          // 0 q, 1 k, 2 v
+    const int head0 = (n0 - sec * hd) >> 7;
+    const int tid = threadIdx.x;
+#pragma unroll 1
+    for (int p = 0; p < TM / 128; ++p) {
+      __syncthreads();                                // operand stages (or the previous pass) are done with
+      if (TM == 128 || wm == p) {
+        const int lrow0 = TM == 128 ? wm * 64 : 0;
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<f32x4*>(stage + (lrow0 + a * 16 + row_in) * RSf + wn * 64 + b * 16 + col_in) = acc[a][b];
+      }
+      if (tid < 128) {
+        const int row = m0 + p * 128 + tid;
+        slot_sh[tid] = row < M ? rs.active_idx[row] : -1;
+      }
+      __syncthreads();
+      if (sec < 2) {
+        if (sec == 1 && rs.kc == nullptr) continue;   // queries only (uniform over the workgroup)
+#pragma unroll 1
+        for (int it = 0; it < 4; ++it) {
+          const int item = tid + it * 512;
+          const int r = item >> 4, hh = (item >> 3) & 1, c = item & 7;
+          const int g = slot_sh[r];
+          if (g < 0) continue;
+          const int bb = g / rs.N, i = g - bb * rs.N;
+          const float* x1 = stage + r * RSf + hh * 128 + c * 8;
+          const float4* cs = reinterpret_cast<const float4*>(rs.rope_tab + (size_t)i * 64 + c * 8);
+          bf16x8 o1, o2;
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const float4 t = cs[e2];                  // (cos, sin) of pairs 2 e2 and 2 e2 + 1
+            const float a0 = x1[2 * e2], b0 = x1[64 + 2 * e2], a1 = x1[2 * e2 + 1], b1 = x1[64 + 2 * e2 + 1];
+            o1[2 * e2] = (bf16_t)(a0 * t.x - b0 * t.y);
+            o2[2 * e2] = (bf16_t)(b0 * t.x + a0 * t.y);
+            o1[2 * e2 + 1] = (bf16_t)(a1 * t.z - b1 * t.w);
+            o2[2 * e2 + 1] = (bf16_t)(b1 * t.z + a1 * t.w);
+          }
+          const int head = head0 + hh;
+          if (sec == 0) {
+            bf16_t* qr = rs.q + (size_t)(m0 + p * 128 + r) * hd + head * 128 + c * 8;
+            *reinterpret_cast<bf16x8*>(qr) = o1;
+            *reinterpret_cast<bf16x8*>(qr + 64) = o2;
+          } else {
+            bf16_t* kb = rs.kc + ((size_t)bb * rs.H + head) * rs.n_pad * 128;
+            *reinterpret_cast<bf16x8*>(kb + kc_index(i, c * 8, 128)) = o1;
+            *reinterpret_cast<bf16x8*>(kb + kc_index(i, 64 + c * 8, 128)) = o2;
+          }
+        }
+      } else {
+        if (rs.vc == nullptr) continue;
+        // V: 16 consecutive rows that are the 16 consecutive slots of one aligned block leave as
+        // 16-byte groups of eight slots per dim; other rows as 2-byte stores
+        if (tid < 8) {
+          const int g0 = slot_sh[tid * 16];
+          bool dense = g0 >= 0 && (g0 % rs.N) % 16 == 0 && (g0 % rs.N) + 16 <= rs.N;
+          for (int jx = 1; jx < 16 && dense; ++jx) dense = slot_sh[tid * 16 + jx] == g0 + jx;
+          dense_sh[tid] = dense;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int it = 0; it < 8; ++it) {
+          const int item = tid + it * 512;
+          const int vdim = item & 127, vcg = (item >> 7) & 1, hh = (item >> 8) & 1, gi = item >> 9;
+          const int head = head0 + hh;
+          const float* col = stage + (gi * 16) * RSf + hh * 128 + vdim;
+          if (dense_sh[gi]) {
+            const int g0 = slot_sh[gi * 16];
+            const int bb = g0 / rs.N, i0 = g0 - bb * rs.N;
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)col[((e >> 2) * 8 + 4 * vcg + (e & 3)) * RSf];
+            *reinterpret_cast<bf16x8*>(rs.vc + ((size_t)bb * rs.H + head) * rs.n_pad * 128 + vc_index(i0 + 4 * vcg, vdim, 128)) = o;
+          } else {
+#pragma unroll 1
+            for (int e = 0; e < 8; ++e) {
+              const int lr = (e >> 2) * 8 + 4 * vcg + (e & 3);
+              const int g = slot_sh[gi * 16 + lr];
+              if (g < 0) continue;
+              const int bb = g / rs.N, i = g - bb * rs.N;
+              rs.vc[((size_t)bb * rs.H + head) * rs.n_pad * 128 + vc_index(i, vdim, 128)] = (bf16_t)col[lr * RSf];
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
   // fp32 partial plane of this k-split: 16 bytes per lane, 64 contiguous bytes per row
 #pragma unroll
   for (int a = 0; a < NA; ++a) {
@@ -330,12 +443,13 @@ template <int OUT, int TM, bool PROBE = false>
 __global__ __launch_bounds__(512, 2) void gemm_mfma256_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe = nullptr) {
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, long long* __restrict__ probe,
+    RopeScatter rs) {
   const int M = min(*m_dev, m_upper);
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
   if (tn >= tiles_n || tm * TM >= M) return;
-  ring_tile<OUT, TM, PROBE>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TM, tn, probe);
+  ring_tile<OUT, TM, PROBE>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TM, tn, probe, rs);
 }
 
 // Full-height row tiles followed by ONE half-height tile for a row tail of at most 128 rows
@@ -344,20 +458,20 @@ template <int OUT>
 __global__ __launch_bounds__(512, 2) void gemm_mfma256_tail_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n) {
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_m, int tiles_n, RopeScatter rs) {
   const int M = min(*m_dev, m_upper);
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int tn = (j / tiles_m) * 8 + xcd, tm = j % tiles_m;
   if (tn >= tiles_n || tm * TILE >= M) return;
   if (tm == tiles_m - 1)
-    ring_tile<OUT, 128, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr);
+    ring_tile<OUT, 128, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr, rs);
   else
-    ring_tile<OUT, 256, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr);
+    ring_tile<OUT, 256, false>(A, a_tiled, Wp, n, k, k_per_split, M, m_upper, Cf, Cb, row_map, ldc, tm * TILE, tn, nullptr, rs);
 }
 
 template <int OUT, int TM>
 static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
-                       int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+                       int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc, const RopeScatter& rs) {
   const int tiles_m = sl_cdiv(mu, TM), tiles_n = sl_cdiv(n, TILE);
   const size_t sh = (size_t)TileCfg<TM>::NS * TileCfg<TM>::STAGE * 16;
   auto kern = gemm_mfma256_kernel<OUT, TM>;
@@ -365,7 +479,7 @@ static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
-                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, (long long*)nullptr);
+                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, (long long*)nullptr, rs);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -387,7 +501,7 @@ static double ring_rounds_cost(int workgroups) {
 #endif
 template <int OUT>
 static int launch_ring_tail(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
-                            int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+                            int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc, const RopeScatter& rs) {
   const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
   const size_t sh = (size_t)TileCfg<256>::NS * TileCfg<256>::STAGE * 16;       // the larger of the two rings
   auto kern = gemm_mfma256_tail_kernel<OUT>;
@@ -395,7 +509,7 @@ static int launch_ring_tail(hipStream_t s, const void* A, int a_tiled, const voi
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), splits), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf,
-                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n);
+                     (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, rs);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -421,11 +535,12 @@ static int ring_tile_mode(int mu, int n, int splits) {
 
 template <int OUT>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
-                     int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+                     int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc,
+                     const RopeScatter& rs = RopeScatter{}) {
   switch (ring_tile_mode(mu, n, splits)) {
-    case 1: return launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
-    case 2: return launch_ring_tail<OUT>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
-    default: return launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+    case 1: return launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 2: return launch_ring_tail<OUT>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    default: return launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
   }
 }
 
@@ -453,7 +568,7 @@ int slk_gemm_mfma256_probe(hipStream_t s, const void* A, int a_tiled, const void
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
   dim3 grid(8 * tiles_m * sl_cdiv(tiles_n, 8), 1), block(512);
   hipLaunchKernelGGL(kern, grid, block, sh, s, (const bf16_t*)A, a_tiled, (const bf16_t*)Wp, n, k, k, m_dev, mu,
-                     (float*)nullptr, (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, probe);
+                     (float*)nullptr, (bf16_t*)Cb, row_map, ldc, tiles_m, tiles_n, probe, RopeScatter{});
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -465,4 +580,20 @@ int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const 
   if (dff % 32 || k % BK2 || k / BK2 < 8) return SL_EINVAL;
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   return launch256<2>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
+}
+
+// Q|K|V projection + RoPE + scatter in one launch: q [mu, H*128] packed bf16, K / V into the layer's
+// cache at the rows' own slots (kc = vc = null: queries only).  Unsplit only (k / 32 >= 8); H even, so
+// that a 256-column tile is two whole heads of q, k or v.
+int slk_gemm_mfma256_qkv_rope(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int H, int k,
+                              const int32_t* active_idx, int N, int n_pad, const void* rope_tab, void* q, void* kc,
+                              void* vc) {
+  if (mu <= 0) return SL_OK;
+  const int n = 3 * H * 128;
+  if (H < 2 || H % 2 || k % BK2 || k / BK2 < 8 || !active_idx || !rope_tab || !q) return SL_EINVAL;
+  if ((kc == nullptr) != (vc == nullptr)) return SL_EINVAL;
+  if ((uintptr_t)q % 16 || (uintptr_t)kc % 16 || (uintptr_t)vc % 16 || (uintptr_t)rope_tab % 16) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  const RopeScatter rs{active_idx, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc, N, n_pad, H};
+  return launch256<3>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, nullptr, nullptr, (size_t)n, rs);
 }

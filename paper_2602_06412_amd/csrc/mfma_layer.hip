@@ -82,21 +82,31 @@ static inline char* kv_k(const sl_ctx* ctx, int l) {
 }
 static inline char* kv_v(const sl_ctx* ctx, int l) { return kv_k(ctx, ctx->cfg.n_layers) + (size_t)l * ctx->kv_layer_elems * 2; }
 
+#ifndef SL_FUSE_QKV_ROPE
+#define SL_FUSE_QKV_ROPE 1
+#endif
 int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, void* o, void* a, float* f32,
                   float* attn_scratch, const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain) {
   const sl_config& c = ctx->cfg;
   const int d = c.d_model, H = c.n_heads, dh = c.d_head, hd = H * dh, dff = c.d_ff;
   const sl_packed_layer& P = ctx->packed[l];
   const sl_layer_weights& L = ctx->layers[l];
-  // Q | K | V projections in one launch
-  int S = slk_gemm_splits(mu, 3 * hd, d);
-  SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, 1, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
-  SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
-                           ctx->kv, q, ctx->probe_read_only ? nullptr : kv_k(ctx, l),
-                           ctx->probe_read_only ? nullptr : kv_v(ctx, l)));
+  void* kc_w = ctx->probe_read_only ? nullptr : kv_k(ctx, l);      // read-only probe: queries only
+  void* vc_w = ctx->probe_read_only ? nullptr : kv_v(ctx, l);
+  if (SL_FUSE_QKV_ROPE && H % 2 == 0 && slk_gemm_unsplit_thick(mu, 3 * hd, d)) {
+    // thick launches: Q | K | V projection, RoPE and the scatter into q and the caches in one kernel
+    SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma256_qkv_rope(s, h, P.wqkv, m_dev, mu, H, d, active_idx, ctx->n_seq, ctx->n_pad,
+                                                             ctx->kv, q, kc_w, vc_w));
+  } else {
+    // Q | K | V projections in one launch (fp32 partial planes), then RoPE + cache write
+    const int S = slk_gemm_splits(mu, 3 * hd, d);
+    SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, 1, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
+    SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
+                             ctx->kv, q, kc_w, vc_w));
+  }
   SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
                             ctx->n_pad, o, attn_scratch));
-  S = slk_gemm_splits(mu, d, hd);
+  int S = slk_gemm_splits(mu, d, hd);
   SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, 1, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
   SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
   if (slk_gemm_unsplit_thick(mu, 2 * dff, d)) {

@@ -70,3 +70,32 @@ def test_c2_full_size_sampled_rows():
                 assert np.all(e <= np.maximum(2e-2, 2.0 ** (np.floor(np.log2(np.maximum(np.abs(wantkv), 1e-30))) - 7)))
     finally:
         sess.close()
+
+
+def test_c2_probe_of_all_rows_reproduces_the_step():
+    """Full-size read-only probe (the launch whose Q|K|V projection, RoPE and scatter are one kernel, here
+    with the cache stores switched off): after a step with every row active, all rows are locked and
+    probed with unchanged tokens.  The probe then recomputes exactly what the step computed (the cache
+    already holds these K/V), so its logits equal the step's bit for bit, D~ = KL(p^ || p_t*) = 0, and
+    the K/V cache and the posterior store are byte-identical afterwards."""
+    shape, N = wl.C2, 1024
+    w = wl.make_weights(shape, seed=0, device="cuda", emb_std=1.0)
+    sess = B.Session(shape, w, 1, N).unlock_state()
+    try:
+        tokens = dev(wl.prompt_uniform(1, N, shape.vocab, shape.mask_id), torch.int32)
+        eps = dev(np.array([1e-3], dtype=np.float32))
+        zero = torch.zeros(N, dtype=torch.uint8, device=DEV)
+        sess.step(tokens, zero.clone(), zero, eps, 1, 0, N, 0, m_upper=N, new_lock=torch.zeros_like(zero))
+        lock = torch.ones(N, dtype=torch.uint8, device=DEV)
+        sess.t_lock.fill_(1)
+        kv_before, post_before = sess.kv.clone(), sess.post.clone()
+        sess.unlock_probe(tokens, lock, 3, 20.0, float("inf"), 0, 1, m_upper_probe=N, m_upper_active=N)
+        torch.cuda.synchronize()
+        assert int(sess.cu_probe[-1].item()) == N
+        assert torch.equal(sess.probe_idx.cpu(), torch.arange(N, dtype=torch.int32))
+        assert torch.equal(sess.kv, kv_before) and torch.equal(sess.post, post_before)
+        assert torch.equal(sess.probe_logits.view(torch.int16), sess.logits_view(1).view(torch.int16))
+        assert torch.all(sess.probe_kl == 0)
+        assert int(sess.unlocked.sum().item()) == 0 and int(lock.sum().item()) == N
+    finally:
+        sess.close()
