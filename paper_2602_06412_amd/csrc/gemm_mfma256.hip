@@ -247,7 +247,9 @@ __device__ __forceinline__ void ring_tile(
 #undef SL_INTERLEAVE
 
   const int row_in = lane & 15, col_in = 4 * (lane >> 4);   // this lane's place in a 16 x 16 block
-  if (OUT == 1) {
+  if (OUT == 1 || OUT == 4) {
+    // OUT = 4: the residual add in the epilogue, Cb [m, n] row-major <- rnd(Cb + sums) in place (each
+    // element belongs to exactly one workgroup, which reads it before it writes it).
     // bf16 rows: a lane's piece of a row is 8 bytes, scattered over 16 rows per instruction.  The
     // ring is drained, so each wave stages its 128 x 64 sub-tile in LDS as bf16 (row stride 144
     // bytes) with 8-byte writes and sends it out as 16-byte stores, eight lanes per 128-byte
@@ -260,8 +262,16 @@ __device__ __forceinline__ void ring_tile(
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         bf16x4 v4;
+        if (OUT == 4) {
+          const int row = m0 + wm * (TM / 2) + a * 16 + row_in, col = n0 + wn * 64 + b * 16 + col_in;
+          bf16x4 x4 = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+          if (row < M && col < n) x4 = *reinterpret_cast<const bf16x4*>(Cb + (size_t)row * ldc + col);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) v4[v] = (bf16_t)acc[a][b][v];
+          for (int v = 0; v < 4; ++v) v4[v] = (bf16_t)((float)x4[v] + acc[a][b][v]);
+        } else {
+#pragma unroll
+          for (int v = 0; v < 4; ++v) v4[v] = (bf16_t)acc[a][b][v];
+        }
         *reinterpret_cast<bf16x4*>(stage + (a * 16 + row_in) * RS + b * 16 + col_in) = v4;
       }
     // same-wave LDS traffic is ordered; no barrier needed between a wave's writes and its reads
@@ -277,7 +287,8 @@ __device__ __forceinline__ void ring_tile(
         // streaming store: these rows (the step's logits, 259 MB at M = 1024) are read once by the
         // next kernel and would otherwise sit dirty in the memory-side cache and be written back
         // under that kernel's reads (scoring 111 -> 99 us)
-        __builtin_nontemporal_store(val, reinterpret_cast<Frag*>(Cb + orow * ldc + col));
+        if (OUT == 4) *reinterpret_cast<Frag*>(Cb + orow * ldc + col) = val;     // read again by the norm kernel
+        else __builtin_nontemporal_store(val, reinterpret_cast<Frag*>(Cb + orow * ldc + col));
       }
     }
     if (PROBE) {
@@ -596,4 +607,14 @@ int slk_gemm_mfma256_qkv_rope(hipStream_t s, const void* A, const void* Wp, cons
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
   const RopeScatter rs{active_idx, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc, N, n_pad, H};
   return launch256<3>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, nullptr, nullptr, (size_t)n, rs);
+}
+
+// x [mu, n] bf16 row-major <- rnd(x + A W^T) in place: a projection with the residual add in its
+// epilogue (unsplit only; n % 8 == 0 for the 16-byte row pieces).
+int slk_gemm_mfma256_residual(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                              void* x) {
+  if (mu <= 0) return SL_OK;
+  if (n % 32 || k % BK2 || k / BK2 < 8 || !x || (uintptr_t)x % 16) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  return launch256<4>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, x, nullptr, (size_t)n);
 }

@@ -85,6 +85,9 @@ static inline char* kv_v(const sl_ctx* ctx, int l) { return kv_k(ctx, ctx->cfg.n
 #ifndef SL_FUSE_QKV_ROPE
 #define SL_FUSE_QKV_ROPE 1
 #endif
+#ifndef SL_FUSE_RESIDUAL
+#define SL_FUSE_RESIDUAL 1
+#endif
 int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, void* o, void* a, float* f32,
                   float* attn_scratch, const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain) {
   const sl_config& c = ctx->cfg;
@@ -106,9 +109,16 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   }
   SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
                             ctx->n_pad, o, attn_scratch));
-  int S = slk_gemm_splits(mu, d, hd);
-  SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, 1, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
-  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
+  int S = 1;
+  if (SL_FUSE_RESIDUAL && slk_gemm_unsplit_thick(mu, d, hd)) {
+    // thick launches: the residual add runs in the projection's epilogue, the norm reads the new x
+    SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma256_residual(s, o, P.wo, m_dev, mu, d, hd, x));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_rmsnorm(s, SL_BF16, x, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
+  } else {
+    S = slk_gemm_splits(mu, d, hd);
+    SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma(s, o, 1, P.wo, m_dev, mu, d, hd, S, f32, nullptr, nullptr, d));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
+  }
   if (slk_gemm_unsplit_thick(mu, 2 * dff, d)) {
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma256_swiglu(s, h, P.wgu, m_dev, mu, dff, d, a));
   } else {
@@ -116,9 +126,14 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1, 1));
   }
-  S = slk_gemm_splits(mu, d, dff);
-  SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, 1, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
-  SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h, 1));
+  if (SL_FUSE_RESIDUAL && slk_gemm_unsplit_thick(mu, d, dff)) {
+    SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma256_residual(s, a, P.wdown, m_dev, mu, d, dff, x));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_rmsnorm(s, SL_BF16, x, m_dev, mu, d, next_gain, c.rms_eps, h, 1));
+  } else {
+    S = slk_gemm_splits(mu, d, dff);
+    SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma(s, a, 1, P.wdown, m_dev, mu, d, dff, S, f32, nullptr, nullptr, d));
+    SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_add_rmsnorm(s, SL_BF16, x, f32, S, (size_t)mu * d, m_dev, mu, d, next_gain, c.rms_eps, h, 1));
+  }
   return SL_OK;
 }
 

@@ -206,6 +206,8 @@ int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d,
                 const void* gain, float eps, void* h, int tiled);
 int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta);
+int slk_gemm_mfma256_residual(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
+                              void* x);
 int slk_gemm_mfma256_qkv_rope(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int H, int k,
                               const int32_t* active_idx, int N, int n_pad, const void* rope_tab, void* q, void* kc,
                               void* vc);
