@@ -145,3 +145,49 @@ def test_bf16_run_with_selection_forced_schedule(Bn, n_p, n_gen, T, block, M_end
     steps = run_oracle(cfg, w64, prompts, n_gen, T, block, eps, forced_M_end=M_end, seed=4,
                        select_k=float(np.float32(k_frac)))
     assert _check_selected_run(shape, w, steps, Bn, n_p + n_gen, eps, k_frac) > 50
+
+
+def test_selected_step_with_k_one_is_the_plain_step_and_argument_errors():
+    """k = 1 selects every non-locked row: logits, scores, masks and the cache must equal the plain
+    step's bit for bit (the selection then only adds its bookkeeping)."""
+    shape = wl.S_BF16
+    w = weights_to_device(wl.make_weights(shape, seed=3, norm_gain_jitter=0.05))
+    N = 136
+    rng = np.random.default_rng(5)
+    tokens0 = wl.prompt_zipf(21, N, shape.vocab, shape.mask_id)
+    lock_np = (rng.random(N) < 0.3).astype(np.uint8)
+    masked_np = ((rng.random(N) < 0.4) & (lock_np == 0)).astype(np.uint8)
+    eps_d = dev(np.array([1e-3], dtype=np.float32))
+    res = []
+    for selected in (False, True):
+        sess = B.Session(shape, w, 1, N)
+        try:
+            zero = torch.zeros(N, dtype=torch.uint8, device=DEV)
+            for t, lock in ((1, zero), (2, dev(lock_np))):
+                tokens, masked = dev(tokens0, torch.int32), dev(masked_np if t == 2 else np.zeros(N, np.uint8))
+                new_lock = torch.full((N,), 9, dtype=torch.uint8, device=DEV)
+                if selected:
+                    sess.step_selected(tokens, masked, lock, eps_d, t, 40, 104, 3, 1.0, new_lock=new_lock)
+                else:
+                    sess.step(tokens, masked, lock, eps_d, t, 40, 104, 3, new_lock=new_lock)
+            torch.cuda.synchronize()
+            M = int(sess.cu_active[-1].item())
+            res.append((M, sess.active_idx[:M].clone(), sess.logits_view(2).view(torch.int16).clone(), sess.kl[:M].clone(),
+                        sess.conf[:M].clone(), sess.argmax[:M].clone(), new_lock.clone(), tokens.clone(), masked.clone(),
+                        sess.kv.clone()))
+            if selected:
+                assert torch.equal(sess.compute_mask, dev(lock_np))
+                with pytest.raises(B.SureLockError):                       # fraction out of range
+                    sess.step_selected(tokens, masked, lock, eps_d, 3, 40, 104, 3, 0.0, new_lock=new_lock)
+                with pytest.raises(B.SureLockError):                       # compute_mask aliases the lock mask
+                    B.sl_surelock_step_selected(sess.ctx, tokens, masked, lock, eps_d, 3, 40, 104, 3, 0.8, sess.d_last, lock,
+                                                N, sess.active_idx, sess.cu_active, sess.kl, sess.conf, sess.argmax,
+                                                new_lock, sess.workspace)
+        finally:
+            sess.close()
+    a, b = res
+    assert a[0] == b[0] == int((lock_np == 0).sum())
+    rows = a[1].long()
+    assert torch.equal(a[2][rows], b[2][rows])
+    for i in (1, 3, 4, 5, 6, 7, 8, 9):
+        assert torch.equal(a[i], b[i]), i

@@ -339,3 +339,31 @@ def test_bf16_run_with_unlocking_forced_schedule(Bn, n_p, n_gen, T, block, M_end
         assert np.array_equal(s.lock_out, s.lock_mid & ~un.astype(bool))
     n_probes, n_events, n_carried = _check_unlock_run(shape, w, steps, Bn, n_p + n_gen, eps, prm, strict=False)
     assert n_probes == T // 2 and n_events > 0 and n_carried > 0
+
+
+@pytest.mark.parametrize("gate", [0.0, 20.0])
+def test_relock_rule_without_unlock_history_is_the_plain_rule(gate):
+    """No position unlocked before, no cool-down running, rho = 1: sl_lock_rule_relock must give what
+    sl_lock_rule / sl_lock_rule_gated give on the same inputs (and record the lock step)."""
+    Bn, N, t = 3, 500, 6
+    rng = np.random.default_rng(9)
+    lock = (rng.random((Bn, N)) < 0.4).astype(np.uint8)
+    masked = ((rng.random((Bn, N)) < 0.3) & (lock == 0)).astype(np.uint8)
+    idx, cu = control.compact_active(lock)
+    M = len(idx)
+    kl, conf = (rng.random(M) * 2e-3).astype(np.float32), rng.random(M).astype(np.float32)
+    eps = (rng.random(Bn) * 2e-3).astype(np.float32)
+    args = (dev(lock.reshape(-1)), dev(masked.reshape(-1)), dev(idx, torch.int32), dev(cu, torch.int32))
+    plain = torch.full((Bn * N,), 7, dtype=torch.uint8, device=DEV)
+    if gate > 0:
+        B.sl_lock_rule_gated(*args, Bn * N, dev(kl), dev(conf), dev(eps), gate, Bn, N, 0, plain)
+    else:
+        B.sl_lock_rule(args[0], args[1], args[2], args[3][Bn:], Bn * N, dev(kl), dev(eps), Bn, N, 0, plain)
+    out = torch.full((Bn * N,), 7, dtype=torch.uint8, device=DEV)
+    tl = torch.zeros(Bn * N, dtype=torch.int32, device=DEV)
+    z8, zi = torch.zeros(Bn * N, dtype=torch.uint8, device=DEV), torch.zeros(Bn * N, dtype=torch.int32, device=DEV)
+    B.sl_lock_rule_relock(*args, Bn * N, dev(kl), dev(conf), dev(eps), gate, z8, zi, 1.0, t, Bn, N, out, tl)
+    torch.cuda.synchronize()
+    assert torch.equal(out, plain)
+    newly = (out.cpu().numpy() == 1) & (lock.reshape(-1) == 0)
+    assert newly.sum() > 0 and np.array_equal(tl.cpu().numpy(), np.where(newly, t, 0))
