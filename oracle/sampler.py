@@ -10,7 +10,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-from . import control, model, posterior
+from . import control, model, posterior, sampling
 
 
 @dataclass
@@ -63,6 +63,7 @@ class StepRecord:
     F: list                       # positions the KL rule locks at this step
     forced: list = field(default_factory=list)   # positions locked by a forced schedule
     probe: ProbeRecord = None     # set on the steps where the unlock probe ran
+    write_id: np.ndarray = None   # [M] the token UpdateMASK would write per row (argmax, or the draw at tau > 0)
 
 
 def init_state(cfg, weights, prompt_tokens, n_gen):
@@ -87,7 +88,7 @@ def init_state(cfg, weights, prompt_tokens, n_gen):
 
 def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
                   gate_m=None, candidates_pre_update=False, forced_lock=None,
-                  kl_drives_lock=True, unlock=None, select_k=None):
+                  kl_drives_lock=True, unlock=None, select_k=None, temperature=0.0, seed=0, seq_index=0):
     """One iteration of the loop of Alg. 1, in the paper's order.
 
     eps < 0 can never be met by a KL (>= 0), which turns locking off.
@@ -101,6 +102,10 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
     only control.select_rows' choice among the non-locked positions is computed;
     a skipped position keeps its K/V, its posterior and its lock state, and its
     next KL is taken against the posterior of the step it was last computed at.
+    temperature > 0 (App. on sampling temperature): UpdateMASK still ranks by the
+    raw-posterior confidence but writes a token drawn from softmax(z / temperature)
+    (sampling.sample_token, keyed by seed, the step and the flat row id
+    seq_index * N + position); scores and the lock test are untouched.
     """
     st.t += 1
     t = st.t
@@ -116,8 +121,14 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
     amax = posterior.argmax_lowest(z)
     # unmasking
     masked_before = st.masked.copy()
+    write_id = amax.copy()
+    if temperature > 0:
+        N = len(st.tokens)
+        for r, p in enumerate(A):
+            if st.masked[p] and block_lo <= p < block_hi:
+                write_id[r] = sampling.sample_token(z[r], temperature, seed, t, seq_index * N + int(p))
     unmasked = control.update_mask(st.masked, st.tokens, A,
-                                   conf.astype(np.float32), amax, block_lo, block_hi, k)
+                                   conf.astype(np.float32), write_id, block_lo, block_hi, k)
     # score
     u = posterior.uncertainty(lp)
     if t > 1:
@@ -132,7 +143,7 @@ def surelock_step(cfg, weights, st, eps, block_lo, block_hi, k,
                           cool_until=st.cool_until if unlock is not None else None,
                           rho=unlock.rho if unlock is not None else 1.0, t=t)
     rec = StepRecord(t=t, active_pos=A, logits=z, kl=D, u=u, conf=conf, argmax=amax,
-                     unmasked=unmasked, F=F)
+                     unmasked=unmasked, F=F, write_id=write_id)
     # posteriors of the active rows become p_{t-1}; locked rows keep p_{t*}
     st.prev_lp[A] = lp
     st.d_last[A] = np.maximum(D, 0.0).astype(np.float32)       # KL >= 0; rounding may leave -1e-17
