@@ -63,6 +63,10 @@ typedef struct sl_config {
   float gate_percentile;         /* 0: the optional confidence gate of the lock rule is off (the
                                   * step then uses sl_lock_rule); m in (0, 100]: the step uses
                                   * sl_lock_rule_gated with this m (Sec. 2.2)                      */
+  float temperature;             /* 0: UpdateMASK writes the argmax (the paper's setting); tau > 0: it
+                                  * writes a token drawn from softmax(z / tau), see sl_sample_tokens.
+                                  * Scores and the lock test always use the raw posterior.          */
+  uint64_t seed;                 /* key of the draws (temperature > 0)                              */
 } sl_config;
 
 /* Plain weights, caller-owned device memory of type T, `[out_features, in_features]`
@@ -212,6 +216,22 @@ int sl_score_posteriors(void *stream, const void *logits_cur, int32_t cur_packed
 int sl_unmask_topk(void *stream, int32_t *tokens, uint8_t *masked, const int32_t *active_idx,
                    const int32_t *cu_active, const float *conf, const int32_t *argmax,
                    int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi, int32_t k);
+
+/* The token UpdateMASK writes at temperature tau > 0 (appendix on sampling temperature): for every
+ * active row r whose position is still masked and inside [block_lo, block_hi), write_id[r] = a token
+ * drawn from softmax(z_r / tau) in Gumbel-max form, argmax_v (z_v + tau * G_v), G_v = -ln(-ln U_v)
+ * (fp32, lowest id on ties); every other row gets write_id[r] = argmax[r].  U_v is word v % 4 of the
+ * Philox4x32-10 block with counter (v / 4, flat row id g, t, 0) and key (seed low word, seed high
+ * word), mapped to (2 (x >> 9) + 1) / 2^24: the draw depends on (seed, t, g) only, not on the launch.
+ * Rows as in sl_score_posteriors (cur_packed, dtype, vocab % 8 == 0); pass write_id as the `argmax`
+ * argument of sl_unmask_topk.  The step does both when sl_config.temperature > 0.
+ * scratch: 64 * m_upper bytes of device memory, 8-byte aligned (a row is streamed by eight workgroups,
+ * each leaves a candidate there). */
+int sl_sample_tokens(void *stream, const void *logits_cur, int32_t cur_packed, int32_t dtype, int32_t vocab,
+                     const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
+                     const uint8_t *masked, int32_t n_seq, int32_t block_lo, int32_t block_hi,
+                     float temperature, uint64_t seed, int32_t t, const int32_t *argmax, int32_t *write_id,
+                     void *scratch, size_t scratch_bytes);
 
 /* Candidates Z_t = active and unmasked; F_t = {i in Z_t : D_i <= eps_b}; new_lock =
  * lock | F_t (gate disabled).  first_step != 0 locks nothing. */

@@ -18,7 +18,7 @@ class sl_config(C.Structure):
                 ("d_head", C.c_int32), ("d_ff", C.c_int32), ("vocab", C.c_int32),
                 ("dtype", C.c_int32), ("mask_id", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("candidates_pre_update", C.c_int32),
-                ("gate_percentile", C.c_float)]
+                ("gate_percentile", C.c_float), ("temperature", C.c_float), ("seed", C.c_uint64)]
 
 
 class sl_layer_weights(C.Structure):
@@ -55,6 +55,7 @@ _SIGS = {
     "sl_lock_rule": [_P, _P, _P, _P, _P, _I, _P, _P, _I, _I, _I, _P],
     "sl_lock_rule_gated": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _I, _I, _I, _P],
     "sl_select_rows": [_P, _P, _P, _P, _I, _I, _I, _I, C.c_float, _P],
+    "sl_sample_tokens": [_P, _P, _I, _I, _I, _P, _P, _I, _P, _I, _I, _I, C.c_float, C.c_uint64, _I, _P, _P, _P, _Z],
     "sl_lock_rule_relock": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _P, _P, C.c_float, _I, _I, _I, _P, _P],
     "sl_unlock_probe": [_P, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
     "sl_unlock_rule": [_P, _P, _P, _P, _P, _P, _P, _P, _I, _P, _P, _P, _I, _P, C.c_float, C.c_float, _I, _I, _I, _P],
@@ -119,10 +120,10 @@ def dtype_code(dt):
     return {torch.float32: SL_F32, torch.bfloat16: SL_BF16}[dt]
 
 
-def make_config(shape, candidates_pre_update=0, gate_percentile=0.0):
+def make_config(shape, candidates_pre_update=0, gate_percentile=0.0, temperature=0.0, seed=0):
     return sl_config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab,
                      {"fp32": SL_F32, "bf16": SL_BF16}[shape.storage], shape.mask_id, shape.rms_eps,
-                     shape.rope_theta, int(candidates_pre_update), float(gate_percentile))
+                     shape.rope_theta, int(candidates_pre_update), float(gate_percentile), float(temperature), int(seed))
 
 
 # ---- entry points, same names as the header -------------------------------------------------
@@ -241,6 +242,16 @@ def sl_lock_rule_gated(lock, masked, active_idx, cu_active, m_upper, kl, conf, e
         C.c_float(gate_percentile), batch, n_seq, int(first_step), _ptr(new_lock)))
 
 
+def sl_sample_tokens(logits_cur, cur_packed, dtype, vocab, active_idx, m_dev, m_upper, masked, n_seq, block_lo, block_hi,
+                     temperature, seed, t, argmax, write_id, scratch=None):
+    if scratch is None:
+        scratch = torch.empty(max(64 * m_upper, 64), dtype=torch.uint8, device=write_id.device)
+    _check("sl_sample_tokens", lib().sl_sample_tokens(
+        _stream(), _ptr(logits_cur), int(cur_packed), dtype, vocab, _ptr(active_idx), _ptr(m_dev), m_upper, _ptr(masked),
+        n_seq, block_lo, block_hi, C.c_float(temperature), C.c_uint64(seed), t, _ptr(argmax), _ptr(write_id),
+        _ptr(scratch), scratch.numel()))
+
+
 def sl_select_rows(lock, masked, d_last, batch, n_seq, block_lo, block_hi, select_fraction, compute_mask):
     _check("sl_select_rows", lib().sl_select_rows(_stream(), _ptr(lock), _ptr(masked), _ptr(d_last), batch, n_seq,
                                                   block_lo, block_hi, C.c_float(select_fraction), _ptr(compute_mask)))
@@ -334,11 +345,11 @@ class Session:
     workspace, per-step outputs) and forwards to the entry points above."""
 
     def __init__(self, shape, weights, batch, n_seq, device="cuda:0", candidates_pre_update=False,
-                 gate_percentile=0.0):
+                 gate_percentile=0.0, temperature=0.0, seed=0):
         self.shape, self.B, self.N, self.device = shape, batch, n_seq, torch.device(device)
         self.weights = weights
         self.T = {"fp32": torch.float32, "bf16": torch.bfloat16}[shape.storage]
-        self.ctx = sl_init(make_config(shape, candidates_pre_update, gate_percentile))
+        self.ctx = sl_init(make_config(shape, candidates_pre_update, gate_percentile, temperature, seed))
         dev = self.device
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
         self.packed = u8(sl_packed_weights_bytes(self.ctx))

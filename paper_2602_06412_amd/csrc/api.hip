@@ -29,6 +29,7 @@ static bool cfg_ok(const sl_config* c) {
   if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return false;
   if (c->candidates_pre_update != 0 && c->candidates_pre_update != 1) return false;
   if (!(c->gate_percentile >= 0.f) || c->gate_percentile > 100.f) return false;
+  if (!(c->temperature >= 0.f)) return false;
   return true;
 }
 
@@ -241,7 +242,11 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows, int batch, int n
   const size_t rows32 = sl_align_up((size_t)rows, 32);     // tiled activation buffers hold whole 32-row blocks
   w.x = take((size_t)rows * c.d_model * ts);
   w.h = take(rows32 * c.d_model * ts);
-  w.q = take((size_t)rows * hd * ts);
+  // q doubles as scratch once the layers are done (token draws: ids + per-part candidates; probe: row indices)
+  size_t q_bytes = (size_t)rows * hd * ts;
+  const size_t draw_bytes = sl_align_up((size_t)rows * sizeof(int32_t), 256) + slk_sample_scratch_bytes(rows);
+  if (draw_bytes > q_bytes) q_bytes = draw_bytes;
+  w.q = take(q_bytes);
   w.o = take(rows32 * hd * ts);
   w.a = take(rows32 * c.d_ff * ts);
   size_t f32_elems = (size_t)rows * f32_cols;
@@ -381,6 +386,18 @@ extern "C" int sl_lock_rule_gated(void* stream, const uint8_t* lock, const uint8
                              gate_percentile, batch, n_seq, first_step, new_lock);
 }
 
+extern "C" int sl_sample_tokens(void* stream, const void* logits_cur, int32_t cur_packed, int32_t dtype, int32_t vocab,
+                               const int32_t* active_idx, const int32_t* m_dev, int32_t m_upper, const uint8_t* masked,
+                               int32_t n_seq, int32_t block_lo, int32_t block_hi, float temperature, uint64_t seed,
+                               int32_t t, const int32_t* argmax, int32_t* write_id, void* scratch, size_t scratch_bytes) {
+  if (!logits_cur || !active_idx || !m_dev || !masked || !argmax || !write_id || !scratch) return SL_EINVAL;
+  if (m_upper > 0 && scratch_bytes < slk_sample_scratch_bytes(m_upper)) return SL_ENOSPC;
+  if ((dtype != SL_F32 && dtype != SL_BF16) || vocab < 8 || vocab % 8 || m_upper < 0 || n_seq < 1) return SL_EINVAL;
+  if (block_lo < 0 || block_hi > n_seq || block_lo > block_hi || !(temperature > 0.f) || t < 1) return SL_EINVAL;
+  return slk_sample_tokens((hipStream_t)stream, logits_cur, cur_packed, dtype, vocab, active_idx, m_dev, m_upper, masked,
+                           n_seq, block_lo, block_hi, temperature, seed, t, argmax, write_id, scratch);
+}
+
 extern "C" int sl_select_rows(void* stream, const uint8_t* lock, const uint8_t* masked, const float* d_last,
                              int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi, float select_fraction,
                              uint8_t* compute_mask) {
@@ -515,7 +532,17 @@ static int step_impl(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked
     return slk_lock_rule(s, lock, masked, active_idx, m_dev, m_upper, kl, eps, B, N, t == 1, new_lock);
   };
   if (c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
-  SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, argmax, B, N, block_lo, block_hi, k));
+  const int32_t* write_id = argmax;
+  if (c.temperature > 0.f) {
+    // the tokens UpdateMASK may write are drawn from softmax(z / temperature); ranking stays on conf
+    // the query buffer is free once the layers are done: [m_upper] drawn ids, then the per-part candidates
+    int32_t* drawn = (int32_t*)ws.q;
+    void* parts = ws.q + sl_align_up((size_t)m_upper * sizeof(int32_t), 256);
+    SL_RUN(ctx, s, SL_PROF_UNMASK, slk_sample_tokens(s, cur, 0, c.dtype, c.vocab, active_idx, m_dev, m_upper, masked, N,
+                                                     block_lo, block_hi, c.temperature, c.seed, t, argmax, drawn, parts));
+    write_id = drawn;
+  }
+  SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, write_id, B, N, block_lo, block_hi, k));
   if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;
 }

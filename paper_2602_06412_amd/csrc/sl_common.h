@@ -174,6 +174,10 @@ int slk_unlock_rule(hipStream_t s, uint8_t* lock, uint8_t* relocked, int32_t* co
                     const int32_t* probe_idx, const int32_t* cu_probe, int mp_upper, const float* kl_probe,
                     const float* conf_probe, const int32_t* cu_active, int ma_upper, const float* conf_active, float m,
                     float eps_unlock, int t, int d_interval, int d_cool, int B, int N, uint8_t* unlocked);
+int slk_sample_tokens(hipStream_t s, const void* logits, int cur_packed, int dtype, int V, const int32_t* active_idx,
+                      const int32_t* m_dev, int m_upper, const uint8_t* masked, int N, int lo, int hi, float tau,
+                      unsigned long long seed, int t, const int32_t* argmax, int32_t* write_id, void* scratch);
+size_t slk_sample_scratch_bytes(int m_upper);
 int slk_select_rows(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const float* d_last, int B, int N,
                     int lo, int hi, float k_frac, uint8_t* compute_mask);
 int slk_posterior_carry_skipped(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const uint8_t* lock,
