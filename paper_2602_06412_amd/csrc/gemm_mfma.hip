@@ -366,6 +366,12 @@ struct GemmPlan {
 // swiglu_consumer: the output is the gate|up pair that SwiGLU consumes; an unsplit launch of the
 // 256 x 256 kernel then writes bf16 activations from its epilogue, every other plan writes fp32
 // planes that a second kernel reads back.
+#ifndef SL_PLAN_HALF
+#define SL_PLAN_HALF 1
+#endif
+#ifndef SL_PLAN_HALF_COST
+#define SL_PLAN_HALF_COST 0.6
+#endif
 static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
   GemmPlan p{0, 1};
   if (mu <= kThinMax) {
@@ -388,8 +394,16 @@ static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
     if (k / (32 * s) < 8) break;
     const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
     const double fused_us = (double)mu * n / 5.0e6;      // bf16 activations of half the width, written once
-    const double t = sl_cdiv(t256 * s, 256) * (k / (32.0 * s) + 4.0) * 0.8 +
-                     (swiglu_consumer && s == 1 ? fused_us : traffic_us);
+    // the ring launcher runs full-height or half-height tiles, whichever its rounds model prefers: price both
+    const double per_tile = (k / (32.0 * s) + 4.0) * 0.8;
+    double ring_us = sl_cdiv(t256 * s, 256) * per_tile;
+    if (SL_PLAN_HALF) {
+      // (0.6 rather than the measured 0.565-0.585: near-ties go to the full-height tile, whose split plans
+      // measured better where the two were within a few per cent)
+      const double half_us = sl_cdiv(t128 * s, 256) * per_tile * SL_PLAN_HALF_COST;
+      if (half_us < ring_us) ring_us = half_us;
+    }
+    const double t = ring_us + (swiglu_consumer && s == 1 ? fused_us : traffic_us);
     if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
   }
   if (p.thick256) return p;
