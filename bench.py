@@ -54,6 +54,44 @@ def lm_head_clock_probe(B, torch, w_lm, M, V, d, seed, launches=12):
             "epilogue_us": round(c[5] / 100.0, 2), "workgroups": c[6], "k_tiles": c[7], "nominal_mhz": 2400}
 
 
+def achievable_peaks(B, torch, dev, seed):
+    """What the chip sustains with nothing else in the way (the library's two peak probes): a bare loop of the
+    projection kernels' MFMA instruction on N(0,1) bf16 register operands, and one read-only / one copying pass
+    over 1 GiB.  Timed with events on the stream the probes are launched on (torch's current one)."""
+    g = torch.Generator(device="cpu").manual_seed(seed + 11)
+    operands = torch.randn(4096, generator=g).to(torch.bfloat16).to(dev)
+    sink = torch.zeros(1 << 19, dtype=torch.float32, device=dev)                  # 2 MiB
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    out = {}
+    for wps in (1, 2):
+        iters = 16384 // wps
+        B.sl_peak_probe_mfma(operands, 1024, wps, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        flops = 0
+        for _ in range(4):
+            flops += B.sl_peak_probe_mfma(operands, iters, wps, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out["mfma_bf16_tflops_%d_wave%s_per_simd" % (wps, "" if wps == 1 else "s")] = round(
+            flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    src = torch.randn(1 << 28, dtype=torch.float32, device=dev)                   # 1 GiB
+    dst = torch.empty_like(src)
+    for name, d_, factor in (("hbm_read_GBps", None, 1), ("hbm_copy_GBps", dst, 2)):
+        B.sl_peak_probe_stream(src, d_, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            B.sl_peak_probe_stream(src, d_, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(10 * factor * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    del src, dst
+    out["note"] = ("bare v_mfma_f32_16x16x32_bf16 loop on N(0,1) bf16 register operands (one workgroup per CU); "
+                   "one pass of 16-byte loads over 1 GiB, read-only and copied (bytes read + written)")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -219,6 +257,16 @@ def main():
     if M0 >= 512:
         roof["clock"] = lm_head_clock_probe(B, torch, w["lm_head"], M0, V, d, args.seed)
 
+    ach_peaks = achievable_peaks(B, torch, dev, args.seed)
+    mfma_ach = max(v for k_, v in ach_peaks.items() if k_.startswith("mfma_bf16_tflops"))
+    if roof["bound"] == "mfma":
+        roof["frac_of_achievable"] = round(roof["achieved"] / mfma_ach, 4)
+    else:
+        roof["frac_of_achievable"] = round(roof["achieved"] / ach_peaks["hbm_read_GBps"], 4)
+    for r_ in results:
+        r_["gemm_frac_of_achievable_mfma"] = round(r_["gemm_tflops"] / mfma_ach, 4)
+        r_["score_frac_of_achievable_hbm_read"] = round(r_["score_hbm_frac"] * HBM_PEAK / 1e9 / ach_peaks["hbm_read_GBps"], 4)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(shape, w, tokens0, N)
@@ -233,6 +281,7 @@ def main():
                    "d_ff": dff, "vocab": V, "n_layers": shape.n_layers},
         "rows_per_s": head["rows_per_s"],
         "roofline": roof,
+        "achievable": ach_peaks,
         "cpu_baseline": cpu,
         "sweep": results,
         "selected_step": {"k": k_sel, "non_locked_rows": N, "computed_rows": M_sel, "ms": round(sel_ms, 4),

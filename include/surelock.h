@@ -355,6 +355,26 @@ int sl_linear_clock_probe(void *stream, const void *x, int32_t x_tiled, const vo
                           int32_t m_upper, int32_t n, int32_t k, void *y_bf16, const int32_t *row_map,
                           int64_t *counters);
 
+/* Measurement aids for the rooflines of Sec. 2.4's terms: what the chip sustains on the matrix units
+ * and on HBM with nothing else in the way, so that a kernel's rate can be read against the published
+ * peak and against the achievable one.
+ * sl_peak_probe_mfma: one launch of one workgroup per compute unit with 4 x waves_per_simd waves, each
+ *   wave running iters x 16 independent v_mfma_f32_16x16x32_bf16 on register operands.
+ *   operands: device, >= 8192 bytes (operand_bytes), 16-byte aligned: eight 64-lane bf16x8 fragments,
+ *   any finite values (the clock the power management grants depends on them: use the distribution of
+ *   the workload).  iters in [1, 2^24]; waves_per_simd 1 or 2.  sink: device floats, one per launched
+ *   thread (sink_bytes >= compute units x waves_per_simd x 1024; 1 MiB covers this chip).
+ *   *flops (host) receives the floating-point operations of the launch.
+ * sl_peak_probe_stream: one grid-stride pass of 16-byte loads over src[bytes] (device, 16-byte aligned,
+ *   bytes a multiple of 16); dst null: read only, the words XOR-folded into sink; dst non-null (same
+ *   size, no overlap with src): copied.  sink: device uint32, one per launched thread (sink_bytes >=
+ *   compute units x 8192; 2 MiB covers this chip).  HBM bytes moved: bytes (read only), 2 x bytes (copy).
+ * Both enqueue on stream and return; the caller times them.  SL_EINVAL for null / misaligned /
+ * out-of-range arguments, SL_ENOSPC for an operand or sink buffer that is too small. */
+int sl_peak_probe_mfma(void *stream, const void *operands, size_t operand_bytes, int32_t iters, int32_t waves_per_simd,
+                       float *sink, size_t sink_bytes, int64_t *flops);
+int sl_peak_probe_stream(void *stream, const void *src, void *dst, size_t bytes, uint32_t *sink, size_t sink_bytes);
+
 /* ---- measurement support ------------------------------------------------------------
  * Per-kernel timing of the step's launches with HIP events on the step's own stream.
  * Between sl_profile_begin and sl_profile_end every kernel the library launches for this

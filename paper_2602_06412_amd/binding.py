@@ -63,6 +63,8 @@ _SIGS = {
     "sl_linear_splits": [_I, _I, _I],
     "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
     "sl_linear_clock_probe": [_P, _P, _I, _P, _P, _I, _I, _I, _P, _P, _P],
+    "sl_peak_probe_mfma": [_P, _P, _Z, _I, _I, _P, _Z, C.POINTER(C.c_int64)],
+    "sl_peak_probe_stream": [_P, _P, _P, _Z, _P, _Z],
     "sl_profile_begin": [_P, _I],
     "sl_profile_end": [_P, C.POINTER(C.c_float), C.POINTER(_I)],
     "sl_lock_test": [_P, _P, _I, _P, _I, _I, _P, _P, _P, _P, _P, _I, _P, _I, _I, _I, _I, _I, _I, _P, _P, _P, _P],
@@ -310,6 +312,24 @@ def sl_linear_clock_probe(x, packed, m_dev, m_upper, n, k, y_bf16, counters, row
     """counters: 8 x int64 on the device (see the header for their meaning)."""
     _check("sl_linear_clock_probe", lib().sl_linear_clock_probe(_stream(), _ptr(x), int(x_tiled), _ptr(packed), _ptr(m_dev),
                                                                 m_upper, n, k, _ptr(y_bf16), _ptr(row_map), _ptr(counters)))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def sl_peak_probe_mfma(operands, iters, waves_per_simd, sink):
+    """Enqueues the bare MFMA loop; returns the floating-point operations of the launch."""
+    flops = C.c_int64()
+    _check("sl_peak_probe_mfma", lib().sl_peak_probe_mfma(_stream(), _ptr(operands), _nbytes(operands), int(iters),
+                                                          int(waves_per_simd), _ptr(sink), _nbytes(sink), C.byref(flops)))
+    return flops.value
+
+
+def sl_peak_probe_stream(src, dst, sink):
+    """Enqueues one streaming pass over src (dst None: read only; else copy)."""
+    _check("sl_peak_probe_stream", lib().sl_peak_probe_stream(_stream(), _ptr(src), _ptr(dst), _nbytes(src), _ptr(sink),
+                                                              _nbytes(sink)))
 
 
 def tile_activations(x):

@@ -87,3 +87,11 @@ def test_controller_entry_points_reject_null_and_bad_sizes():
     assert lib.sl_lock_rule(None, 256, 256, 256, 256, 4, 256, None, 1, 64, 0, 256) == B.SL_EINVAL
     assert lib.sl_lock_test(None, 256, 1, 256, 1, 1024, 256, 256, 256, 256, None, 4, 256, 1, 64, 0, 0, 64, 1,
                             256, 256, 256, 256) == B.SL_EINVAL
+    fl = C.c_int64()
+    assert lib.sl_peak_probe_mfma(None, 256, 8192, 0, 1, 256, 1 << 20, C.byref(fl)) == B.SL_EINVAL      # iters
+    assert lib.sl_peak_probe_mfma(None, 256, 8192, 8, 3, 256, 1 << 20, C.byref(fl)) == B.SL_EINVAL      # waves per SIMD
+    assert lib.sl_peak_probe_mfma(None, 256, 8192, 8, 1, 256, 1 << 20, None) == B.SL_EINVAL
+    assert lib.sl_peak_probe_mfma(None, 256, 4096, 8, 1, 256, 1 << 20, C.byref(fl)) == B.SL_ENOSPC      # operands
+    assert lib.sl_peak_probe_stream(None, 256, None, 40, 256, 1 << 21) == B.SL_EINVAL                   # bytes % 16
+    assert lib.sl_peak_probe_stream(None, 256, 512, 1024, 256, 1 << 21) == B.SL_EINVAL                  # overlap
+    assert lib.sl_peak_probe_stream(None, 264, None, 1024, 256, 1 << 21) == B.SL_EINVAL                 # alignment
