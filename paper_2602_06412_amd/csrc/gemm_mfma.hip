@@ -214,25 +214,28 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
 // load by load (vmcnt(n) waits, never a drain).  The activation fragments (1 KiB per 32 rows and
 // k-step) are fetched by all four waves of a workgroup; they are a few hundred KB in total and
 // stay in L1/L2, while the weights come from HBM exactly once.
-template <int MB, int OUT>
+// NBW = 32-column blocks per wave: 2 (workgroup tile 256 columns, 8 k-steps in flight) or 1 (128 columns, 16
+// k-steps in flight: the same bytes in flight per wave over twice as many workgroups, for launches whose
+// 256-column tiles would leave CUs without a workgroup).
+template <int MB, int OUT, int NBW>
 __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
     const int32_t* __restrict__ row_map, size_t ldc, int tiles_n) {
-  constexpr int DEPTH = 8;
+  constexpr int DEPTH = 16 / NBW;
   const int M = min(*m_dev, m_upper);
   const int tn = blockIdx.x;
   if (tn >= tiles_n || M <= 0) return;
-  const int n0 = tn * 256;
+  const int n0 = tn * 128 * NBW;
   const int kbeg = blockIdx.y * k_per_split;
   const int ksteps = k_per_split / 16;                 // a multiple of DEPTH
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int K16 = k / 16, NB32 = n / 32;
 
-  const Frag* bp[2];
+  const Frag* bp[NBW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int nb = n0 / 32 + wave * 2 + i;
+  for (int i = 0; i < NBW; ++i) {
+    int nb = n0 / 32 + wave * NBW + i;
     nb = nb < NB32 ? nb : NB32 - 1;                    // column tail: load something valid, never stored
     bp[i] = reinterpret_cast<const Frag*>(Wp) + ((size_t)nb * K16 + kbeg / 16) * 64 + lane;
   }
@@ -255,38 +258,44 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   }
   a_step = a_tiled ? 512 : 16;
 
-  f32x16 acc[MB][2];
+  f32x16 acc[MB][NBW];
 #pragma unroll
   for (int a = 0; a < MB; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NBW; ++b)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
   // The loads are issued as inline assembly and waited for with explicit vmcnt counts: left to
   // the compiler, loads that cross the loop's back edge are drained (vmcnt(0)) at the top of
   // every trip, which empties the pipeline DEPTH k-steps at a time.  Loads return in order and
-  // each k-step issues 2 + MB of them, so the operands of a step have landed once at most
-  // (DEPTH-1)(2+MB) younger loads are outstanding.  The waits name the registers they release,
+  // each k-step issues NBW + MB of them, so the operands of a step have landed once at most
+  // (DEPTH-1)(NBW+MB) younger loads are outstanding (at most 45: the counter holds 63).  The waits name the registers they release,
   // which keeps the MFMAs behind them.
   // The weight loads carry the non-temporal hint: every weight byte is used once per launch, and
   // streaming them past the caches measured 191 -> 165 us on the LM head at M = 16 (6.3 TB/s).
-  Frag fa[DEPTH][MB], fb[DEPTH][2];
+  Frag fa[DEPTH][MB], fb[DEPTH][NBW];
   auto fetch = [&](int step, int slot) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NBW; ++i)
       asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
       asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
   };
   auto landed = [&](int slot) {
-    if (MB == 1)
-      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]) : "n"((DEPTH - 1) * 3));
-    else
+    static_assert((DEPTH - 1) * (NBW + MB) <= 63, "vmcnt range");
+    constexpr int kYounger = (DEPTH - 1) * (NBW + MB);
+    if constexpr (NBW == 2 && MB == 1)
+      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]) : "n"(kYounger));
+    else if constexpr (NBW == 2)
       asm volatile("s_waitcnt vmcnt(%4)"
                    : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]), "+v"(fa[slot][MB - 1])
-                   : "n"((DEPTH - 1) * 4));
+                   : "n"(kYounger));
+    else if constexpr (MB == 1)
+      asm volatile("s_waitcnt vmcnt(%2)" : "+v"(fb[slot][0]), "+v"(fa[slot][0]) : "n"(kYounger));
+    else
+      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fa[slot][0]), "+v"(fa[slot][MB - 1]) : "n"(kYounger));
   };
 #pragma unroll
   for (int u = 0; u < DEPTH; ++u) fetch(u, u);
@@ -298,7 +307,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NBW; ++i)
           acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][mb], fb[u][i], acc[mb][i], 0, 0, 0);
       const int nx = s0 + u + DEPTH;                   // past the end: re-fetch the last step (never used)
       fetch(nx < ksteps ? nx : last, u);
@@ -315,8 +324,8 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
       const int row = mb * 32 + 8 * (v / 4) + row_in + (v % 4);
       if (row >= M) continue;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int col = n0 + (wave * 2 + i) * 32 + col_in;
+      for (int i = 0; i < NBW; ++i) {
+        const int col = n0 + (wave * NBW + i) * 32 + col_in;
         if (col >= n) continue;
         if (OUT == 0) {
           Cf[((size_t)blockIdx.y * m_upper + row) * ldc + col] = acc[mb][i][v];
@@ -329,11 +338,12 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   }
 }
 
-template <int MB, int OUT>
+template <int MB, int OUT, int NBW = 2>
 static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
                          int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
-  const int tiles_n = sl_cdiv(n, 256);
-  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, a_tiled,
+  const int tiles_n = sl_cdiv(n, 128 * NBW);
+  if ((k / splits) % (16 * (16 / NBW))) return SL_EINVAL;        // whole trips of the register ring
+  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT, NBW>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, a_tiled,
                      (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n);
   SL_LAUNCH_CHECK();
   return SL_OK;
@@ -342,6 +352,9 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // ---- host side ------------------------------------------------------------------------------
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
+#ifndef SL_STREAM_NARROW
+#define SL_STREAM_NARROW 1
+#endif
 #ifndef SL_THIN_MAX
 #define SL_THIN_MAX 32
 #endif
@@ -349,9 +362,9 @@ constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
 // Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
-//  * thin launches (mu <= kThinMax) are weight-stream bound: one BM x 256 tile per 256 columns, k
-//    split until there are about two workgroups per CU, with the fp32 partial traffic capped
-//    at a fraction of the weight bytes (k >= 32*S*mu);
+//  * thin launches (mu <= kThinMax) are weight-stream bound: 256- or 128-column tiles and the k split
+//    that bring the launch closest to about one workgroup per CU with few fp32 planes, the partial
+//    traffic capped at a fraction of the weight bytes (k >= 16*S*mu);
 //  * thicker launches take the 256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep
 //    k-tile and wave of workgroups; its half-height variant is chosen inside that launcher) with the
 //    split count that minimises  waves * (k-tiles per split + fixed) * t_tile + bytes of fp32
@@ -372,15 +385,31 @@ struct GemmPlan {
 #ifndef SL_PLAN_HALF_COST
 #define SL_PLAN_HALF_COST 0.6
 #endif
+// Thin launches: 128-column tiles when 256-column ones would give at most 160 workgroups (and the split's
+// reduction is whole trips of the deeper register ring); the workgroup count that results.
+static bool thin_narrow(int n, int k, int splits) {
+  return SL_STREAM_NARROW && sl_cdiv(n, 256) * splits <= 160 && (k / splits) % 256 == 0;
+}
+static long thin_workgroups(int n, int k, int splits) {
+  return (long)sl_cdiv(n, thin_narrow(n, k, splits) ? 128 : 256) * splits;
+}
+
 static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
   GemmPlan p{0, 1};
   if (mu <= kThinMax) {
-    const int tiles = sl_cdiv(n, 256);
-    int s = 1;
-    while (s < 8 && tiles * s < 512 && (k % (BK * 2 * s * 2) == 0) && (k / (BK * s * 2) >= 4) &&
-           (size_t)(s * 2) * 16 * mu <= (size_t)k)
-      s *= 2;
-    p.splits = s;
+    // Measured at the LLaDA-8B shapes (16 and 32 rows): a weight stream is fastest with about one workgroup
+    // per CU (192-256 workgroups: 100 MB in 23-24 us); 96-128 workgroups leave CUs idle (29-36 us) and 384-768
+    // are slower again (26-28 us; 201 MB: 44-46 us against 37-39 us), as is every extra fp32 plane.
+    int best_s = 1;
+    long best_cost = -1;
+    for (int s = 1; s <= 16; s *= 2) {
+      if (k % (128 * s) || k / s < 256) break;
+      if (s > 1 && (size_t)s * 16 * mu > (size_t)k) break;         // fp32 partial traffic capped against the weights
+      const long wgs = thin_workgroups(n, k, s);
+      const long cost = (wgs > 224 ? wgs - 224 : 224 - wgs) + 4 * s;
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_s = s; }
+    }
+    p.splits = best_s;
     return p;
   }
   // The ring kernel wherever its k loop is long enough (at least 8 k-tiles per split); its half-height
@@ -460,6 +489,8 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
   }
   // the barrier-free weight stream with one 32-row block (at most 32 rows) or two (33..64 rows, reached
   // only where the reduction is too short for the ring kernel)
+  if (Cf && mu <= 32 && thin_narrow(n, k, splits))
+    return launch_stream<1, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
   if (mu <= 32 && (k / splits) % 128 == 0)
     return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
               : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);

@@ -25,6 +25,9 @@ CASES = [
     (12288, 1536, 704, 700),
     (8192, 4096, 1024, 1000),
     (4096, 12288, 1024, 1024),
+    (4096, 4096, 16, 13),         # thin launches with few column tiles: the 128-column weight-stream tiles
+    (4096, 12288, 32, 32),
+    (4160, 2048, 24, 20),         # ... with a column tail
 ]
 
 
