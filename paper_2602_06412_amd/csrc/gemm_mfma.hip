@@ -352,8 +352,12 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // ---- host side ------------------------------------------------------------------------------
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
+// The 128-column form of the weight-stream kernel is compiled but switched off: one run of the whole GPU test
+// suite returned non-finite partial sums from it for a 16-row, n = k = 4096 launch that passed in every other
+// run (alone, 80 repetitions, and in a second whole-suite run), and no cause was found by reading the kernel.
+// Until one is shown the plan uses 256-column tiles only, which reach the same workgroup counts with more k-splits.
 #ifndef SL_STREAM_NARROW
-#define SL_STREAM_NARROW 1
+#define SL_STREAM_NARROW 0
 #endif
 #ifndef SL_THIN_MAX
 #define SL_THIN_MAX 32
@@ -362,9 +366,9 @@ constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
 // Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
-//  * thin launches (mu <= kThinMax) are weight-stream bound: 256- or 128-column tiles and the k split
-//    that bring the launch closest to about one workgroup per CU with few fp32 planes, the partial
-//    traffic capped at a fraction of the weight bytes (k >= 16*S*mu);
+//  * thin launches (mu <= kThinMax) are weight-stream bound: the k split (and, where enabled, the
+//    128-column tile form) that brings the launch closest to about one workgroup per CU with few
+//    fp32 planes, the partial traffic capped at a fraction of the weight bytes (k >= 16*S*mu);
 //  * thicker launches take the 256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep
 //    k-tile and wave of workgroups; its half-height variant is chosen inside that launcher) with the
 //    split count that minimises  waves * (k-tiles per split + fixed) * t_tile + bytes of fp32
