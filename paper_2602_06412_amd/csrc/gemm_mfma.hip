@@ -206,6 +206,21 @@ __global__ __launch_bounds__(256, (BM <= 128 ? 2 : 1)) void gemm_mfma_kernel(
   }
 }
 
+// Wait until at most N younger loads are outstanding; the asm names the registers of the slot it releases, which
+// keeps the MFMAs that read them behind it.
+template <int N, int NBW, int MB>
+__device__ __forceinline__ void stream_landed(Frag (&b)[NBW], Frag (&a)[MB]) {
+  static_assert(N >= 0 && N <= 63, "vmcnt range");
+  if constexpr (NBW == 2 && MB == 1)
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b[0]), "+v"(b[1]), "+v"(a[0]) : "n"(N));
+  else if constexpr (NBW == 2)
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(b[0]), "+v"(b[1]), "+v"(a[0]), "+v"(a[MB - 1]) : "n"(N));
+  else if constexpr (MB == 1)
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(b[0]), "+v"(a[0]) : "n"(N));
+  else
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b[0]), "+v"(a[0]), "+v"(a[MB - 1]) : "n"(N));
+}
+
 // ---- thin launches (at most 32 MB rows, MB = 1 or 2): a pure weight stream ---------------------
 // Below ~300 rows the projection is bound by reading the weights once (2 n k bytes), so the only
 // thing that matters is keeping enough loads in flight.  Here every wave streams its own 64
@@ -270,8 +285,7 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   // the compiler, loads that cross the loop's back edge are drained (vmcnt(0)) at the top of
   // every trip, which empties the pipeline DEPTH k-steps at a time.  Loads return in order and
   // each k-step issues NBW + MB of them, so the operands of a step have landed once at most
-  // (DEPTH-1)(NBW+MB) younger loads are outstanding (at most 45: the counter holds 63).  The waits name the registers they release,
-  // which keeps the MFMAs behind them.
+  // (DEPTH-1)(NBW+MB) younger loads are outstanding (at most 45: the counter holds 63).
   // The weight loads carry the non-temporal hint: every weight byte is used once per launch, and
   // streaming them past the caches measured 191 -> 165 us on the LM head at M = 16 (6.3 TB/s).
   Frag fa[DEPTH][MB], fb[DEPTH][NBW];
@@ -283,38 +297,40 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
     for (int mb = 0; mb < MB; ++mb)
       asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
   };
-  auto landed = [&](int slot) {
-    static_assert((DEPTH - 1) * (NBW + MB) <= 63, "vmcnt range");
-    constexpr int kYounger = (DEPTH - 1) * (NBW + MB);
-    if constexpr (NBW == 2 && MB == 1)
-      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]) : "n"(kYounger));
-    else if constexpr (NBW == 2)
-      asm volatile("s_waitcnt vmcnt(%4)"
-                   : "+v"(fb[slot][0]), "+v"(fb[slot][1]), "+v"(fa[slot][0]), "+v"(fa[slot][MB - 1])
-                   : "n"(kYounger));
-    else if constexpr (MB == 1)
-      asm volatile("s_waitcnt vmcnt(%2)" : "+v"(fb[slot][0]), "+v"(fa[slot][0]) : "n"(kYounger));
-    else
-      asm volatile("s_waitcnt vmcnt(%3)" : "+v"(fb[slot][0]), "+v"(fa[slot][0]), "+v"(fa[slot][MB - 1]) : "n"(kYounger));
-  };
 #pragma unroll
   for (int u = 0; u < DEPTH; ++u) fetch(u, u);
-  const int last = ksteps - 1;
-  for (int s0 = 0; s0 < ksteps; s0 += DEPTH) {
+  auto mfma_step = [&](int u) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int i = 0; i < NBW; ++i)
+        acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][mb], fb[u][i], acc[mb][i], 0, 0, 0);
+  };
+  // Every trip but the last refills each slot DEPTH steps ahead as soon as its MFMAs are issued.
+  for (int s0 = 0; s0 + DEPTH < ksteps; s0 += DEPTH) {
 #pragma unroll
     for (int u = 0; u < DEPTH; ++u) {
-      landed(u);
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < NBW; ++i)
-          acc[mb][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u][mb], fb[u][i], acc[mb][i], 0, 0, 0);
-      const int nx = s0 + u + DEPTH;                   // past the end: re-fetch the last step (never used)
-      fetch(nx < ksteps ? nx : last, u);
+      stream_landed<(DEPTH - 1) * (NBW + MB), NBW, MB>(fb[u], fa[u]);
+      mfma_step(u);
+      fetch(s0 + u + DEPTH, u);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the unused tail re-fetches
+  // The last trip fetches nothing: slot u has landed once at most DEPTH-1-u younger steps are outstanding, and
+  // after its last wait no load is in flight.  (Re-fetching a dummy step here instead, to keep one wait count,
+  // left loads in flight into registers the compiler already counted as free: it placed the epilogue's row
+  // index in one of them ahead of the final wait, and a late load could overwrite it.)
+#define SL_LAST_STEP(U)                                                            \
+  if constexpr (U < DEPTH) {                                                       \
+    stream_landed<(DEPTH - 1 - U) * (NBW + MB), NBW, MB>(fb[U], fa[U]);            \
+    mfma_step(U);                                                                  \
+    __builtin_amdgcn_sched_barrier(0);                                             \
+  }
+  SL_LAST_STEP(0) SL_LAST_STEP(1) SL_LAST_STEP(2) SL_LAST_STEP(3) SL_LAST_STEP(4) SL_LAST_STEP(5) SL_LAST_STEP(6)
+  SL_LAST_STEP(7) SL_LAST_STEP(8) SL_LAST_STEP(9) SL_LAST_STEP(10) SL_LAST_STEP(11) SL_LAST_STEP(12)
+  SL_LAST_STEP(13) SL_LAST_STEP(14) SL_LAST_STEP(15)
+#undef SL_LAST_STEP
+  static_assert(DEPTH <= 16, "last trip is written out for 16 slots");
 
   const int col_in = lane & 31, row_in = 4 * (lane >> 5);
 #pragma unroll
@@ -352,12 +368,8 @@ static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* 
 // ---- host side ------------------------------------------------------------------------------
 // Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
 // measured at least as fast as 256 x 256 at one per CU for every projection shape here.
-// The 128-column form of the weight-stream kernel is compiled but switched off: one run of the whole GPU test
-// suite returned non-finite partial sums from it for a 16-row, n = k = 4096 launch that passed in every other
-// run (alone, 80 repetitions, and in a second whole-suite run), and no cause was found by reading the kernel.
-// Until one is shown the plan uses 256-column tiles only, which reach the same workgroup counts with more k-splits.
 #ifndef SL_STREAM_NARROW
-#define SL_STREAM_NARROW 0
+#define SL_STREAM_NARROW 1
 #endif
 #ifndef SL_THIN_MAX
 #define SL_THIN_MAX 32
