@@ -27,7 +27,7 @@ HBM_PEAK = 8.0e12            # B/s
 # HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
 # WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
 # the copy-kernel calibration given there), keyed by M.
-LM_HEAD_TRAFFIC_BYTES = {1024: 1848871289, 16: 1044102269}
+LM_HEAD_TRAFFIC_BYTES = {1024: 1851893935, 16: 1042204494}
 
 
 def lm_head_clock_probe(B, torch, w_lm, M, V, d, seed, launches=12):
