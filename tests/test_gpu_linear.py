@@ -135,3 +135,37 @@ def test_clock_probe_matches_plain_launch_and_reports_sane_counters():
     assert 500.0 < mhz < 3000.0
     with pytest.raises(B.SureLockError):
         B.sl_linear_clock_probe(x, packed, m_dev, 64, n, k, y1, counters)     # thin launches have no probe
+
+
+@pytest.mark.parametrize("n,k,m_upper", [(4096, 4096, 16), (4096, 12288, 32), (12288, 4096, 16)])
+def test_thin_launch_repeats_bitwise_under_memory_traffic(n, k, m_upper):
+    """The weight-stream kernel keeps loads in flight in a register ring with hand-counted waits.  Its result
+    must not depend on when those loads land: repeat the launch while a second stream keeps HBM busy and
+    compare every repetition bit for bit with the first (every partial written, none left at the NaN fill)."""
+    w, x = _inputs(3 * n + k, n, k, m_upper)
+    wd = w.to(DEV)
+    packed = torch.empty_like(wd)
+    B.sl_linear_pack(wd, packed)
+    xin = B.tile_activations(x.to(DEV))
+    S = B.sl_linear_splits(m_upper, n, k)
+    m_dev = torch.tensor([m_upper], dtype=torch.int32, device=DEV)
+    src = torch.empty(1 << 26, dtype=torch.float32, device=DEV).normal_()
+    dst = torch.empty_like(src)
+    side = torch.cuda.Stream()
+    first = None
+    for rep in range(24):
+        y = torch.full((S, m_upper, n), float("nan"), device=DEV)
+        torch.cuda.synchronize()
+        if rep % 3:
+            with torch.cuda.stream(side):
+                for _ in range(rep % 3):
+                    dst.copy_(src)
+        B.sl_linear_forward(xin, packed, m_dev, m_upper, n, k, S, y_f32=y, x_tiled=1)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(y).all()), f"repetition {rep}: partials left unwritten or non-finite"
+        if first is None:
+            first = y
+            ref = x.double().numpy() @ w.double().numpy().T
+            assert np.all(np.abs(y.double().sum(0).cpu().numpy() - ref) <= _bound(x.double().numpy(), w.double().numpy(), k))
+        else:
+            assert torch.equal(y, first), f"repetition {rep} differs from the first"
