@@ -151,7 +151,13 @@ int sl_workspace_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *
  *                              positions with block_lo <= i < block_hi in each sequence
  *   m_upper            host    an upper bound on the number of active rows (B*N is
  *                              always valid); launches are sized by it, rows beyond
- *                              the true M exit early
+ *                              the true M exit early.  The bound is the caller's
+ *                              promise: if the true count exceeds it, only the first
+ *                              m_upper active rows (in active_idx order) are computed,
+ *                              scored, unmasked and tested, nothing is written past
+ *                              m_upper entries of the packed arrays, and cu_active
+ *                              still reports the true counts (cu_active[B] > m_upper
+ *                              tells the caller the step was incomplete)
  *   active_idx [>=m_upper] i32 out  flat ids of active rows, ascending
  *   cu_active  [B+1]   i32 out  exclusive prefix sums of per-sequence counts; [B] = M
  *   kl, conf [>=m_upper] f32 out  D_t and max_v p_t per active row (u = 1 - conf)

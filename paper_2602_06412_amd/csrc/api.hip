@@ -341,7 +341,7 @@ extern "C" int sl_compact_active(void* stream, const uint8_t* lock, int32_t batc
                                  int32_t* active_idx, int32_t* cu_active) {
   if (!lock || !active_idx || !cu_active || batch < 1 || n_seq < 1) return SL_EINVAL;
   if ((size_t)batch * n_seq > (size_t)1 << 30) return SL_EINVAL;
-  return slk_compact_active((hipStream_t)stream, lock, batch, n_seq, active_idx, cu_active);
+  return slk_compact_active((hipStream_t)stream, lock, batch, n_seq, batch * n_seq, active_idx, cu_active);
 }
 
 extern "C" int sl_score_posteriors(void* stream, const void* logits_cur, int32_t cur_packed, const void* logits_prev,
@@ -363,7 +363,7 @@ extern "C" int sl_unmask_topk(void* stream, int32_t* tokens, uint8_t* masked, co
   if (batch < 1 || n_seq < 1 || block_lo < 0 || block_hi > n_seq || block_lo > block_hi || k < 0) return SL_EINVAL;
   if ((size_t)(block_hi - block_lo) * 8 > 60 * 1024) return SL_EINVAL;
   return slk_unmask_topk((hipStream_t)stream, tokens, masked, active_idx, cu_active, conf, argmax, batch, n_seq,
-                         block_lo, block_hi, k);
+                         block_lo, block_hi, k, batch * n_seq);
 }
 
 extern "C" int sl_lock_rule(void* stream, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
@@ -502,7 +502,7 @@ static int step_impl(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked
                                                                 (size_t)c.vocab * ts, lock, compute_mask, B * N, t));
     rows_mask = compute_mask;
   }
-  SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, rows_mask, B, N, active_idx, cu_active));
+  SL_RUN(ctx, s, SL_PROF_COMPACT, slk_compact_active(s, rows_mask, B, N, m_upper, active_idx, cu_active));
   // block input of the active rows + first LN
   SL_RUN(ctx, s, SL_PROF_EMBED_NORM, slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, active_idx, m_dev, m_upper, c.d_model, c.vocab,
                            ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
@@ -542,7 +542,7 @@ static int step_impl(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked
                                                      block_lo, block_hi, c.temperature, c.seed, t, argmax, drawn, parts));
     write_id = drawn;
   }
-  SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, write_id, B, N, block_lo, block_hi, k));
+  SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, write_id, B, N, block_lo, block_hi, k, m_upper));
   if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;
 }
@@ -585,7 +585,7 @@ extern "C" int sl_unlock_probe(sl_ctx* ctx, void* stream, const int32_t* tokens,
   const sl_config& c = ctx->cfg;
   const int32_t* m_dev = cu_probe + B;
   // L_t, the rows the probe visits
-  SL_TRY(slk_compact_active(s, lock, B, N, probe_idx, cu_probe, 1));
+  SL_TRY(slk_compact_active(s, lock, B, N, m_upper, probe_idx, cu_probe, 1));
   SL_TRY(slk_embed_rmsnorm(s, c.dtype, ctx->plain.emb, tokens, probe_idx, m_dev, m_upper, c.d_model, c.vocab,
                            ctx->layers[0].attn_norm, c.rms_eps, ws.x, ws.h, ctx->use_mfma));
   // queries only: keys and values of every slot come from the cache, nothing is written

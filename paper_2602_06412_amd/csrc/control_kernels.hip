@@ -7,8 +7,11 @@
 // One 1024-thread block walks the mask in chunks of 1024: wave ballot + popcount gives
 // the rank inside a wave, an LDS scan over the 16 wave totals gives the rank inside the
 // chunk, a running base carries across chunks.  cu_active[b] is the rank of flat id b*N.
+// active_idx holds `cap` entries: ranks beyond it are counted (cu_active stays the true prefix sums, so the
+// caller can see the overflow) but not stored.
 __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __restrict__ lock, int B, int N,
-                                                              int select_locked, int32_t* __restrict__ active_idx,
+                                                              int select_locked, int cap,
+                                                              int32_t* __restrict__ active_idx,
                                                               int32_t* __restrict__ cu_active) {
   __shared__ int wave_tot[16];
   __shared__ int base_sh;
@@ -33,7 +36,7 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __r
     const int base = base_sh;
     const int rank = base + before + in_wave;
     if (g < total) {
-      if (act) active_idx[rank] = g;
+      if (act && rank < cap) active_idx[rank] = g;
       if (g % N == 0) cu_active[g / N] = rank;
     }
     __syncthreads();
@@ -44,9 +47,10 @@ __global__ __launch_bounds__(1024) void compact_active_kernel(const uint8_t* __r
 }
 
 // select_locked = 0: the unlocked positions (A_t); 1: the locked ones (L_t, the rows the unlock probe visits)
-int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active,
-                       int select_locked) {
-  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, s, lock, B, N, select_locked, active_idx, cu_active);
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int cap, int32_t* active_idx,
+                       int32_t* cu_active, int select_locked) {
+  hipLaunchKernelGGL(compact_active_kernel, dim3(1), dim3(1024), 0, s, lock, B, N, select_locked, cap, active_idx,
+                     cu_active);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
@@ -63,7 +67,7 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
                                                           const int32_t* __restrict__ cu_active,
                                                           const float* __restrict__ conf,
                                                           const int32_t* __restrict__ argmax, int N, int lo, int hi,
-                                                          int k) {
+                                                          int k, int m_upper) {
   extern __shared__ unsigned long long keys[];     // [hi - lo]
   __shared__ int count;
   __shared__ int hist[256];
@@ -71,7 +75,8 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
   __shared__ int want_sh, done_sh;
   __shared__ int wave_tot[4];
   const int b = blockIdx.x, tid = threadIdx.x;
-  const int r0 = cu_active[b], r1 = cu_active[b + 1];
+  // packed arrays hold m_upper rows: rows beyond the caller's bound do not exist
+  const int r0 = min(cu_active[b], m_upper), r1 = min(cu_active[b + 1], m_upper);
   if (tid == 0) count = 0;
   __syncthreads();
   for (int r = r0 + tid; r < r1; r += 256) {
@@ -139,11 +144,11 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
 
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
                     const int32_t* cu_active, const float* conf, const int32_t* argmax, int B, int N, int lo, int hi,
-                    int k) {
-  if (hi <= lo || k <= 0) return SL_OK;
+                    int k, int m_upper) {
+  if (hi <= lo || k <= 0 || m_upper <= 0) return SL_OK;
   const size_t sh = (size_t)(hi - lo) * 8;
   hipLaunchKernelGGL(unmask_topk_kernel, dim3(B), dim3(256), sh, s, tokens, masked, active_idx, cu_active, conf,
-                     argmax, N, lo, hi, k);
+                     argmax, N, lo, hi, k, m_upper);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

@@ -164,8 +164,8 @@ struct sl_ctx {
 int slk_lock_rule_gated(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                         const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
                         float gate_m, int B, int N, int first_step, uint8_t* new_lock);
-int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int32_t* active_idx, int32_t* cu_active,
-                       int select_locked = 0);
+int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int cap, int32_t* active_idx,
+                       int32_t* cu_active, int select_locked = 0);
 int slk_lock_rule_relock(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                          const int32_t* cu_active, int m_upper, const float* kl, const float* conf, const float* eps,
                          float gate_m, const uint8_t* relocked, const int32_t* cool_until, float rho, int t, int B,
@@ -190,7 +190,7 @@ int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row
                         const int32_t* m_dev, int m_upper, const int32_t* t_lock, const uint8_t* unlocked, int t);
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
                     const int32_t* cu_active, const float* conf, const int32_t* argmax,
-                    int B, int N, int lo, int hi, int k);
+                    int B, int N, int lo, int hi, int k, int m_upper);
 int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                   const int32_t* m_dev, int m_upper, const float* kl, const float* eps, int B, int N,
                   int first_step, uint8_t* new_lock);

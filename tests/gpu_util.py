@@ -35,14 +35,21 @@ def bf16_ulp(x):
 
 def logits_tol(z_oracle, storage):
     """Per-element tolerance on logits.
-    bf16: the nominal 2e-2 plus one bf16 spacing at |z|: oracle and GPU keep the same bf16
-    rounding points but accumulate in fp64 / fp32, so a value that sits on a rounding boundary
-    can land on the neighbouring bf16 number on either side (spacing 0.0156 on [2,4), 0.031 on
-    [4,8)); everything else must stay within 2e-2.
+    bf16: max(2e-2, one bf16 spacing at |z|).  2e-2 is the stated bound; the spacing term only matters
+    where a single bf16 step is larger than it (0.031 on [4,8), 0.0625 on [8,16)): oracle and GPU keep
+    the same bf16 rounding points but accumulate in fp64 / fp32, so a sum that sits on a rounding
+    boundary can land on the neighbouring bf16 number, and no implementation that stores bf16 logits
+    can do better than one spacing there.
     fp32: 2e-4 absolute (fp32 accumulation over <= 4096-term dot products)."""
     if storage == "bf16":
-        return 2e-2 + bf16_ulp(z_oracle)
+        return np.maximum(2e-2, bf16_ulp(z_oracle))
     return np.full_like(z_oracle, 2e-4)
+
+
+# Largest fraction of bf16 logits allowed beyond 2e-2 (they must all be one-spacing flips at |z| >= 4,
+# which logits_tol admits): with N(0, 0.02^2) weights |z| >= 4 is a 3-sigma event and a flip needs the
+# sum within ~1e-3 of a boundary, so the measured fraction is 0 to a few 1e-6.
+MAX_FRAC_BEYOND_NOMINAL = 1e-4
 
 
 def check_logits(z_gpu, z_oracle, storage, what=""):
@@ -50,10 +57,12 @@ def check_logits(z_gpu, z_oracle, storage, what=""):
     tol = logits_tol(z_oracle, storage)
     ratio = err / tol
     w = int(ratio.argmax())
+    beyond = float(np.mean(err > 2e-2)) if storage == "bf16" else 0.0
     assert np.all(err <= tol), (f"{what}: {int((err > tol).sum())} of {err.size} logits out of tolerance; worst: err "
                                 f"{err.flat[w]:.4g} vs tol {tol.flat[w]:.4g} at z={z_oracle.flat[w]:.4g}; "
-                                f"mean err {err.mean():.3g}, frac > 2e-2: {np.mean(err > 2e-2):.2e}")
-    print(f"{what}: logits max err {err.max():.4g}, mean {err.mean():.3g}, frac > 2e-2: {np.mean(err > 2e-2):.2e}", flush=True)
+                                f"mean err {err.mean():.3g}, frac > 2e-2: {beyond:.2e}")
+    assert beyond <= MAX_FRAC_BEYOND_NOMINAL, f"{what}: fraction of logits beyond 2e-2 is {beyond:.2e}"
+    print(f"{what}: logits max err {err.max():.4g}, mean {err.mean():.3g}, frac > 2e-2: {beyond:.2e}", flush=True)
     return err
 
 

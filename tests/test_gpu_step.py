@@ -315,3 +315,46 @@ def test_out_of_range_token_ids_are_clamped():
         assert torch.equal(z_ok, sess.logits_view(1))
     finally:
         sess.close()
+
+
+def test_m_upper_too_small_is_contained():
+    """A bound below the true number of active rows: the first m_upper active rows are processed exactly
+    as in a step with a valid bound, nothing is written past m_upper entries of the packed arrays, no
+    position beyond them is unmasked or locked, and cu_active reports the true counts."""
+    shape = wl.C1
+    w = weights_to_device(wl.make_weights(shape, seed=1))
+    Bn, N, mu = 2, 64, 40
+    sess = B.Session(shape, w, Bn, N)
+    try:
+        lock = np.zeros((Bn, N), dtype=np.uint8); lock[0, ::4] = 1; lock[1, 1::3] = 1
+        true_M = int((lock == 0).sum())
+        assert true_M > mu
+        tok0 = np.stack([wl.prompt_uniform(3 + b, N, shape.vocab, shape.mask_id) for b in range(Bn)])
+        masked0 = (1 - lock).astype(np.uint8)                 # every active slot can be unmasked
+        eps_d = dev(np.array([1e30, 1e30], dtype=np.float32))   # every unmasked active row would lock at t = 2
+        out = {}
+        for name, bound in (("ok", Bn * N), ("small", mu)):
+            tokens, masked = dev(tok0.reshape(-1), torch.int32), dev(masked0.reshape(-1))
+            for t in (1, 2):
+                for buf in (sess.active_idx, sess.argmax):
+                    buf.fill_(-7)
+                sess.kl.fill_(-7.0); sess.conf.fill_(-7.0)
+                new_lock = torch.full((Bn * N,), 9, dtype=torch.uint8, device=DEV)
+                sess.step(tokens, masked, dev(lock.reshape(-1)), eps_d, t, 0, N, 5 if t == 2 else 0, m_upper=bound,
+                          new_lock=new_lock)
+            torch.cuda.synchronize()
+            out[name] = [x.cpu().numpy().copy() for x in (sess.active_idx, sess.cu_active, sess.kl, sess.conf, sess.argmax,
+                                                          tokens, masked, new_lock)]
+        idx_ok, cu_ok, kl_ok, conf_ok, am_ok, tok_ok, msk_ok, lock_ok = out["ok"]
+        idx, cu, kl, conf, am, tok, msk, nl = out["small"]
+        assert np.array_equal(cu, cu_ok) and cu[-1] == true_M
+        assert np.array_equal(idx[:mu], idx_ok[:mu]) and np.all(idx[mu:] == -7)
+        assert np.all(am[mu:] == -7) and np.all(kl[mu:] == -7.0) and np.all(conf[mu:] == -7.0)
+        assert np.array_equal(am[:mu], am_ok[:mu])
+        beyond = idx_ok[mu:true_M]                            # flat ids of the active rows the bound cut off
+        assert np.array_equal(tok[beyond], tok0.reshape(-1)[beyond]) and np.all(msk[beyond] == 1)
+        assert np.all(nl[beyond] != 1)                        # never locked (left as the caller's buffer held them)
+        changed = np.flatnonzero(msk != masked0.reshape(-1))
+        assert len(changed) > 0 and set(changed) <= set(idx_ok[:mu].tolist())
+    finally:
+        sess.close()
