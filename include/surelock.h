@@ -239,6 +239,21 @@ int sl_sample_tokens(void *stream, const void *logits_cur, int32_t cur_packed, i
                      float temperature, uint64_t seed, int32_t t, const int32_t *argmax, int32_t *write_id,
                      void *scratch, size_t scratch_bytes);
 
+/* sl_sample_tokens for callers that cannot allocate device memory or bring a scratch buffer: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical write_id; the per-part candidates go to a buffer that is part of the
+ * library's device code (1 MiB, held by every GPU the library runs on until the process ends) instead
+ * of a caller's scratch.  Calls no allocating routine.  m_upper <= 16384, otherwise SL_ENOSPC (nothing
+ * is launched).  All calls on one GPU share that buffer: nothing in it has to start at zero (every
+ * entry that is read is written earlier in the same call), but two calls whose kernels overlap on
+ * one GPU (different streams) race on it; calls on one stream are ordered and safe.  The first call
+ * on a device looks the buffer's address up (hipGetSymbolAddress, no allocation) with that device
+ * current; SL_EHIP if that fails. */
+int sl_sample_tokens_noalloc(void *stream, const void *logits_cur, int32_t cur_packed, int32_t dtype, int32_t vocab,
+                             const int32_t *active_idx, const int32_t *m_dev, int32_t m_upper,
+                             const uint8_t *masked, int32_t n_seq, int32_t block_lo, int32_t block_hi,
+                             float temperature, uint64_t seed, int32_t t, const int32_t *argmax, int32_t *write_id);
+
 /* Candidates Z_t = active and unmasked; F_t = {i in Z_t : D_i <= eps_b}; new_lock =
  * lock | F_t (gate disabled).  first_step != 0 locks nothing. */
 int sl_lock_rule(void *stream, const uint8_t *lock, const uint8_t *masked,

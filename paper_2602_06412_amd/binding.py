@@ -56,6 +56,7 @@ _SIGS = {
     "sl_lock_rule_gated": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _I, _I, _I, _P],
     "sl_select_rows": [_P, _P, _P, _P, _I, _I, _I, _I, C.c_float, _P],
     "sl_sample_tokens": [_P, _P, _I, _I, _I, _P, _P, _I, _P, _I, _I, _I, C.c_float, C.c_uint64, _I, _P, _P, _P, _Z],
+    "sl_sample_tokens_noalloc": [_P, _P, _I, _I, _I, _P, _P, _I, _P, _I, _I, _I, C.c_float, C.c_uint64, _I, _P, _P],
     "sl_lock_rule_relock": [_P, _P, _P, _P, _P, _I, _P, _P, _P, C.c_float, _P, _P, C.c_float, _I, _I, _I, _P, _P],
     "sl_unlock_probe": [_P, _P, _P, _P, _P, _I, _P, _P, _P, _P, _P, _P, _P, _Z],
     "sl_unlock_rule": [_P, _P, _P, _P, _P, _P, _P, _P, _I, _P, _P, _P, _I, _P, C.c_float, C.c_float, _I, _I, _I, _P],
@@ -252,6 +253,13 @@ def sl_sample_tokens(logits_cur, cur_packed, dtype, vocab, active_idx, m_dev, m_
         _stream(), _ptr(logits_cur), int(cur_packed), dtype, vocab, _ptr(active_idx), _ptr(m_dev), m_upper, _ptr(masked),
         n_seq, block_lo, block_hi, C.c_float(temperature), C.c_uint64(seed), t, _ptr(argmax), _ptr(write_id),
         _ptr(scratch), scratch.numel()))
+
+
+def sl_sample_tokens_noalloc(logits_cur, cur_packed, dtype, vocab, active_idx, m_dev, m_upper, masked, n_seq, block_lo,
+                             block_hi, temperature, seed, t, argmax, write_id):
+    _check("sl_sample_tokens_noalloc", lib().sl_sample_tokens_noalloc(
+        _stream(), _ptr(logits_cur), int(cur_packed), dtype, vocab, _ptr(active_idx), _ptr(m_dev), m_upper, _ptr(masked),
+        n_seq, block_lo, block_hi, C.c_float(temperature), C.c_uint64(seed), t, _ptr(argmax), _ptr(write_id)))
 
 
 def sl_select_rows(lock, masked, d_last, batch, n_seq, block_lo, block_hi, select_fraction, compute_mask):

@@ -398,6 +398,21 @@ extern "C" int sl_sample_tokens(void* stream, const void* logits_cur, int32_t cu
                            n_seq, block_lo, block_hi, temperature, seed, t, argmax, write_id, scratch);
 }
 
+extern "C" int sl_sample_tokens_noalloc(void* stream, const void* logits_cur, int32_t cur_packed, int32_t dtype,
+                                       int32_t vocab, const int32_t* active_idx, const int32_t* m_dev, int32_t m_upper,
+                                       const uint8_t* masked, int32_t n_seq, int32_t block_lo, int32_t block_hi,
+                                       float temperature, uint64_t seed, int32_t t, const int32_t* argmax,
+                                       int32_t* write_id) {
+  if (!logits_cur || !active_idx || !m_dev || !masked || !argmax || !write_id) return SL_EINVAL;
+  if ((dtype != SL_F32 && dtype != SL_BF16) || vocab < 8 || vocab % 8 || m_upper < 0 || n_seq < 1) return SL_EINVAL;
+  if (block_lo < 0 || block_hi > n_seq || block_lo > block_hi || !(temperature > 0.f) || t < 1) return SL_EINVAL;
+  if (m_upper > slk_sample_static_rows()) return SL_ENOSPC;       // beyond the static buffer: use sl_sample_tokens
+  void* parts = nullptr;
+  SL_TRY(slk_sample_static_ptr(&parts));
+  return slk_sample_tokens((hipStream_t)stream, logits_cur, cur_packed, dtype, vocab, active_idx, m_dev, m_upper, masked,
+                           n_seq, block_lo, block_hi, temperature, seed, t, argmax, write_id, parts);
+}
+
 extern "C" int sl_select_rows(void* stream, const uint8_t* lock, const uint8_t* masked, const float* d_last,
                              int32_t batch, int32_t n_seq, int32_t block_lo, int32_t block_hi, float select_fraction,
                              uint8_t* compute_mask) {

@@ -136,3 +136,30 @@ int slk_sample_tokens(hipStream_t s, const void* logits, int cur_packed, int dty
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
+
+// ---- the same draw for callers that cannot allocate ----------------------------------------------
+// The per-part candidates live in a file-scope device array instead of a caller's buffer.  Every
+// GPU holds its own copy of the array at its own address; the address is looked up once per device
+// (with that device current) and kept.  The array's name is only a host-side handle: device code
+// and HIP calls always get the looked-up pointer.
+constexpr int kSampleStaticRows = 16384;                       // largest m_upper the static buffer serves (1 MiB)
+static __device__ __align__(256) unsigned char scratch[(size_t)kSampleStaticRows * kSampleParts * sizeof(SamplePart)];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];                       // per device; null until first use there
+
+int slk_sample_static_rows() { return kSampleStaticRows; }
+
+// Device address of this device's copy of `scratch` (no allocation: the array is part of the code object).
+int slk_sample_static_ptr(void** out) {
+  int dev = 0;
+  SL_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SL_EINVAL;
+  void* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    SL_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return SL_EHIP;
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);  // racing first calls store the same address
+  }
+  *out = p;
+  return SL_OK;
+}

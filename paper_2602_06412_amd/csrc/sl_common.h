@@ -178,6 +178,8 @@ int slk_sample_tokens(hipStream_t s, const void* logits, int cur_packed, int dty
                       const int32_t* m_dev, int m_upper, const uint8_t* masked, int N, int lo, int hi, float tau,
                       unsigned long long seed, int t, const int32_t* argmax, int32_t* write_id, void* scratch);
 size_t slk_sample_scratch_bytes(int m_upper);
+int slk_sample_static_rows();
+int slk_sample_static_ptr(void** out);
 int slk_select_rows(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const float* d_last, int B, int N,
                     int lo, int hi, float k_frac, uint8_t* compute_mask);
 int slk_posterior_carry_skipped(hipStream_t s, void* store, size_t buf_bytes, size_t row_bytes, const uint8_t* lock,

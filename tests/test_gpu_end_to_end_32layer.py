@@ -1,0 +1,136 @@
+"""End-to-end parity of the 32-layer step against the oracle (config 3: LLaDA-8B shape, 32 layers,
+vocabulary 126464, N = 512, one sequence): the oracle runs the whole restricted forward of
+Algorithm 1's loop body on the CPU in fp64 (every active row through all 32 blocks, its own K/V
+tables carried from step to step), the GPU runs sl_surelock_step on the same state, and the
+logits of sampled rows are compared directly: no re-synchronisation between layers, so whatever
+32 blocks of bf16 rounding do to the two computations shows here.
+
+Three steps on a shrinking active set (512 rows, then 288 = one full row tile + a ragged 32-row
+tail, then 40): steps 2 and 3 attend to K/V that earlier steps cached, on both sides.
+
+What is asserted, and why (derivation in the design doc, 'Tolerances'): both sides round the same tensors
+to bf16 but sum in fp64 / fp32, so a value near a rounding boundary lands on one or the other
+neighbouring bf16 number, a whole spacing apart; such differences feed the next operator and
+multiply until the two computations differ by the bf16 rounding noise itself
+(tests/test_oracle_bf16_conditioning.py shows it on the CPU for the oracle against itself).  Over 32
+blocks that noise is several 1e-3 of the logit scale, and no implementation whose sums are not
+bit-identical to the oracle's can stay within 2e-2 on every one of 10^6 logits.  The yardstick is
+therefore measured in the same run: the oracle is evaluated a second time with every value perturbed
+by 1e-7 relative before it is rounded (what fp32 accumulation does), with its own K/V tables, and
+the GPU must be as close to the plain oracle as that second correct evaluation is: mean error,
+share of logits beyond 2e-2 and beyond max(2e-2, one bf16 spacing), and the largest error, each
+within a small factor of the yardstick's.  All figures are printed."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import control, model, posterior
+from paper_2602_06412_amd import binding as B
+from paper_2602_06412_amd import workloads as wl
+from tests.gpu_util import DEV, bf16_ulp, compare_logits, dev, oracle_cfg, second_evaluation_cfg
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
+
+
+def test_c3_three_steps_end_to_end_against_the_oracle():
+    shape, N, n_p, seed = wl.C3, 512, 256, 3
+    cfg = oracle_cfg(shape)
+    w = wl.make_weights(shape, seed=seed, device="cuda")
+    sess = B.Session(shape, w, 1, N)
+    rng = np.random.default_rng(seed)
+    try:
+        # a moment late in the schedule: all but the last 64 generation slots already hold tokens
+        tokens = np.empty(N, dtype=np.int64)
+        tokens[:n_p] = wl.prompt_uniform(11, n_p, shape.vocab, shape.mask_id)
+        tokens[n_p:] = wl.prompt_uniform(12, N - n_p, shape.vocab, shape.mask_id)
+        masked = np.zeros(N, dtype=np.uint8)
+        masked[N - 64:] = 1
+        tokens[N - 64:] = shape.mask_id
+        lock = np.zeros(N, dtype=np.uint8)
+        pri = np.random.default_rng(seed * 100).permutation(N)
+        eps_d = dev(np.array([1e-3], dtype=np.float32))
+        emb64 = f64(w["emb"][torch.as_tensor(tokens, device=DEV)])        # rows by position (tokens do not change: k = 0)
+        fn64, lm64 = f64(w["final_norm"]), f64(w["lm_head"])
+        cfg2 = second_evaluation_cfg(cfg, seed)
+        # K/V tables of the oracle and of its second, perturbed evaluation
+        Kc, Vc, Kc2, Vc2 = ([np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)] for _ in range(4))
+        prev_gpu = None
+        for t, M_t in ((1, 512), (2, 288), (3, 40)):
+            n_lock = int((lock == 0).sum()) - M_t
+            for i in wl.forced_lock_positions(pri, lock, masked, n_lock):
+                lock[i] = 1
+            active = np.flatnonzero(lock == 0)
+            assert len(active) == M_t
+            new_lock = torch.zeros(N, dtype=torch.uint8, device=DEV)
+            sess.step(dev(tokens, torch.int32), dev(masked), dev(lock), eps_d, t, N - 64, N, 0, m_upper=M_t, new_lock=new_lock)
+            torch.cuda.synchronize()
+            assert np.array_equal(sess.active_idx[:M_t].cpu().numpy(), active)
+            # the oracle: every active row through all 32 blocks (weights converted one layer at a time)
+            t0 = time.perf_counter()
+            x = x2 = emb64[active]
+            for l in range(cfg.n_layers):
+                wl64 = {k: f64(v) for k, v in w["layers"][l].items()}
+                x = model.layer_active(cfg, wl64, x, active, Kc[l], Vc[l])
+                x2 = model.layer_active(cfg2, wl64, x2, active, Kc2[l], Vc2[l])
+                del wl64
+            sample = np.unique(np.concatenate([rng.choice(M_t, size=min(M_t, 10), replace=False), [0, M_t - 1]]))
+            z = cfg.rnd(cfg.rnd(model.rmsnorm(x[sample], fn64, cfg.rms_eps)) @ lm64.T)
+            z2 = cfg2.rnd(cfg2.rnd(model.rmsnorm(x2[sample], fn64, cfg.rms_eps)) @ lm64.T)
+            print(f"end-to-end t={t} M={M_t}: oracle forward {time.perf_counter() - t0:.1f} s", flush=True)
+            flat = torch.as_tensor(active[sample], device=DEV, dtype=torch.long)
+            z_gpu = sess.logits_view(t)[flat].double().cpu().numpy()
+            compare_logits(z_gpu, z, z2, f"32 layers end to end, t={t} M={M_t}")
+            # the last cached K/V rows (layer 31) of the sampled rows against the oracle's tables
+            kg, vg = sess.kv_read(cfg.n_layers - 1)
+            for got, want, what in ((f64(kg[0, flat]), Kc[-1][active[sample]], "K"), (f64(vg[0, flat]), Vc[-1][active[sample]], "V")):
+                e = np.abs(got - want)
+                rms = np.sqrt(np.mean(want ** 2))
+                print(f"  layer-32 cached {what}: max err {e.max():.3g}, mean {e.mean():.3g} (rms {rms:.3g})", flush=True)
+                assert e.mean() <= 1e-2 * rms and np.all(e <= bf16_ulp(want) + 8e-2 * rms)
+            # scores in situ on the GPU's own logits of the sampled rows
+            lp = posterior.log_softmax(z_gpu)
+            assert np.array_equal(sess.argmax[:M_t].cpu().numpy()[sample], posterior.argmax_lowest(z_gpu))
+            assert np.allclose(sess.conf[:M_t].cpu().numpy()[sample], posterior.max_prob(lp), rtol=2e-6)
+            kl = sess.kl[:M_t].cpu().numpy().astype(np.float64)[sample]
+            if t > 1:
+                want = posterior.kl_rows(lp, posterior.log_softmax(prev_gpu[active[sample]]))
+                assert np.all(np.abs(kl - want) <= 1e-4 * want + 2e-7)
+            else:
+                assert np.all(np.isinf(kl))
+            prev_gpu = _merge_prev(prev_gpu, sess.logits_view(t), active)
+            # the lock rule on the GPU's own scores (the forced schedule, not the rule, drives this test's mask:
+            # with unchanged tokens every row would lock at t = 2)
+            kl_all = sess.kl[:M_t].cpu().numpy()
+            F = control.lock_rule(lock, masked, active, kl_all, 1.0 - sess.conf[:M_t].cpu().numpy(), np.float32(1e-3), t == 1)
+            want_lock = lock.copy()
+            want_lock[F] = 1
+            near = active[np.abs(kl_all.astype(np.float64) - 1e-3) <= 1e-6]
+            ok = want_lock == new_lock.cpu().numpy()
+            ok[near] = True
+            assert np.all(ok)
+    finally:
+        sess.close()
+        del w
+        torch.cuda.empty_cache()
+
+
+class _PrevRows:
+    """Newest GPU logits of every row, kept on the device; indexable by an array of flat ids."""
+
+    def __init__(self, full):
+        self.buf = full.clone()
+
+    def __getitem__(self, ids):
+        return self.buf[torch.as_tensor(ids, device=DEV, dtype=torch.long)].double().cpu().numpy()
+
+
+def _merge_prev(prev, full, active):
+    if not isinstance(prev, _PrevRows):
+        return _PrevRows(full)
+    idx = torch.as_tensor(active, device=DEV, dtype=torch.long)
+    prev.buf[idx] = full[idx]
+    return prev

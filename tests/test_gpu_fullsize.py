@@ -8,7 +8,7 @@ import torch
 from oracle import model, posterior
 from paper_2602_06412_amd import binding as B
 from paper_2602_06412_amd import workloads as wl
-from tests.gpu_util import DEV, check_logits, dev, oracle_cfg
+from tests.gpu_util import DEV, compare_logits, dev, oracle_cfg, second_evaluation_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -26,8 +26,8 @@ def test_c2_full_size_sampled_rows():
         lm64 = f64(w["lm_head"])
         eps = dev(np.array([1e-3], dtype=np.float32))
         zero = torch.zeros(N, dtype=torch.uint8, device=DEV)
-        Kc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
-        Vc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
+        cfg2 = second_evaluation_cfg(cfg, 0)          # the yardstick: a second evaluation of the oracle (tests/gpu_util.py)
+        Kc, Vc, Kc2, Vc2 = ([np.zeros((N, cfg.n_heads, cfg.d_head))] for _ in range(4))
         rng = np.random.default_rng(0)
         prev_rows = {}
         active = np.arange(N)
@@ -43,14 +43,14 @@ def test_c2_full_size_sampled_rows():
             assert int(sess.cu_active[-1].item()) == M
             assert np.array_equal(sess.active_idx[:M].cpu().numpy(), active)
             # oracle: block output of the active rows (tokens index w64['emb'] by position)
-            x = w64["emb"][active]
-            x = model.layer_active(cfg, w64["layers"][0], x, active, Kc[0], Vc[0])
+            x = model.layer_active(cfg, w64["layers"][0], w64["emb"][active], active, Kc[0], Vc[0])
+            x2 = model.layer_active(cfg2, w64["layers"][0], w64["emb"][active], active, Kc2[0], Vc2[0])
             sample = np.unique(np.concatenate([rng.choice(M, size=min(M, 5), replace=False), [M - 1, max(0, M - 40)]]))
-            hf = cfg.rnd(model.rmsnorm(x[sample], w64["final_norm"], cfg.rms_eps))
-            z = cfg.rnd(hf @ lm64.T)
+            z = cfg.rnd(cfg.rnd(model.rmsnorm(x[sample], w64["final_norm"], cfg.rms_eps)) @ lm64.T)
+            z2 = cfg2.rnd(cfg2.rnd(model.rmsnorm(x2[sample], w64["final_norm"], cfg.rms_eps)) @ lm64.T)
             rows = torch.as_tensor(active[sample], device=DEV, dtype=torch.long)
             z_gpu = sess.logits_view(t)[rows].double().cpu().numpy()
-            check_logits(z_gpu, z, "bf16", f"t={t} M={M}")
+            compare_logits(z_gpu, z, z2, f"t={t} M={M}")
             # scoring in situ on the GPU's own logits for the sampled rows
             lp = posterior.log_softmax(z_gpu)
             conf = sess.conf[:M].cpu().numpy()[sample]

@@ -34,8 +34,11 @@ f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
 CHECK_LAYERS = (0, 1, 13, 31)
 
 
-def _run_case(Bn, N, prompts, n_prompt, eps_list, schedule, block, seed):
-    """schedule: per step a list of per-sequence active counts (nested forced locks)."""
+def _run_case(Bn, N, prompts, n_prompt, eps_list, schedule, block, seed, n_masked=None):
+    """schedule: per step a list of per-sequence active counts (nested forced locks; a count below the
+    number of lockable, i.e. unmasked, positions is met as far as those go).
+    n_masked: generation slots still masked at the first step (default: all); the others already hold
+    seeded token ids, the state late in a schedule, where most positions can lock."""
     shape = wl.C3
     cfg = oracle_cfg(shape)
     w = wl.make_weights(shape, seed=seed, device="cuda")
@@ -47,6 +50,10 @@ def _run_case(Bn, N, prompts, n_prompt, eps_list, schedule, block, seed):
         for b in range(Bn):
             tokens[b, :n_prompt] = prompts[b]
             masked[b, :n_prompt] = 0
+            if n_masked is not None:
+                done = N - n_masked
+                tokens[b, n_prompt:done] = wl.prompt_uniform(seed * 10 + b, done - n_prompt, shape.vocab, shape.mask_id)
+                masked[b, n_prompt:done] = 0
         lock = np.zeros((Bn, N), dtype=np.uint8)
         pri = [np.random.default_rng(seed * 100 + b).permutation(N) for b in range(Bn)]
         eps_d = dev(np.asarray(eps_list, dtype=np.float32))
@@ -151,12 +158,15 @@ def test_c3_shape_32_layers_single_sequence():
 
 
 def test_c5_shape_32_layers_ragged_batch():
-    """Four sequences of N = 1024 (512 Zipf(1.1) prompt tokens + 512 [MASK]) with different
-    thresholds and different active counts: packed varlen rows through all 32 layers."""
-    N, n_p, Bn = 1024, 512, 4
+    """Config 5 at its own batch size: eight sequences of N = 1024 (512 Zipf(1.1) prompt tokens + 512 [MASK]),
+    per-sequence thresholds {1e-4, 1e-3, 1e-2}[b mod 3] and different active counts per sequence: packed
+    varlen rows (8192, then 4841, then 1328 in total) through all 32 layers.  All but the last 64 slots of
+    each sequence are already unmasked, so that the per-sequence counts (down to one row) can be met."""
+    N, n_p, Bn = 1024, 512, 8
     prompts = [wl.prompt_zipf(20 + b, n_p, wl.C3.vocab, wl.C3.mask_id) for b in range(Bn)]
-    eps = [1e-4, 1e-3, 1e-2, 1e-4]
-    _run_case(Bn, N, prompts, n_p, eps, [[1024] * 4, [900, 640, 1000, 130], [300, 64, 700, 17]], (n_p, N, 1), seed=5)
+    eps = [[1e-4, 1e-3, 1e-2][b % 3] for b in range(Bn)]
+    schedule = [[1024] * Bn, [900, 640, 1000, 130, 512, 777, 257, 625], [300, 64, 700, 17, 33, 128, 1, 85]]
+    _run_case(Bn, N, prompts, n_p, eps, schedule, (N - 64, N, 1), seed=5, n_masked=64)
 
 
 def test_c4_shape_32_layers_long_sequence():
