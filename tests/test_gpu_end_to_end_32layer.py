@@ -6,7 +6,7 @@ logits of sampled rows are compared directly: no re-synchronisation between laye
 32 blocks of bf16 rounding do to the two computations shows here.
 
 Three steps on a shrinking active set (512 rows, then 288 = one full row tile + a ragged 32-row
-tail, then 40): steps 2 and 3 attend to K/V that earlier steps cached, on both sides.
+tail, then 72): steps 2 and 3 attend to K/V that earlier steps cached, on both sides.
 
 What is asserted, and why (derivation in the design doc, 'Tolerances'): both sides round the same tensors
 to bf16 but sum in fp64 / fp32, so a value near a rounding boundary lands on one or the other
@@ -59,7 +59,7 @@ def test_c3_three_steps_end_to_end_against_the_oracle():
         # K/V tables of the oracle and of its second, perturbed evaluation
         Kc, Vc, Kc2, Vc2 = ([np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)] for _ in range(4))
         prev_gpu = None
-        for t, M_t in ((1, 512), (2, 288), (3, 40)):
+        for t, M_t in ((1, 512), (2, 288), (3, 72)):
             n_lock = int((lock == 0).sum()) - M_t
             for i in wl.forced_lock_positions(pri, lock, masked, n_lock):
                 lock[i] = 1
@@ -84,13 +84,16 @@ def test_c3_three_steps_end_to_end_against_the_oracle():
             flat = torch.as_tensor(active[sample], device=DEV, dtype=torch.long)
             z_gpu = sess.logits_view(t)[flat].double().cpu().numpy()
             compare_logits(z_gpu, z, z2, f"32 layers end to end, t={t} M={M_t}")
-            # the last cached K/V rows (layer 31) of the sampled rows against the oracle's tables
+            # the last layer's cached K/V rows of the sampled rows against the oracle's tables, same yardstick
             kg, vg = sess.kv_read(cfg.n_layers - 1)
-            for got, want, what in ((f64(kg[0, flat]), Kc[-1][active[sample]], "K"), (f64(vg[0, flat]), Vc[-1][active[sample]], "V")):
-                e = np.abs(got - want)
+            rows = active[sample]
+            for got, want, second, what in ((f64(kg[0, flat]), Kc[-1][rows], Kc2[-1][rows], "K"),
+                                            (f64(vg[0, flat]), Vc[-1][rows], Vc2[-1][rows], "V")):
+                e, e2 = np.abs(got - want), np.abs(second - want)
                 rms = np.sqrt(np.mean(want ** 2))
-                print(f"  layer-32 cached {what}: max err {e.max():.3g}, mean {e.mean():.3g} (rms {rms:.3g})", flush=True)
-                assert e.mean() <= 1e-2 * rms and np.all(e <= bf16_ulp(want) + 8e-2 * rms)
+                print(f"  layer-32 cached {what} (rms {rms:.3g}): GPU vs oracle max err {e.max():.3g}, mean {e.mean():.3g}; "
+                      f"second evaluation vs oracle max {e2.max():.3g}, mean {e2.mean():.3g}", flush=True)
+                assert e.mean() <= 1.25 * e2.mean() + 1e-4 and e.max() <= 1.5 * e2.max() + float(bf16_ulp(np.array(rms)))
             # scores in situ on the GPU's own logits of the sampled rows
             lp = posterior.log_softmax(z_gpu)
             assert np.array_equal(sess.argmax[:M_t].cpu().numpy()[sample], posterior.argmax_lowest(z_gpu))
