@@ -95,3 +95,21 @@ def test_controller_entry_points_reject_null_and_bad_sizes():
     assert lib.sl_peak_probe_stream(None, 256, None, 40, 256, 1 << 21) == B.SL_EINVAL                   # bytes % 16
     assert lib.sl_peak_probe_stream(None, 256, 512, 1024, 256, 1 << 21) == B.SL_EINVAL                  # overlap
     assert lib.sl_peak_probe_stream(None, 264, None, 1024, 256, 1 << 21) == B.SL_EINVAL                 # alignment
+
+
+def test_noalloc_draw_rejects_bad_arguments_without_gpu():
+    """sl_sample_tokens_noalloc validates on the host before it touches HIP: null pointers and a row bound
+    beyond its static buffer (16384 rows) are errors with no GPU present."""
+    lib = B.lib()
+    buf = (C.c_char * 64)()
+    p = C.cast(buf, C.c_void_p)                    # any non-null address: nothing is dereferenced on the host
+    ok = [None, p, 1, B.SL_BF16, 64, p, p, 16, p, 32, 0, 32, C.c_float(1.0), C.c_uint64(1), 1, p, p]
+    bad = list(ok); bad[7] = 16385
+    assert lib.sl_sample_tokens_noalloc(*bad) == B.SL_ENOSPC
+    for i in (1, 5, 6, 8, 15, 16):
+        bad = list(ok); bad[i] = None
+        assert lib.sl_sample_tokens_noalloc(*bad) == B.SL_EINVAL
+    bad = list(ok); bad[12] = C.c_float(0.0)
+    assert lib.sl_sample_tokens_noalloc(*bad) == B.SL_EINVAL
+    bad = list(ok); bad[4] = 63
+    assert lib.sl_sample_tokens_noalloc(*bad) == B.SL_EINVAL
