@@ -1,20 +1,25 @@
 #!/usr/bin/env python3
 """SureLock step latency vs unlocked fraction M/N on one MI355X.
 
-Workload (BASELINE config 2): one LLaDA-8B-shaped bf16 layer (d=4096, 32 heads x 128,
-SwiGLU FFN 12288) plus the LLaDA LM head (vocab 126464) so that every step of the hot path
-runs: compaction, gather+RMSNorm, QKV GEMM, RoPE + K/V cache write, M x N attention over
-N=1024 cached slots, Out GEMM, FFN GEMMs, LM head, KL/conf/argmax scoring, UpdateMASK,
-lock rule.  Active sets of M in {1024, 512, 256, 64, 16} positions are drawn uniformly
-without replacement from a seed.  Inputs are resident in HBM before the timed region.
+Headline workload (BASELINE config 5, the largest that is one GPU's share): the full 32-layer
+LLaDA-8B-shaped bf16 model (d=4096, 32 heads x 128, SwiGLU FFN 12288, vocabulary 126464, random-init
+N(0, 0.02)), B = 8 sequences of N = 1024 slots (512 Zipf(1.1) prompt tokens + 512 generated), packed
+ragged rows.  `value` is the latency of one whole SureLock step (compaction, gather + RMSNorm, 32 x
+[Q|K|V projection, RoPE + K/V cache write, M x N attention, Out projection, SwiGLU FFN], LM head,
+KL / confidence / argmax scoring, UpdateMASK, lock rule) with every row active (sum M = 8192), timed
+over exactly --steps steps; `sweep` samples the configuration's forced linear lock schedule, so that
+latency can be read against M/N, and gives the time ratio of the whole schedule against full
+recompute beside the active-row ratio (the algorithmic work kept, Sec. 2.4).  The same is done for
+configs 4 (B=1, N=2048) and 3 (B=1, N=512) and, on one layer, config 2 (N=1024, M in
+{1024,512,256,64,16}).  All inputs are seeded, synthetic and resident in HBM before any timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only c5,c4,c3,c2] [--points P]
 
-Prints one JSON line; `value` is the step latency at M = N, `sweep` the latency at each M.
-"""
+Prints one JSON line."""
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,10 +29,18 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK = 2.5e15      # dense bf16 FLOP/s, MI355X
 HBM_PEAK = 8.0e12            # B/s
-# HBM bytes (fetched + written) of one LM-head launch, from the rocprofv3 FETCH_SIZE and
-# WRITE_SIZE counter runs summarised in profiles/bench_c2_hbm_traffic.txt (already scaled by
-# the copy-kernel calibration given there), keyed by M.
-LM_HEAD_TRAFFIC_BYTES = {1024: 1851893935, 16: 1042204494}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_c5_gate_up_hbm_traffic.txt")
+
+
+def traffic_from_profile():
+    """HBM bytes per launch of the dominant kernel, read from the rocprofv3 counter summary that measured
+    them (the line 'roofline.traffic = <bytes>' of the profile, which also gives the commands); None when the
+    summary is not there.  Counters cannot be collected by this run itself."""
+    try:
+        m = re.search(r"roofline\.traffic\s*=\s*([0-9][0-9,]*)", open(TRAFFIC_PROFILE).read())
+        return int(m.group(1).replace(",", "")) if m else None
+    except OSError:
+        return None
 
 
 def lm_head_clock_probe(B, torch, w_lm, M, V, d, seed, launches=12):
@@ -92,14 +105,109 @@ def achievable_peaks(B, torch, dev, seed):
     return out
 
 
+def c2_sweep(B, torch, np, wl, w, K, W, seed, sweep):
+    """Config 2: one layer (layer 0 of the model) + LM head, N = 1024, M swept; plus the optional-unlocking probe
+    and the selection-hybrid step on the same session."""
+    from paper_2602_06412_amd.run_config import slot_work
+    shape, N = wl.C2, 1024
+    dev = torch.device("cuda:0")
+    w1 = {"emb": w["emb"], "final_norm": w["final_norm"], "lm_head": w["lm_head"], "layers": [w["layers"][0]]}
+    sess = B.Session(shape, w1, 1, N)
+    rng = np.random.default_rng(seed)
+    tokens0 = torch.as_tensor(wl.prompt_uniform(seed + 1, N, shape.vocab, shape.mask_id), dtype=torch.int32, device=dev)
+    eps = torch.full((1,), 1e-3, dtype=torch.float32, device=dev)
+    zero_mask = torch.zeros(N, dtype=torch.uint8, device=dev)
+    new_lock = torch.zeros(N, dtype=torch.uint8, device=dev)
+    t = 0
+    for _ in range(2):                       # cache + both posterior buffers filled by two M = N passes
+        t += 1
+        sess.step(tokens0.clone(), zero_mask.clone(), zero_mask, eps, t, 0, N, 0, m_upper=N, new_lock=new_lock)
+    torch.cuda.synchronize()
+    results = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for M in sweep:
+        active = wl.active_positions(seed + 100 + M, N, M)
+        lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
+        masked = (1 - lock).clone()                 # every active slot still masked: UpdateMASK has work
+        tokens = tokens0.clone()
+
+        def run(n_steps):
+            nonlocal t
+            for _ in range(n_steps):
+                t += 1
+                sess.step(tokens, masked, lock, eps, t, 0, N, 1, m_upper=M, new_lock=new_lock)
+
+        run(max(W, 2))
+        torch.cuda.synchronize()
+        e0.record()
+        run(K)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / K
+        B.sl_profile_begin(sess.ctx, K * 32)
+        run(K)
+        prof = B.sl_profile_end(sess.ctx)
+        per = {k: v[0] / K for k, v in prof.items()}            # ms per step per kernel slot
+        work = slot_work(shape, N, M)
+        gem = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "lm_head"]
+        gsec = sum(per[s] for s in gem) * 1e-3
+        results.append({
+            "M": M, "M_over_N": M / N, "ms": round(ms, 4), "rows_per_s": round(M / (ms * 1e-3), 1),
+            "gemm_mfma_frac": round(sum(work[s]["flops"] for s in gem) / gsec / MFMA_BF16_PEAK, 4),
+            "gemm_hbm_frac": round(sum(work[s]["bytes"] for s in gem) / gsec / HBM_PEAK, 4),
+            "attention_mfma_frac": round(work["attention"]["flops"] / (per["attention"] * 1e-3) / MFMA_BF16_PEAK, 4),
+            "score_hbm_frac": round(work["score"]["bytes"] / (per["score"] * 1e-3) / HBM_PEAK, 4),
+            "kernels_ms": {k: round(v, 4) for k, v in per.items()},
+        })
+    # Optional unlocking (appendix): one read-only probe + unlock rule over N/2 locked rows (eps_unlock = +inf:
+    # nothing unlocks, the state stays as it is); amortised over the probe period P.
+    Mp = N // 2
+    active = wl.active_positions(seed + 100 + Mp, N, N - Mp)
+    lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
+    sess.unlock_state()
+    sess.t_lock.copy_(torch.as_tensor(rng.integers(1, 3, N), dtype=torch.int32, device=dev) * lock.to(torch.int32))
+    sess.step(tokens0.clone(), (1 - lock).clone(), lock, eps, t + 1, 0, N, 1, m_upper=N - Mp, new_lock=new_lock)
+    for i in range(W + K):
+        if i == W:
+            torch.cuda.synchronize()
+            e0.record()
+        sess.unlock_probe(tokens0, lock, t + 1, 20.0, float("inf"), 1, 2, m_upper_probe=Mp, m_upper_active=N - Mp)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_ms = e0.elapsed_time(e1) / K
+    t += 1
+    # Selection hybrid (Exp-5, combined setting): the step that computes ceil(0.8 n) of the n = N non-locked rows.
+    k_sel = 0.8
+    M_sel = int(np.ceil(float(np.float32(k_sel)) * N))
+    sel_masked = zero_mask.clone()
+    for i in range(W + K):
+        if i == W:
+            torch.cuda.synchronize()
+            e0.record()
+        t += 1
+        sess.step_selected(tokens0, sel_masked, zero_mask, eps, t, 0, N, 0, k_sel, m_upper=M_sel, new_lock=new_lock)
+    e1.record()
+    torch.cuda.synchronize()
+    sel_ms = e0.elapsed_time(e1) / K
+    sess.close()
+    return {"workload": "C2: one LLaDA-8B-shaped bf16 layer + LM head (V=126464), N=1024 cached K/V, B=1", "sweep": results,
+            "unlock_probe": {"locked_rows": Mp, "ms": round(probe_ms, 4),
+                             "note": "read-only probe + unlock rule over the locked rows, once per P steps"},
+            "selected_step": {"k": k_sel, "non_locked_rows": N, "computed_rows": M_sel, "ms": round(sel_ms, 4),
+                              "note": "step with on-device selection of ceil(k n) rows + posterior carry of the skipped ones"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--points", type=int, default=6, help="samples of each lock schedule")
+    ap.add_argument("--only", type=str, default="c5,c4,c3,c2", help="which configurations to run (c5 is always run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep", type=str, default="1024,512,256,64,16")
+    ap.add_argument("--no-probes", action="store_true", help="skip the peak and clock probes")
+    ap.add_argument("--c2-sweep", type=str, default="1024,512,256,64,16")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB elementwise copy kernel, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -112,120 +220,68 @@ def main():
     import torch
     from paper_2602_06412_amd import binding as B
     from paper_2602_06412_amd import workloads as wl
+    from paper_2602_06412_amd.run_config import DESCRIBE, ScheduleRunner, slot_work
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    shape, N, Bn = wl.C2, 1024, 1
     K, W = args.steps, args.warmup
-    sweep = [int(x) for x in args.sweep.split(",")]
+    only = set(args.only.split(",")) | {"c5"}
+    shape = wl.C3
+    d, V = shape.d_model, shape.vocab
 
-    w = wl.make_weights(shape, args.seed, device="cuda", emb_std=1.0)
-    sess = B.Session(shape, w, Bn, N)
-    rng = np.random.default_rng(args.seed)
-    tokens0 = torch.as_tensor(wl.prompt_uniform(args.seed + 1, N, shape.vocab, shape.mask_id), dtype=torch.int32,
-                              device=dev)
-    eps = torch.full((Bn,), 1e-3, dtype=torch.float32, device=dev)
-    zero_mask = torch.zeros(N, dtype=torch.uint8, device=dev)
-    new_lock = torch.zeros(N, dtype=torch.uint8, device=dev)
+    w = wl.make_weights(shape, args.seed, device="cuda")
+    log = lambda row: print(json.dumps(row), file=sys.stderr, flush=True)
 
-    # cache + both posterior buffers filled by two M = N passes
-    t = 0
-    for _ in range(2):
-        t += 1
-        sess.step(tokens0.clone(), zero_mask.clone(), zero_mask, eps, t, 0, N, 0, m_upper=N, new_lock=new_lock)
-    torch.cuda.synchronize()
+    # ---- headline: config 5, every row active, exactly K timed steps after W warm-up steps ----
+    r5 = ScheduleRunner("c5", w, args.seed)
+    packed = r5.sess.packed
+    masked, lock, blk = r5.state(1, full=True)
+    lock = np.zeros_like(lock)
+    M0, ms0, per0 = r5.timed(masked, lock, blk, K, warmup=W)
+    work0 = slot_work(shape, r5.N, M0)
+    dom = max((s for s in per0 if per0[s][1] > 0), key=lambda s: per0[s][0] * per0[s][1])      # largest share of the step
+    dom_ms = per0[dom][0]
+    roof = {"kernel": "%s launch (layer projection d=%d -> 2 x d_ff=%d with SwiGLU epilogue, %d rows)" % (dom, d, shape.d_ff, M0)
+            if dom == "gemm_gate_up" else "%s launch at %d rows" % (dom, M0),
+            "bound": "mfma", "achieved": round(work0[dom]["flops"] / (dom_ms * 1e-3) / 1e12, 2),
+            "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+            "frac": round(work0[dom]["flops"] / (dom_ms * 1e-3) / MFMA_BF16_PEAK, 4),
+            "traffic": traffic_from_profile() if dom == "gemm_gate_up" else None,
+            "launch_ms": round(dom_ms, 4), "launches_per_step": per0[dom][1],
+            "algorithmic_flops_per_launch": work0[dom]["flops"],
+            "share_of_step": round(per0[dom][0] * per0[dom][1] / sum(a * n for a, n in per0.values()), 3)}
+    fam = {}
+    for s, wk in work0.items():
+        if per0.get(s, (0, 0))[1] == 0:
+            continue
+        sec = per0[s][0] * 1e-3
+        fam[s] = {"us": round(per0[s][0] * 1e3, 1), "launches_per_step": per0[s][1]}
+        if wk["flops"] is not None:
+            fam[s]["mfma_frac"] = round(wk["flops"] / sec / MFMA_BF16_PEAK, 4)
+        else:
+            fam[s]["hbm_frac"] = round(wk["bytes"] / sec / HBM_PEAK, 4)
+    roof["per_kernel"] = fam
+    gemm4 = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down"]
+    roof["layer_projections_frac"] = round(sum(work0[s]["flops"] for s in gemm4) /
+                                           (sum(per0[s][0] for s in gemm4) * 1e-3) / MFMA_BF16_PEAK, 4)
 
-    d, dff, hd, V = shape.d_model, shape.d_ff, shape.n_heads * shape.d_head, shape.vocab
-    layer_gemm_flops = 2 * d * (3 * hd) + 2 * hd * d + 2 * d * (2 * dff) + 2 * dff * d      # per row
-    lm_flops = 2 * d * V
-    attn_flops = 4 * N * hd                                                                 # per row
-    layer_w_bytes = 2 * (d * 3 * hd + hd * d + d * 2 * dff + dff * d)
-    lm_w_bytes = 2 * d * V
-    gemm_slots = ["gemm_qkv", "gemm_out", "gemm_gate_up", "gemm_down", "lm_head"]
-
-    results = []
-    for M in sweep:
-        active = wl.active_positions(args.seed + 100 + M, N, M)
-        lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
-        masked = (1 - lock).clone()                 # every active slot still masked: UpdateMASK has work
-        tokens = tokens0.clone()
-
-        def run(n_steps):
-            nonlocal t
-            for _ in range(n_steps):
-                t += 1
-                sess.step(tokens, masked, lock, eps, t, 0, N, 1, m_upper=M, new_lock=new_lock)
-
-        run(W)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        run(K)
-        e1.record()
-        torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / K
-        ms = e0.elapsed_time(e1) / K
-        # per-kernel event timing of the same steps (profiling on: separate pass)
-        B.sl_profile_begin(sess.ctx, K * 16)
-        run(K)
-        prof = B.sl_profile_end(sess.ctx)
-        per = {k: v[0] / K for k, v in prof.items()}            # ms per step per kernel slot
-        gemm_ms = sum(per[s] for s in gemm_slots)
-        gemm_flops = M * (layer_gemm_flops + lm_flops)
-        gemm_bytes = layer_w_bytes + lm_w_bytes + 2 * M * (d * 6 + hd * 2 + dff * 2) + 2 * M * V
-        score_bytes = M * V * 4
-        results.append({
-            "M": M, "M_over_N": M / N, "ms": round(ms, 4), "wall_ms": round(wall_ms, 4),
-            "rows_per_s": round(M / (ms * 1e-3), 1),
-            "gemm_ms": round(gemm_ms, 4), "gemm_tflops": round(gemm_flops / (gemm_ms * 1e-3) / 1e12, 2),
-            "gemm_mfma_frac": round(gemm_flops / (gemm_ms * 1e-3) / MFMA_BF16_PEAK, 4),
-            "gemm_weight_stream_GBps": round(gemm_bytes / (gemm_ms * 1e-3) / 1e9, 1),
-            "gemm_hbm_frac": round(gemm_bytes / (gemm_ms * 1e-3) / HBM_PEAK, 4),
-            "attention_ms": round(per["attention"], 4),
-            "attention_mfma_frac": round(M * attn_flops / (per["attention"] * 1e-3) / MFMA_BF16_PEAK, 4),
-            "score_ms": round(per["score"], 4),
-            "score_hbm_frac": round(score_bytes / (per["score"] * 1e-3) / HBM_PEAK, 4),
-            "kernels_ms": {k: round(v, 4) for k, v in per.items()},
-        })
-
-    # Optional unlocking (appendix): cost of one read-only probe + unlock rule over N/2 locked rows, to be
-    # amortised over the probe period P.  eps_unlock = +inf: nothing unlocks, the state stays as it is.
-    Mp = N // 2
-    active = wl.active_positions(args.seed + 100 + Mp, N, N - Mp)
-    lock = torch.as_tensor(wl.lock_mask_from_active(N, active), device=dev)
-    sess.unlock_state()
-    sess.t_lock.copy_(torch.as_tensor(rng.integers(1, 3, N), dtype=torch.int32, device=dev) * lock.to(torch.int32))
-    sess.step(tokens0.clone(), (1 - lock).clone(), lock, eps, t + 1, 0, N, 1, m_upper=N - Mp, new_lock=new_lock)
-    for _ in range(W):
-        sess.unlock_probe(tokens0, lock, t + 1, 20.0, float("inf"), 1, 2, m_upper_probe=Mp, m_upper_active=N - Mp)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(K):
-        sess.unlock_probe(tokens0, lock, t + 1, 20.0, float("inf"), 1, 2, m_upper_probe=Mp, m_upper_active=N - Mp)
-    e1.record()
-    torch.cuda.synchronize()
-    assert int(sess.cu_probe[-1].item()) == Mp and int(lock.sum().item()) == Mp
-    probe_ms = e0.elapsed_time(e1) / K
-    t += 1
-
-    # Selection hybrid (Exp-5, combined setting): the step that computes ceil(0.8 n) of the n = N non-locked
-    # rows, chosen on the device by their last KL; skipped rows have their posterior row carried over.
-    k_sel = 0.8
-    M_sel = int(np.ceil(float(np.float32(k_sel)) * N))
-    sel_masked = zero_mask.clone()
-    for i in range(W + K):
-        if i == W:
-            torch.cuda.synchronize()
-            e0.record()
-        t += 1
-        sess.step_selected(tokens0, sel_masked, zero_mask, eps, t, 0, N, 0, k_sel, m_upper=M_sel, new_lock=new_lock)
-    e1.record()
-    torch.cuda.synchronize()
-    assert int(sess.cu_active[-1].item()) == M_sel
-    sel_ms = e0.elapsed_time(e1) / K
+    sweeps, summaries = {}, {}
+    rows, summ = r5.sweep(args.points, max(3, min(K, 10)), log=log)
+    sweeps["c5"], summaries["c5"] = rows, summ
+    r5.close()
+    torch.cuda.empty_cache()
+    for name in ("c4", "c3"):
+        if name not in only:
+            continue
+        r = ScheduleRunner(name, w, args.seed, packed=packed)
+        rows, summ = r.sweep(args.points, max(3, min(K, 10)), log=log)
+        sweeps[name], summaries[name] = rows, summ
+        r.close()
+        torch.cuda.empty_cache()
+    c2 = None
+    if "c2" in only:
+        c2 = c2_sweep(B, torch, np, wl, w, max(3, min(K, 20)), W, args.seed, [int(x) for x in args.c2_sweep.split(",")])
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)          # 1 GiB read + 1 GiB written
@@ -234,104 +290,101 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    head = results[0]
-    M0 = head["M"]
-    # Dominant kernel of the step: the LM-head GEMM launch (one per step).  Its duration is the
-    # HIP-event time of that launch on the step's stream, averaged over the K profiled steps.
-    lm_ms = head["kernels_ms"]["lm_head"]
-    if M0 >= 512:
-        ach = M0 * lm_flops / (lm_ms * 1e-3) / 1e12
-        roof = {"kernel": "gemm_mfma256_kernel<1, 256, false> (LM head, M=%d x V=%d x d=%d)" % (M0, V, d), "bound": "mfma",
-                "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
-                "frac": round(ach * 1e12 / MFMA_BF16_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
-                "launch_ms": round(lm_ms, 4), "algorithmic_flops_per_launch": M0 * lm_flops,
-                "gemm_family_tflops": head["gemm_tflops"], "gemm_family_frac": head["gemm_mfma_frac"]}
-    else:
-        bytes_ = lm_w_bytes + 2 * M0 * d + 2 * M0 * V
-        ach = bytes_ / (lm_ms * 1e-3) / 1e9
-        roof = {"kernel": "thin-launch GEMM (LM head weight stream, M=%d)" % M0, "bound": "hbm",
-                "achieved": round(ach, 1), "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": round(ach * 1e9 / HBM_PEAK, 4), "traffic": LM_HEAD_TRAFFIC_BYTES.get(M0),
-                "launch_ms": round(lm_ms, 4), "algorithmic_bytes_per_launch": bytes_}
-
-    if M0 >= 512:
-        roof["clock"] = lm_head_clock_probe(B, torch, w["lm_head"], M0, V, d, args.seed)
-
-    ach_peaks = achievable_peaks(B, torch, dev, args.seed)
-    mfma_ach = max(v for k_, v in ach_peaks.items() if k_.startswith("mfma_bf16_tflops"))
-    if roof["bound"] == "mfma":
+    ach_peaks = None
+    if not args.no_probes:
+        roof["lm_head_clock"] = lm_head_clock_probe(B, torch, w["lm_head"], 1024, V, d, args.seed)
+        ach_peaks = achievable_peaks(B, torch, dev, args.seed)
+        mfma_ach = max(v for k_, v in ach_peaks.items() if k_.startswith("mfma_bf16_tflops"))
         roof["frac_of_achievable"] = round(roof["achieved"] / mfma_ach, 4)
-    else:
-        roof["frac_of_achievable"] = round(roof["achieved"] / ach_peaks["hbm_read_GBps"], 4)
-    for r_ in results:
-        r_["gemm_frac_of_achievable_mfma"] = round(r_["gemm_tflops"] / mfma_ach, 4)
-        r_["score_frac_of_achievable_hbm_read"] = round(r_["score_hbm_frac"] * HBM_PEAK / 1e9 / ach_peaks["hbm_read_GBps"], 4)
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(shape, w, tokens0, N)
+        cpu = cpu_baseline(shape, w, args.seed)
 
     out = {
         "metric": "SureLock step latency (ms) vs unlocked fraction M/N; % bf16 MFMA peak",
-        "value": head["ms"], "unit": "ms", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": head["ms"],
+        "value": round(ms0, 4), "unit": "ms", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms0, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "C2: one LLaDA-8B-shaped bf16 layer + LM head (V=126464), N=1024 cached K/V, "
-                               "whole SureLock step at M=%d active rows (value); sweep over M in `sweep`" % M0,
-                   "N": N, "batch": Bn, "M": M0, "d_model": d, "n_heads": shape.n_heads, "d_head": shape.d_head,
-                   "d_ff": dff, "vocab": V, "n_layers": shape.n_layers},
-        "rows_per_s": head["rows_per_s"],
+        "config": {"workload": DESCRIBE["c5"] + "; value = whole SureLock step with every row active (sum M = %d); "
+                               "`sweep` samples the lock schedule" % M0,
+                   "N": r5.N, "batch": r5.Bn, "M": M0, "d_model": d, "n_heads": shape.n_heads, "d_head": shape.d_head,
+                   "d_ff": shape.d_ff, "vocab": V, "n_layers": shape.n_layers},
+        "rows_per_s": round(M0 / ms0 * 1e3),
         "roofline": roof,
         "achievable": ach_peaks,
         "cpu_baseline": cpu,
-        "sweep": results,
-        "selected_step": {"k": k_sel, "non_locked_rows": N, "computed_rows": M_sel, "ms": round(sel_ms, 4),
-                          "note": "step with on-device selection of ceil(k n) rows + posterior carry of the skipped ones"},
-        "unlock_probe": {"locked_rows": Mp, "ms": round(probe_ms, 4),
-                         "note": "read-only probe + unlock rule over the locked rows, once per P steps"},
+        "latency_vs_active_fraction": {k: {"workload": DESCRIBE[k], **summaries[k]} for k in summaries},
+        "sweep": sweeps,
+        "c2": c2,
     }
     print(json.dumps(out))
-    sess.close()
 
 
-def cpu_baseline(shape, w, tokens0, N):
-    """The oracle, as it stands, on the host cores: one full C2 step at M = N (restricted
-    forward of one layer + LM head + scoring), timed once."""
+def cpu_baseline(shape, w, seed):
+    """The oracle, as it stands, on the host cores, on a bounded sample of the headline workload: ONE of
+    config 5's eight sequences (N = 1024) through ONE of the 32 layers, the LM head and the scoring
+    (log-softmax, KL, confidence, argmax), at the sequence's largest, median and smallest active-row counts
+    (1024, 544, 64), with all cores; and the smallest once more on a single thread."""
     import numpy as np
     import torch
     from oracle import model, posterior
     from oracle.model import Config
+    from paper_2602_06412_amd import workloads as wl
+    try:
+        import threadpoolctl
+    except Exception:
+        threadpoolctl = None
 
-    cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab, shape.mask_id,
+    N, n_p = 1024, 512
+    cfg = Config(1, shape.d_model, shape.n_heads, shape.d_head, shape.d_ff, shape.vocab, shape.mask_id,
                  shape.rms_eps, shape.rope_theta, shape.storage)
-    tok = tokens0.cpu().numpy().astype(np.int64)
+    tok = np.concatenate([wl.prompt_zipf(seed + 10, n_p, shape.vocab, shape.mask_id),
+                          wl.prompt_uniform(seed + 50, N - n_p, shape.vocab, shape.mask_id)]).astype(np.int64)
     f64 = lambda t_: t_.detach().to("cpu", torch.float64).numpy()
     w64 = {"emb": f64(w["emb"][torch.as_tensor(tok, device=w["emb"].device)]),      # only the rows the tokens use
            "final_norm": f64(w["final_norm"]), "lm_head": f64(w["lm_head"]),
-           "layers": [{k: f64(v) for k, v in l.items()} for l in w["layers"]]}
-    Kc = [np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)]
-    Vc = [np.zeros((N, cfg.n_heads, cfg.d_head)) for _ in range(cfg.n_layers)]
-    prev = None
-    t0 = time.perf_counter()
-    z = model.forward_active(cfg, w64, np.arange(N), np.arange(N), Kc, Vc)
-    lp = posterior.log_softmax(z)
-    conf = posterior.max_prob(lp)
-    amax = posterior.argmax_lowest(z)
-    D = posterior.kl_rows(lp, lp if prev is None else prev)
-    dt = time.perf_counter() - t0
+           "layers": [{k: f64(v) for k, v in w["layers"][0].items()}]}
+    Kc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
+    Vc = [np.zeros((N, cfg.n_heads, cfg.d_head))]
     try:
         cores = len(os.sched_getaffinity(0))
     except Exception:
         cores = os.cpu_count()
-    try:
-        import threadpoolctl
-        nthreads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
-        cores = min(cores, nthreads) if nthreads else cores
-    except Exception:
-        pass
-    return {"value": round(dt * 1e3, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
-            "sample": "one full step of the same workload at M=N=1024 (1 layer + LM head + KL/conf/argmax), "
-                      "NumPy fp64, timed once", "rows_per_s": round(N / dt, 1),
-            "checksum": float(np.sum(D) + conf[0] + amax[0])}
+    pools = threadpoolctl.threadpool_info() if threadpoolctl else []
+    nthreads = max((p.get("num_threads", 1) for p in pools), default=cores)
+
+    def one(M):
+        active = wl.active_positions(seed + 100 + M, N, M) if M < N else np.arange(N)
+        t0 = time.perf_counter()
+        z = model.forward_active(cfg, w64, np.arange(N), active, Kc, Vc)
+        lp = posterior.log_softmax(z)
+        conf = posterior.max_prob(lp)
+        amax = posterior.argmax_lowest(z)
+        D = posterior.kl_rows(lp, lp)
+        return time.perf_counter() - t0, float(np.sum(D) + conf[0] + amax[0])
+
+    samples, chk = [], 0.0
+    for M in (1024, 544, 64):
+        dt, c = one(M)
+        chk += c
+        samples.append({"M": M, "ms": round(dt * 1e3, 1), "rows_per_s": round(M / dt, 1), "threads": int(min(cores, nthreads))})
+    single = None
+    if threadpoolctl:
+        with threadpoolctl.threadpool_limits(limits=1):
+            dt, c = one(64)
+        chk += c
+        single = {"M": 64, "ms": round(dt * 1e3, 1), "rows_per_s": round(64 / dt, 1), "threads": 1}
+    top = samples[0]
+    # one layer + LM head of one sequence -> 32 layers + LM head of eight sequences (labelled: an extrapolation)
+    layer_share = 436.2 / (436.2 + 1036.0)            # of the sample's matrix work that is the layer (MFLOP per row)
+    full_step_ms = top["ms"] * 8 * (32 * layer_share + (1 - layer_share))
+    return {"value": top["ms"], "unit": "ms", "cores": int(min(cores, nthreads)), "kind": "oracle",
+            "sample": "one of config 5's eight sequences (N=1024) through one of the 32 layers + LM head + KL/conf/argmax "
+                      "scoring, NumPy fp64, all host cores, at M=1024 (value), 544 and 64 active rows; M=64 again on one thread",
+            "rows_per_s": top["rows_per_s"], "samples": samples, "single_thread": single,
+            "extrapolated_full_step_ms": round(full_step_ms, 1),
+            "extrapolation": "value x 8 sequences x (32 layers + LM head) / (1 layer + LM head) by matrix work; not measured",
+            "host_cores": int(cores), "checksum": chk}
 
 
 if __name__ == "__main__":

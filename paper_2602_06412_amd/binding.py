@@ -373,14 +373,18 @@ class Session:
     workspace, per-step outputs) and forwards to the entry points above."""
 
     def __init__(self, shape, weights, batch, n_seq, device="cuda:0", candidates_pre_update=False,
-                 gate_percentile=0.0, temperature=0.0, seed=0):
+                 gate_percentile=0.0, temperature=0.0, seed=0, packed=None):
         self.shape, self.B, self.N, self.device = shape, batch, n_seq, torch.device(device)
         self.weights = weights
         self.T = {"fp32": torch.float32, "bf16": torch.bfloat16}[shape.storage]
         self.ctx = sl_init(make_config(shape, candidates_pre_update, gate_percentile, temperature, seed))
         dev = self.device
         u8 = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
-        self.packed = u8(sl_packed_weights_bytes(self.ctx))
+        # `packed`: a buffer another session of the same model already holds its re-tiled weights in (it is
+        # written again with the same bytes); saves a second copy of the weights
+        need = sl_packed_weights_bytes(self.ctx)
+        self.packed = u8(need) if packed is None else packed
+        assert self.packed.numel() >= need
         sl_bind_weights(self.ctx, weights, self.packed)
         self.kv = u8(sl_kv_cache_bytes(self.ctx, batch, n_seq))
         sl_kv_cache_bind(self.ctx, self.kv, batch, n_seq)

@@ -251,8 +251,12 @@ static Workspace carve(const sl_ctx* ctx, void* base, int rows, int batch, int n
   w.a = take(rows32 * c.d_ff * ts);
   size_t f32_elems = (size_t)rows * f32_cols;
   if (ctx->use_mfma) {
-    const size_t e = sl_mfma_f32_elems(&c, rows);
-    if (e > f32_elems) f32_elems = e;
+    // the plans' need grows with the row bound: one evaluation for the largest bound seen serves every smaller one
+    if (rows > ctx->f32_plan_rows) {
+      ctx->f32_plan_elems = sl_mfma_f32_elems(&c, rows);
+      ctx->f32_plan_rows = rows;
+    }
+    if (ctx->f32_plan_elems > f32_elems) f32_elems = ctx->f32_plan_elems;
   }
   w.f32 = (float*)take(f32_elems * sizeof(float));
   w.attn = nullptr;

@@ -143,6 +143,10 @@ struct sl_ctx {
   void* post; size_t post_buf_elems;
   // true while the read-only unlock probe runs: the forward stores queries only, no K/V
   bool probe_read_only;
+  // fp32 partial-plane elements the launch plans need for any launch of at most f32_plan_rows rows
+  // (evaluating the plans for every row count is host work that must stay off the per-step path)
+  mutable int f32_plan_rows;
+  mutable size_t f32_plan_elems;
 };
 
 // Run one launcher call, bracketed by an event pair when profiling is on.
