@@ -358,6 +358,18 @@ int sl_lock_test(void *stream, const void *logits_cur, int32_t cur_packed, const
  * must be non-null. */
 int sl_linear_pack(void *stream, const void *w, int32_t n, int32_t k, void *packed, size_t packed_bytes);
 int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k);
+/* The launch sl_linear_forward(.., splits = 0, y_f32) makes for a row bound (host outputs; nothing is
+ * launched), so that tests can tell which kernel form a shape reaches and check that every form a
+ * model shape can reach is covered:
+ *   kernel     0 = weight-stream kernel (rows <= 64: no LDS, operands global -> registers),
+ *              1 = ring kernel (operands through an LDS ring, one workgroup per CU),
+ *              2 = LDS kernel for reductions too short for the ring
+ *   splits     k-split count (= sl_linear_splits)
+ *   tile_rows  rows per workgroup tile (ring kernel: a multiple of 32 from 64 to 256, fitted to m_upper)
+ *   tile_cols  columns per workgroup tile (128 or 256)
+ *   tail_tile  1: full-height row tiles plus one half-height tile for the row tail (ring kernel) */
+int sl_linear_plan(int32_t m_upper, int32_t n, int32_t k, int32_t *kernel, int32_t *splits, int32_t *tile_rows,
+                   int32_t *tile_cols, int32_t *tail_tile);
 int sl_linear_forward(void *stream, const void *x, int32_t x_tiled, const void *packed, const int32_t *m_dev,
                       int32_t m_upper, int32_t n, int32_t k, int32_t splits, float *y_f32, void *y_bf16,
                       const int32_t *row_map);

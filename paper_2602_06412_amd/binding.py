@@ -62,6 +62,7 @@ _SIGS = {
     "sl_unlock_rule": [_P, _P, _P, _P, _P, _P, _P, _P, _I, _P, _P, _P, _I, _P, C.c_float, C.c_float, _I, _I, _I, _P],
     "sl_linear_pack": [_P, _P, _I, _I, _P, _Z],
     "sl_linear_splits": [_I, _I, _I],
+    "sl_linear_plan": [_I, _I, _I, C.POINTER(_I), C.POINTER(_I), C.POINTER(_I), C.POINTER(_I), C.POINTER(_I)],
     "sl_linear_forward": [_P, _P, _I, _P, _P, _I, _I, _I, _I, _P, _P, _P],
     "sl_linear_clock_probe": [_P, _P, _I, _P, _P, _I, _I, _I, _P, _P, _P],
     "sl_peak_probe_mfma": [_P, _P, _Z, _I, _I, _P, _Z, C.POINTER(C.c_int64)],
@@ -308,6 +309,13 @@ def sl_linear_splits(m_upper, n, k):
     if r < 0:
         raise SureLockError("sl_linear_splits", r)
     return r
+
+
+def sl_linear_plan(m_upper, n, k):
+    """(kernel, splits, tile_rows, tile_cols, tail_tile) of the launch a row bound gets (host only)."""
+    out = [_I() for _ in range(5)]
+    _check("sl_linear_plan", lib().sl_linear_plan(m_upper, n, k, *[C.byref(o) for o in out]))
+    return tuple(int(o.value) for o in out)
 
 
 def sl_linear_forward(x, packed, m_dev, m_upper, n, k, splits=0, y_f32=None, y_bf16=None, row_map=None, x_tiled=0):

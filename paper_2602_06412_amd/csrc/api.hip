@@ -469,6 +469,13 @@ extern "C" int sl_linear_splits(int32_t m_upper, int32_t n, int32_t k) {
   return slk_gemm_splits(m_upper, n, k);
 }
 
+extern "C" int sl_linear_plan(int32_t m_upper, int32_t n, int32_t k, int32_t* kernel, int32_t* splits, int32_t* tile_rows,
+                              int32_t* tile_cols, int32_t* tail_tile) {
+  if (m_upper < 1 || n < 32 || k < 64 || n % 32 || k % 64) return SL_EINVAL;
+  if (!kernel || !splits || !tile_rows || !tile_cols || !tail_tile) return SL_EINVAL;
+  return slk_gemm_describe(m_upper, n, k, kernel, splits, tile_rows, tile_cols, tail_tile);
+}
+
 extern "C" int sl_linear_forward(void* stream, const void* x, int32_t x_tiled, const void* packed, const int32_t* m_dev,
                                  int32_t m_upper, int32_t n, int32_t k, int32_t splits, float* y_f32, void* y_bf16,
                                  const int32_t* row_map) {

@@ -221,6 +221,142 @@ __device__ __forceinline__ void stream_landed(Frag (&b)[NBW], Frag (&a)[MB]) {
     asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b[0]), "+v"(a[0]), "+v"(a[MB - 1]) : "n"(N));
 }
 
+// ---- consumers run by the workgroup that completes a tile of a k-split launch (see sl_join) ---------
+// All work on the fp32 planes [S][m_upper][ldc] restricted to rows [0, M) and columns [n0, n0 + bn) of the
+// tile, with every thread of the workgroup; plane sums are taken in split order.
+__device__ inline void join_sum8(const float* p, int S, size_t sstride, float (&v)[8]) {
+  ld8f(p, v);
+  for (int sp = 1; sp < S; ++sp) {
+    float t[8];
+    ld8f(p + sp * sstride, t);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += t[e];
+  }
+}
+__device__ inline void join_sum4(const float* p, int S, size_t sstride, float (&v)[4]) {
+  ld4f(p, v);
+  for (int sp = 1; sp < S; ++sp) {
+    float t[4];
+    ld4f(p + sp * sstride, t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += t[e];
+  }
+}
+
+// x[r, c] <- rnd(x[r, c] + sum); x is [m, n] row-major
+__device__ inline void join_residual(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
+                                     int bn, int n) {
+  const int chunks = bn >> 3;
+  for (int it = threadIdx.x; it < M * chunks; it += blockDim.x) {
+    const int r = it / chunks, c = n0 + (it - r * chunks) * 8;
+    if (c >= n) continue;
+    float dl[8], v[8];
+    join_sum8(planes + (size_t)r * ldc + c, S, sstride, dl);
+    ld8(ja.x + (size_t)r * n + c, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = st<bf16_t>::rnd(v[e] + dl[e]);
+    st8(ja.x + (size_t)r * n + c, v);
+  }
+}
+
+// columns are gate / up interleaved by 32-column blocks; a[r, c] = silu(gate) * up, fragment-tiled
+__device__ inline void join_swiglu(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
+                                   int bn, int n) {
+  const int per_row = (bn >> 6) * 4;                     // (gate, up) pairs of the tile x four 8-column chunks
+  for (int it = threadIdx.x; it < M * per_row; it += blockDim.x) {
+    const int r = it / per_row, rem = it - r * per_row, pr = rem >> 2, ch = rem & 3;
+    const int gcol = n0 + 64 * pr + 8 * ch;
+    if (gcol + 32 >= n) continue;
+    float g[8], u[8], o[8];
+    join_sum8(planes + (size_t)r * ldc + gcol, S, sstride, g);
+    join_sum8(planes + (size_t)r * ldc + gcol + 32, S, sstride, u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+    st8(ja.a + afrag_index(r, (n0 >> 1) + 32 * pr + 8 * ch, ja.dff), o);
+  }
+}
+
+// columns are [q | k | v], H heads of 128 each; the tile lies inside one of the three (H * 128 is a multiple
+// of the tile width).  RoPE on the unrounded sums (pairs (j, j + 64) of a head, angle from the slot's table
+// row), q to the packed query rows, K and V to the slot's place in the cache layouts.
+__device__ inline void join_rope(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
+                                 int bn) {
+  const int hd = ja.H * 128, sec = n0 / hd, head0 = (n0 - sec * hd) >> 7;
+  const int per_row = (bn >> 7) * 16;                    // heads of the tile x sixteen chunks of four rotation pairs
+  if (sec > 0 && ja.kc == nullptr) return;               // read-only probe: queries only
+  for (int it = threadIdx.x; it < M * per_row; it += blockDim.x) {
+    const int r = it / per_row, rem = it - r * per_row, hh = rem >> 4, j = (rem & 15) * 4;
+    const int c0 = n0 + hh * 128 + j;
+    float a0[4], a1[4];
+    join_sum4(planes + (size_t)r * ldc + c0, S, sstride, a0);
+    join_sum4(planes + (size_t)r * ldc + c0 + 64, S, sstride, a1);
+    const int g = ja.active_idx[r];
+    const int b = g / ja.N, i = g - b * ja.N;
+    const int head = head0 + hh;
+    const size_t head_base = ((size_t)b * ja.H + head) * ja.n_pad * 128;
+    if (sec == 2) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        ja.vc[head_base + vc_index(i, j + e, 128)] = (bf16_t)a0[e];
+        ja.vc[head_base + vc_index(i, j + 64 + e, 128)] = (bf16_t)a1[e];
+      }
+      continue;
+    }
+    float cs0[4], cs1[4], oa[4], ob[4];
+    const float* tab = reinterpret_cast<const float*>(ja.rope_tab + (size_t)i * 64 + j);   // (cos, sin) x 4
+    ld4f(tab, cs0);
+    ld4f(tab + 4, cs1);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)], sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
+      oa[e] = a0[e] * c - a1[e] * sn;
+      ob[e] = a1[e] * c + a0[e] * sn;
+    }
+    if (sec == 0) {
+      st4(ja.q + (size_t)r * hd + head * 128 + j, oa);
+      st4(ja.q + (size_t)r * hd + head * 128 + j + 64, ob);
+    } else {
+      st4(ja.kc + head_base + kc_index(i, j, 128), oa);
+      st4(ja.kc + head_base + kc_index(i, j + 64, 128), ob);
+    }
+  }
+}
+
+// h[r, :] = x[r, :] / rms(x[r, :]) * gain, fragment-tiled, one wave per row, d = 512 CH.  The sum of squares is
+// taken in the order of the row-wise norm kernels (thread t of 256 sums chunks t and t + 256, wave totals
+// are added in wave order), so that a row's result does not depend on which path normalised it.
+template <int CH>
+__device__ inline void join_norm_rows(const sl_join& ja, int M) {
+  constexpr int d = 512 * CH;
+  const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+  for (int r = threadIdx.x >> 6; r < M; r += nwaves) {
+    const bf16_t* xr = ja.x + (size_t)r * d;
+    float v[CH][8];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) ld8(xr + (lane + j * 64) * 8, v[j]);
+    float ssq = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float part = 0.f;
+#pragma unroll
+      for (int jj = w; jj < CH; jj += 4)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part += v[jj][e] * v[jj][e];
+      ssq += wave_sum(part);
+    }
+    const float rstd = 1.0f / sqrtf(ssq / (float)d + ja.eps);
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int c8 = lane + j * 64;
+      float g[8], o[8];
+      ld8(ja.gain + c8 * 8, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = v[j][e] * rstd * g[e];
+      st8(ja.h + afrag_index(r, c8 * 8, d), o);
+    }
+  }
+}
+
 // ---- thin launches (at most 32 MB rows, MB = 1 or 2): a pure weight stream ---------------------
 // Below ~300 rows the projection is bound by reading the weights once (2 n k bytes), so the only
 // thing that matters is keeping enough loads in flight.  Here every wave streams its own 64
@@ -232,11 +368,12 @@ __device__ __forceinline__ void stream_landed(Frag (&b)[NBW], Frag (&a)[MB]) {
 // NBW = 32-column blocks per wave: 2 (workgroup tile 256 columns, 8 k-steps in flight) or 1 (128 columns, 16
 // k-steps in flight: the same bytes in flight per wave over twice as many workgroups, for launches whose
 // 256-column tiles would leave CUs without a workgroup).
-template <int MB, int OUT, int NBW>
+// JOIN: the launch also consumes its planes (sl_join; OUT = 0, MB = 1).
+template <int MB, int OUT, int NBW, bool JOIN = false>
 __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_n) {
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_n, sl_join ja) {
   constexpr int DEPTH = 16 / NBW;
   const int M = min(*m_dev, m_upper);
   const int tn = blockIdx.x;
@@ -288,14 +425,30 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   // (DEPTH-1)(NBW+MB) younger loads are outstanding (at most 45: the counter holds 63).
   // The weight loads carry the non-temporal hint: every weight byte is used once per launch, and
   // streaming them past the caches measured 191 -> 165 us on the LM head at M = 16 (6.3 TB/s).
+  // Register-ring contract.  The compiler cannot see that a register is still being written after the load
+  // instruction has issued, so the code must never give it a reason to touch fa / fb between a fetch and the
+  // stream_landed that waits for it:
+  //  * every fetched slot is consumed (no dummy fetches: a destination the compiler counts as dead may be
+  //    handed to another value while the load is still in flight);
+  //  * the ring registers are read-write operands ("+v") of both the load and the wait, i.e. one live value
+  //    from the first fetch to the last MFMA, never dead, never rematerialised;
+  //  * the kernel must not spill (a spill or a copy of a ring register before its wait would read bytes that
+  //    have not landed): the build fails if the compiler reports scratch for this kernel.
   Frag fa[DEPTH][MB], fb[DEPTH][NBW];
+#pragma unroll
+  for (int u = 0; u < DEPTH; ++u) {
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) fb[u][i] = Frag{};
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) fa[u][mb] = Frag{};
+  }
   auto fetch = [&](int step, int slot) {
 #pragma unroll
     for (int i = 0; i < NBW; ++i)
-      asm volatile("global_load_dwordx4 %0, %1, off nt" : "=v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off nt" : "+v"(fb[slot][i]) : "v"(bp[i] + (size_t)step * 64) : "memory");
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
-      asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
+      asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(fa[slot][mb]) : "v"(ap[mb] + (size_t)step * a_step) : "memory");
   };
 #pragma unroll
   for (int u = 0; u < DEPTH; ++u) fetch(u, u);
@@ -352,59 +505,80 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
       }
     }
   }
+  if constexpr (JOIN) {
+    static_assert(OUT == 0 && MB == 1, "the join consumes fp32 planes of a one-block launch");
+    __shared__ int ticket_sh;
+    const int S = gridDim.y;
+    // this workgroup's plane is complete: publish it, take a ticket; the last of the tile's S workgroups goes on
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) ticket_sh = atomicAdd(&ja.tickets[tn], 1);
+    __syncthreads();
+    if (ticket_sh != S - 1) return;
+    __threadfence();
+    const size_t sstride = (size_t)m_upper * ldc;
+    constexpr int BN = 128 * NBW;
+    if (ja.kind == SL_JOIN_ROPE) join_rope(ja, Cf, S, sstride, ldc, M, n0, BN);
+    else if (ja.kind == SL_JOIN_SWIGLU) join_swiglu(ja, Cf, S, sstride, ldc, M, n0, BN, n);
+    else join_residual(ja, Cf, S, sstride, ldc, M, n0, BN, n);
+    if (threadIdx.x == 0) ja.tickets[tn] = 0;
+    if (ja.kind != SL_JOIN_RESIDUAL_NORM) return;
+    // the residual stream's tile is updated: the tile that finishes last normalises the rows
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) ticket_sh = atomicAdd(&ja.tickets[tiles_n], 1);
+    __syncthreads();
+    if (ticket_sh != tiles_n - 1) return;
+    __threadfence();
+    if (n == 4096) join_norm_rows<8>(ja, M);
+    else if (n == 2048) join_norm_rows<4>(ja, M);
+    else if (n == 1024) join_norm_rows<2>(ja, M);
+    else join_norm_rows<1>(ja, M);
+    if (threadIdx.x == 0) ja.tickets[tiles_n] = 0;
+  }
 }
 
-template <int MB, int OUT, int NBW = 2>
+template <int MB, int OUT, int NBW = 2, bool JOIN = false>
 static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
-                         int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
+                         int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc,
+                         const sl_join& ja = sl_join{}) {
   const int tiles_n = sl_cdiv(n, 128 * NBW);
   if ((k / splits) % (16 * (16 / NBW))) return SL_EINVAL;        // whole trips of the register ring
-  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT, NBW>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A, a_tiled,
-                     (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n);
+  if (JOIN && (tiles_n + 1 > kJoinTickets || !ja.tickets)) return SL_EINVAL;
+  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT, NBW, JOIN>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A,
+                     a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n, ja);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }
 
 // ---- host side ------------------------------------------------------------------------------
-// Row-tile height for a launch bounded by mu rows.  128 x 256 tiles at two workgroups per CU
-// measured at least as fast as 256 x 256 at one per CU for every projection shape here.
-#ifndef SL_STREAM_NARROW
-#define SL_STREAM_NARROW 1
-#endif
-#ifndef SL_THIN_MAX
-#define SL_THIN_MAX 32
-#endif
-constexpr int kThinMax = SL_THIN_MAX;   // launches bounded by at most this many rows take the thin (weight-stream) kernels
+constexpr int kThinMax = 32;   // launches bounded by at most this many rows take the thin (weight-stream) kernels
 static int pick_bm(int mu) { return mu <= 32 ? 32 : mu <= 64 ? 64 : 128; }
 
 // Launch plan for a projection bounded by mu rows: which kernel and how many k-splits.
-//  * thin launches (mu <= kThinMax) are weight-stream bound: the k split (and, where enabled, the
-//    128-column tile form) that brings the launch closest to about one workgroup per CU with few
-//    fp32 planes, the partial traffic capped at a fraction of the weight bytes (k >= 16*S*mu);
-//  * thicker launches take the 256 x 256 ring kernel (one workgroup per CU, ~0.8 us per 32-deep
-//    k-tile and wave of workgroups; its half-height variant is chosen inside that launcher) with the
-//    split count that minimises  waves * (k-tiles per split + fixed) * t_tile + bytes of fp32
-//    partials written and read back / 5 TB/s; reductions too short for its ring (fewer than 8
-//    k-tiles per split) go to the 128 x 256 LDS kernel (two per CU, ~1.8 us per 64-deep k-tile).
-//  The thin limit is 32 rows: from 33 rows on the ring's half-height tile is ahead of the two-block
+//  * thin launches (mu <= kThinMax) are weight-stream bound: the k split (and the 128-column tile
+//    form) that brings the launch closest to about one workgroup per CU with few fp32 planes, the
+//    partial traffic capped at a fraction of the weight bytes (k >= 16*S*mu);
+//  * thicker launches take the ring kernel (one workgroup per CU, ~0.8 us per 32-deep k-tile and round
+//    of full-height workgroups; its tile height is fitted to the rows by that launcher, whose cost
+//    model is shared here) with the split count that minimises  rounds * tile cost * (k-tiles per split
+//    + fixed) * t_tile + bytes of fp32 partials written and read back / 5 TB/s; reductions too short
+//    for its ring (fewer than 8 k-tiles per split) go to the 128 x 256 LDS kernel (two per CU, ~1.8 us
+//    per 64-deep k-tile).
+//  The thin limit is 32 rows: from 33 rows on the ring's short tiles are ahead of the two-block
 //  weight-stream kernel (whole step at 64 rows 0.39 -> 0.36 ms, at 33 rows 0.365 -> 0.337 ms).
 struct GemmPlan {
   int thick256;   // 1: gemm_mfma256_kernel
   int splits;
 };
+double slk_ring_cost(int mu, int n, int splits);     // gemm_mfma256.hip
 // swiglu_consumer: the output is the gate|up pair that SwiGLU consumes; an unsplit launch of the
-// 256 x 256 kernel then writes bf16 activations from its epilogue, every other plan writes fp32
+// ring kernel then writes bf16 activations from its epilogue, every other plan writes fp32
 // planes that a second kernel reads back.
-#ifndef SL_PLAN_HALF
-#define SL_PLAN_HALF 1
-#endif
-#ifndef SL_PLAN_HALF_COST
-#define SL_PLAN_HALF_COST 0.6
-#endif
 // Thin launches: 128-column tiles when 256-column ones would give at most 160 workgroups (and the split's
 // reduction is whole trips of the deeper register ring); the workgroup count that results.
 static bool thin_narrow(int n, int k, int splits) {
-  return SL_STREAM_NARROW && sl_cdiv(n, 256) * splits <= 160 && (k / splits) % 256 == 0;
+  return sl_cdiv(n, 256) * splits <= 160 && (k / splits) % 256 == 0;
 }
 static long thin_workgroups(int n, int k, int splits) {
   return (long)sl_cdiv(n, thin_narrow(n, k, splits) ? 128 : 256) * splits;
@@ -433,21 +607,13 @@ static GemmPlan gemm_plan(int mu, int n, int k, bool swiglu_consumer = false) {
   // the 128 x 256 LDS kernel never won where the ring was eligible (LM head at 820 rows: 1.19 ms
   // against 0.79 ms), so it is kept for short reductions only.
   double best = 1e30;
-  const int t256 = sl_cdiv(mu, 256) * sl_cdiv(n, 256), t128 = sl_cdiv(mu, 128) * sl_cdiv(n, 256);
+  const int t128 = sl_cdiv(mu, 128) * sl_cdiv(n, 256);
   for (int s = 1; s <= 8; s *= 2) {
     if (k % (2 * BK * s)) break;
     if (k / (32 * s) < 8) break;
     const double traffic_us = 2.0 * s * (double)mu * n * 4.0 / 5.0e6 * (s > 1 ? 1.0 : 0.5);
     const double fused_us = (double)mu * n / 5.0e6;      // bf16 activations of half the width, written once
-    // the ring launcher runs full-height or half-height tiles, whichever its rounds model prefers: price both
-    const double per_tile = (k / (32.0 * s) + 4.0) * 0.8;
-    double ring_us = sl_cdiv(t256 * s, 256) * per_tile;
-    if (SL_PLAN_HALF) {
-      // (0.6 rather than the measured 0.565-0.585: near-ties go to the full-height tile, whose split plans
-      // measured better where the two were within a few per cent)
-      const double half_us = sl_cdiv(t128 * s, 256) * per_tile * SL_PLAN_HALF_COST;
-      if (half_us < ring_us) ring_us = half_us;
-    }
+    const double ring_us = slk_ring_cost(mu, n, s) * (k / (32.0 * s) + 4.0) * 0.8;
     const double t = ring_us + (swiglu_consumer && s == 1 ? fused_us : traffic_us);
     if (t < best) { best = t; p.thick256 = 1; p.splits = s; }
   }
@@ -487,6 +653,37 @@ static int launch_gemm(hipStream_t s, const void* A, int a_tiled, const void* Wp
   return SL_OK;
 }
 
+// Which kernel a launch bounded by mu rows takes (one decision, shared by the launcher and by
+// sl_linear_plan): kind 0 = weight-stream kernel (rows = 32 or 64, cols = 128 or 256 per workgroup),
+// 1 = ring kernel (rows / tail as its launcher chooses), 2 = 128 x 256 LDS kernel (short reductions).
+struct KernelPick { int kind, rows, cols, tail; };
+void slk_ring_describe(int mu, int n, int splits, int* rows, int* tail);     // gemm_mfma256.hip
+static KernelPick pick_kernel(int mu, int n, int k, int splits, bool f32_out) {
+  if (mu > kThinMax && k / splits >= 256) {
+    const GemmPlan plan = gemm_plan(mu, n, k);
+    const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
+    if (use256) {
+      KernelPick p{1, 256, 256, 0};
+      slk_ring_describe(mu, n, splits, &p.rows, &p.tail);
+      return p;
+    }
+  }
+  // the barrier-free weight stream with one 32-row block (at most 32 rows) or two (33..64 rows, reached
+  // only where the reduction is too short for the ring kernel)
+  if (f32_out && mu <= 32 && thin_narrow(n, k, splits)) return KernelPick{0, 32, 128, 0};
+  if (mu <= 32 && (k / splits) % 128 == 0) return KernelPick{0, 32, 256, 0};
+  if (mu <= 64 && (k / splits) % 128 == 0) return KernelPick{0, 64, 256, 0};
+  return KernelPick{2, pick_bm(mu), 256, 0};
+}
+
+// kind / splits / rows / cols / tail of the launch sl_linear_forward(.., splits = 0, y_f32) would make
+int slk_gemm_describe(int mu, int n, int k, int* kind, int* splits, int* rows, int* cols, int* tail) {
+  const int S = gemm_plan(mu, n, k).splits;
+  const KernelPick p = pick_kernel(mu, n, k, S, true);
+  *kind = p.kind; *splits = S; *rows = p.rows; *cols = p.cols; *tail = p.tail;
+  return SL_OK;
+}
+
 // C = A . Wp^T for a launch bounded by mu rows.  Cf != null: fp32 partials [splits][mu][n];
 // else bf16 rows into Cb through row_map (splits must be 1).
 int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
@@ -495,27 +692,21 @@ int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, con
   if (splits < 1 || n % 32 || k % (2 * BK * splits)) return SL_EINVAL;     // even number of k-tiles per split
   if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;   // 32-bit offsets
   if (!Cf && splits != 1) return SL_EINVAL;
+  const KernelPick p = pick_kernel(mu, n, k, splits, Cf != nullptr);
+  if (p.kind == 1) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
+  if (p.kind == 0 && p.cols == 128)
+    return launch_stream<1, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
+  if (p.kind == 0 && p.rows == 32)
+    return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+              : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
+  if (p.kind == 0)
+    return Cf ? launch_stream<2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
+              : launch_stream<2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
 #define GO(BM)                                                                                             \
   return Cf ? launch_gemm<BM, 2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)          \
             : launch_gemm<BM, 2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc)
-  if (mu > kThinMax && k / splits >= 256) {
-    const GemmPlan plan = gemm_plan(mu, n, k);
-    const bool use256 = plan.splits == splits ? plan.thick256 != 0 : true;
-    if (use256) return slk_gemm_mfma256(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc);
-  }
-  // the barrier-free weight stream with one 32-row block (at most 32 rows) or two (33..64 rows, reached
-  // only where the reduction is too short for the ring kernel)
-  if (Cf && mu <= 32 && thin_narrow(n, k, splits))
-    return launch_stream<1, 0, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc);
-  if (mu <= 32 && (k / splits) % 128 == 0)
-    return Cf ? launch_stream<1, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
-              : launch_stream<1, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
-  if (mu <= 64 && (k / splits) % 128 == 0)
-    return Cf ? launch_stream<2, 0>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, nullptr, nullptr, ldc)
-              : launch_stream<2, 1>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, nullptr, Cb, row_map, ldc);
-  const int bm = pick_bm(mu);
-  if (bm == 32) { GO(32); }
-  if (bm == 64) { GO(64); }
+  if (p.rows == 32) { GO(32); }
+  if (p.rows == 64) { GO(64); }
   GO(128);
 #undef GO
 }

@@ -37,17 +37,20 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK2 = 32;                   // k per stage: one 16x16x32 MFMA k-step
 constexpr int TILE = 256;                 // columns per tile, and rows of the full-height tile
-// Rows per tile TM is 256 or 128.  The half-height tile (waves own 64 x 64, six ring stages of
-// 24 KiB) costs about a tenth more per FLOP (more LDS reads and operand traffic per MFMA) and is
-// used where it saves rounds of workgroups: 384 full tiles on 256 CUs take two rounds, 768 half
-// tiles take three half rounds.
+// Rows per tile TM: any multiple of 32 from 64 to 256, so that a launch can fit its row tiles to the
+// number of active rows (320 rows = two tiles of 160, not two of 256) and latency follows M.  A
+// shorter tile costs more per row (the weight half of the operand traffic and the per-k-tile barrier
+// do not shrink: kTileCost below); its smaller stages allow a deeper ring.
 template <int TM> struct TileCfg {
+  static_assert(TM % 32 == 0 && TM >= 64 && TM <= 256, "tile height");
   static constexpr int A_FR = TM / 16;              // A fragments (32 x 16, 1 KiB) per stage
   static constexpr int STAGE = (A_FR + 16) * 64;    // Frag elements per stage: A, then 16 B fragments
   static constexpr int NA = TM / 32;                // 16-row accumulator blocks per wave (sub-tile TM/2 x 64)
-  static constexpr int HA = NA / 2;                 // ... per half of a k-tile step
-  static constexpr int DMA = TM == 256 ? 4 : 3;     // direct-to-LDS loads per wave and k-tile
-  static constexpr int NS = TM == 256 ? 5 : 6;      // ring stages
+  static constexpr int HL = (NA + 1) / 2;           // ... in the first half of a k-tile step
+  static constexpr int HH = NA / 2;                 // ... in the second half
+  static constexpr int DMA = TM > 128 ? 4 : 3;      // direct-to-LDS loads per wave and k-tile (2 B + 1 or 2 A)
+  static constexpr int NS0 = (160 * 1024) / (STAGE * 16);
+  static constexpr int NS = NS0 > 8 ? 8 : NS0;      // ring stages: all of the 160 KiB LDS (5 .. 8)
 };
 
 // PROBE: one workgroup in the middle of the grid also records shader-clock cycles and 100 MHz
@@ -72,7 +75,7 @@ __device__ __forceinline__ void ring_tile(
     const int32_t* __restrict__ row_map, size_t ldc, const int m0, const int tn, long long* __restrict__ probe,
     const RopeScatter& rs) {
   typedef TileCfg<TM> TC;
-  constexpr int STAGE = TC::STAGE, NA = TC::NA, HA = TC::HA, NS = TC::NS;
+  constexpr int STAGE = TC::STAGE, NA = TC::NA, HL = TC::HL, HH = TC::HH, NS = TC::NS, A_FR = TC::A_FR;
   extern __shared__ Frag lds[];           // [NS stages][A: TM/32 mb x 2 kb | B: 8 nb x 2 kb][64 lanes]
 
   const int n0 = tn * TILE;
@@ -83,26 +86,34 @@ __device__ __forceinline__ void ring_tile(
   const int wm = wave >> 2, wn = wave & 3;          // this wave's (TM/2) x 64 sub-tile
   const int K16 = k / 16, NB32 = n / 32;
 
-  // global -> LDS: wave w moves the two B fragments of column block w and, of A, the two
-  // fragments of row block w (TM = 256) or the one fragment (row block w / 2, k half w % 2) (128).
+  // global -> LDS: wave w moves the two B fragments of column block w and one or two of the A_FR
+  // fragments of A (fragment f = row block f / 2, k half f % 2, at byte f * 1024 of the stage): f = w
+  // for tiles of at most 128 rows, f = 2 w and 2 w + 1 above, taken modulo A_FR (a wave without a
+  // fragment of its own repeats another wave's load, same bytes to the same place, so that every wave
+  // issues the same number of loads per k-tile and one wait count serves all).
   // A is row-major [m_upper, k] (a 32 x 16 fragment is gathered from 32 rows) or already
   // fragment-tiled (one contiguous 1 KiB block per fragment, rows padded to 32).
   const bf16_t* Ab = a_tiled ? A : A + kbeg;
   const int a_kt_stride = a_tiled ? 2 * 512 : BK2, a_kb_stride = a_tiled ? 512 : 16;   // elements
-  uint32_t a_off;
-  const int a_mb = TM == 256 ? wave : wave >> 1;      // 32-row block of the tile this wave fetches
-  const int a_kb = TM == 256 ? 0 : wave & 1;          // ... and its k half (TM = 128: one fragment only)
-  if (a_tiled) {
-    int mbg = m0 / 32 + a_mb;
-    // row tail: stay inside the buffer (blocks past the end read valid blocks; their products are never stored)
-    const int n_mb = (m_upper + 31) / 32;
-    mbg = mbg < n_mb ? mbg : mbg % n_mb;
-    a_off = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u +
-            (uint32_t)(a_kb * a_kb_stride);
-  } else {
-    int row = m0 + a_mb * 32 + (lane & 31);
-    row = row < m_upper ? row : row % m_upper;        // row tail: stay inside the buffer
-    a_off = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8) + (uint32_t)(a_kb * a_kb_stride);
+  constexpr int NAF = TC::DMA - 2;                    // A fragments this wave fetches per k-tile
+  uint32_t a_off[NAF], a_slot[NAF];                   // per-lane element offset, byte offset inside the stage
+#pragma unroll
+  for (int i = 0; i < NAF; ++i) {
+    const int f = (NAF == 2 ? 2 * wave + i : wave) % A_FR;
+    const int a_mb = f >> 1, a_kb = f & 1;
+    a_slot[i] = (uint32_t)f * 1024u;
+    if (a_tiled) {
+      int mbg = m0 / 32 + a_mb;
+      // row tail: stay inside the buffer (blocks past the end read valid blocks; their products are never stored)
+      const int n_mb = (m_upper + 31) / 32;
+      mbg = mbg < n_mb ? mbg : mbg % n_mb;
+      a_off[i] = (((uint32_t)mbg * (uint32_t)K16 + (uint32_t)(kbeg / 16)) * 64u + (uint32_t)lane) * 8u +
+                 (uint32_t)(a_kb * a_kb_stride);
+    } else {
+      int row = m0 + a_mb * 32 + (lane & 31);
+      row = row < m_upper ? row : row % m_upper;        // row tail: stay inside the buffer
+      a_off[i] = (uint32_t)row * (uint32_t)k + (uint32_t)((lane >> 5) * 8) + (uint32_t)(a_kb * a_kb_stride);
+    }
   }
   const Frag* Wf = reinterpret_cast<const Frag*>(Wp) + (size_t)(kbeg / 16) * 64;
   uint32_t b_off;
@@ -123,9 +134,13 @@ __device__ __forceinline__ void ring_tile(
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) Frag*)lds);
   const uint32_t wave_u = __builtin_amdgcn_readfirstlane((uint32_t)wave);
-  const uint32_t lds_a = lds_base + (TM == 256 ? wave_u * 2048u : wave_u * 1024u);          // this wave's A slot(s)
-  const uint32_t lds_b = lds_base + (uint32_t)TC::A_FR * 1024u + wave_u * 2048u;            // ... and B slots
-  const uint32_t a_voff0 = a_off * 2u, a_voff1 = a_voff0 + (uint32_t)a_kb_stride * 2u;   // bytes
+  uint32_t lds_a[NAF], a_voff[NAF];
+#pragma unroll
+  for (int i = 0; i < NAF; ++i) {
+    lds_a[i] = lds_base + __builtin_amdgcn_readfirstlane(a_slot[i]);                      // this wave's A slot(s)
+    a_voff[i] = a_off[i] * 2u;                                                            // bytes
+  }
+  const uint32_t lds_b = lds_base + (uint32_t)A_FR * 1024u + wave_u * 2048u;              // ... and B slots
   const uint32_t b_voff0 = b_off * 16u, b_voff1 = b_voff0 + 1024u;
   const uint64_t a_base = (uint64_t)(uintptr_t)Ab, b_base = (uint64_t)(uintptr_t)Wf;
   const uint32_t a_kt_bytes = (uint32_t)a_kt_stride * 2u;
@@ -140,11 +155,11 @@ __device__ __forceinline__ void ring_tile(
                : "memory", "m0")
   auto issue = [&](int kt, int st) {
     kt = kt < last ? kt : last;                       // past the end: re-fetch the last tile (never used)
-    const uint32_t so = (uint32_t)(st * STAGE) * 16u, la = lds_a + so, lb = lds_b + so;
+    const uint32_t so = (uint32_t)(st * STAGE) * 16u, lb = lds_b + so;
     const uint64_t ga = a_base + (uint64_t)kt * a_kt_bytes, gb = b_base + (uint64_t)kt * (128u * 16u);
-    SL_DMA(a_voff0, ga, la, "");
+    SL_DMA(a_voff[0], ga, lds_a[0] + so, "");
     SL_DMA(b_voff0, gb, lb, " nt");
-    if (TM == 256) SL_DMA(a_voff1, ga, la + 1024u, "");
+    if (NAF == 2) SL_DMA(a_voff[NAF - 1], ga, lds_a[NAF - 1] + so, "");
     SL_DMA(b_voff1, gb, lb + 1024u, " nt");
   };
 #undef SL_DMA
@@ -161,48 +176,55 @@ __device__ __forceinline__ void ring_tile(
   // group g = l / 16, i.e. slot (l % 16) + 32 * (g % 2) of k-block g / 2; a second 16-row half
   // of a block is 16 slots further on
   const int frag_lane = (lane >> 5) * 64 + ((lane >> 4) & 1) * 32 + (lane & 15);
-  const Frag* sa0 = lds + wm * (TM / 64) * 128 + frag_lane;         // 32-row block (TM/64)*wm + i at i * 128
-  const Frag* sb0 = lds + TC::A_FR * 64 + wn * 2 * 128 + frag_lane; // 32-column block 2*wn + i
-  auto a_frag = [&](int st, int a) { return sa0[st * STAGE + (a >> 1) * 128 + (a & 1) * 16]; };
+  const Frag* sa0 = lds + frag_lane;                                 // 32-row block j of the tile at j * 128
+  const Frag* sb0 = lds + A_FR * 64 + wn * 2 * 128 + frag_lane;      // 32-column block 2*wn + i
+  // 16-row block a of this wave's sub-tile is 16-row block wm * NA + a of the tile: half (.. & 1) of 32-row block (.. >> 1)
+  auto a_frag = [&](int st, int a) { const int g = wm * NA + a; return sa0[st * STAGE + (g >> 1) * 128 + (g & 1) * 16]; };
   auto b_frag = [&](int st, int b) { return sb0[st * STAGE + (b >> 1) * 128 + (b & 1) * 16]; };
-  // A fragments of the lower / upper half of the sub-tile's rows, B fragments of two successive k-tiles
-  Frag a_lo[HA], a_hi[HA], b_even[4], b_odd[4];
+  // A fragments of the first HL / the last HH 16-row blocks of the sub-tile, B fragments of two successive k-tiles
+  Frag a_lo[HL], a_hi[HH], b_even[4], b_odd[4];
   // in the order the MFMAs consume them: (a0,b0) (a0,b1) (a0,b2) (a0,b3) (a1,*) ...
-  auto read_tile_head = [&](int st, Frag (&af)[HA], Frag (&bf)[4]) {
+  auto read_tile_head = [&](int st, Frag (&af)[HL], Frag (&bf)[4]) {
     bf[0] = b_frag(st, 0);
     af[0] = a_frag(st, 0);
 #pragma unroll
     for (int b = 1; b < 4; ++b) bf[b] = b_frag(st, b);
 #pragma unroll
-    for (int a = 1; a < HA; ++a) af[a] = a_frag(st, a);
+    for (int a = 1; a < HL; ++a) af[a] = a_frag(st, a);
   };
-  auto read_tile_rest = [&](int st, Frag (&af)[HA]) {
+  auto read_tile_rest = [&](int st, Frag (&af)[HH]) {
 #pragma unroll
-    for (int a = 0; a < HA; ++a) af[a] = a_frag(st, HA + a);
+    for (int a = 0; a < HH; ++a) af[a] = a_frag(st, HL + a);
   };
-  auto mma = [&](int a_base, const Frag (&af)[HA], const Frag (&bf)[4]) {
+  auto mma_lo = [&](const Frag (&af)[HL], const Frag (&bf)[4]) {
 #pragma unroll
-    for (int a = 0; a < HA; ++a)
+    for (int a = 0; a < HL; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[b], af[a], acc[a][b], 0, 0, 0);
+  };
+  auto mma_hi = [&](const Frag (&af)[HH], const Frag (&bf)[4]) {
+#pragma unroll
+    for (int a = 0; a < HH; ++a)
 #pragma unroll
       for (int b = 0; b < 4; ++b)
-        acc[a_base + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[b], af[a], acc[a_base + a][b], 0, 0, 0);
+        acc[HL + a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[b], af[a], acc[HL + a][b], 0, 0, 0);
   };
   // "s_waitcnt vmcnt(DMA*(NS-2))": all but this wave's newest NS-2 tiles have landed (loads
   // complete in order, DMA per tile per wave)
 #define SL_WAIT_RING() asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TC::DMA * (NS - 2)) : "memory")
 
-  // NR LDS reads slotted behind the first MFMAs of a group of 4 * HA, MPR MFMAs apart: the wave's
-  // issue slot is blocked while the MFMA pipe is busy anyway, so the reads issue for free
-#ifndef SL_MPR
-#define SL_MPR 1
-#endif
-#define SL_INTERLEAVE(NR)                                                                  \
+  // NR LDS reads slotted one each behind the first MFMAs of a group of NM: the wave's issue slot is blocked
+  // while the MFMA pipe is busy anyway, so the reads issue for free (short tiles have fewer MFMAs than reads
+  // in their second half: the reads left over follow the group)
+#define SL_INTERLEAVE(NR, NM)                                                              \
   do {                                                                                     \
-    _Pragma("unroll") for (int q_ = 0; q_ < (NR); ++q_) {                                  \
-      __builtin_amdgcn_sched_group_barrier(0x008, SL_MPR, 0);                              \
+    constexpr int nr_ = (NR) < (NM) ? (NR) : (NM);                                         \
+    _Pragma("unroll") for (int q_ = 0; q_ < nr_; ++q_) {                                   \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                   \
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                   \
     }                                                                                      \
-    __builtin_amdgcn_sched_group_barrier(0x008, 4 * HA - (NR) * SL_MPR, 0);                \
+    if constexpr ((NM) > nr_) __builtin_amdgcn_sched_group_barrier(0x008, (NM) - nr_, 0);   \
+    if constexpr ((NR) > nr_) __builtin_amdgcn_sched_group_barrier(0x100, (NR) - nr_, 0);   \
   } while (0)
   long long pc0 = 0, pw0 = 0, pc1 = 0, pw1 = 0, pc2 = 0, pw2 = 0;
   if (PROBE) { pc0 = clock64(); pw0 = wall_clock64(); }
@@ -214,8 +236,8 @@ __device__ __forceinline__ void ring_tile(
   read_tile_head(0, a_lo, b_even);
 
   // One k-tile per step: refill the stage every wave finished reading before the previous
-  // barrier, multiply the lower half of the sub-tile's rows while reading the A fragments of
-  // the upper half, wait for tile kt+1 and publish it, multiply the upper half while reading the
+  // barrier, multiply the first HL 16-row blocks of the sub-tile while reading the A fragments of
+  // the other HH, wait for tile kt+1 and publish it, multiply the upper half while reading the
   // first fragments of tile kt+1.  B fragments alternate between two register sets, hence two steps per trip.
   if (PROBE) { pc1 = clock64(); pw1 = wall_clock64(); }
   int st = 0;                                         // stage of tile kt
@@ -224,14 +246,14 @@ __device__ __forceinline__ void ring_tile(
     const int st_next = st == NS - 1 ? 0 : st + 1;
     issue(kt + NS - 1, st_prev);
     read_tile_rest(st, a_hi);
-    mma(0, a_lo, b_cur);
-    SL_INTERLEAVE(HA);
+    mma_lo(a_lo, b_cur);
+    SL_INTERLEAVE(HH, 4 * HL);
     __builtin_amdgcn_sched_barrier(0);
     SL_WAIT_RING();                                   // this wave's share of tile kt+1 has landed
     __syncthreads();                                  // ... and so has everyone else's
     read_tile_head(st_next, a_lo, b_next);
-    mma(HA, a_hi, b_cur);
-    SL_INTERLEAVE(4 + HA);
+    mma_hi(a_hi, b_cur);
+    SL_INTERLEAVE(4 + HL, 4 * HH);
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
   };
@@ -349,19 +371,19 @@ __device__ __forceinline__ void ring_tile(
     const int head0 = (n0 - sec * hd) >> 7;
     const int tid = threadIdx.x;
 #pragma unroll 1
-    for (int p = 0; p < TM / 128; ++p) {
+    for (int p = 0; p < (TM + 127) / 128; ++p) {
       __syncthreads();                                // operand stages (or the previous pass) are done with
-      if (TM == 128 || wm == p) {
-        const int lrow0 = TM == 128 ? wm * 64 : 0;
 #pragma unroll
-        for (int a = 0; a < NA; ++a)
+      for (int a = 0; a < NA; ++a) {
+        const int trow = wm * (TM / 2) + a * 16;      // this 16-row block's first row inside the tile
+        if (trow / 128 != p) continue;
 #pragma unroll
-          for (int b = 0; b < 4; ++b)
-            *reinterpret_cast<f32x4*>(stage + (lrow0 + a * 16 + row_in) * RSf + wn * 64 + b * 16 + col_in) = acc[a][b];
+        for (int b = 0; b < 4; ++b)
+          *reinterpret_cast<f32x4*>(stage + (trow - p * 128 + row_in) * RSf + wn * 64 + b * 16 + col_in) = acc[a][b];
       }
       if (tid < 128) {
         const int row = m0 + p * 128 + tid;
-        slot_sh[tid] = row < M ? rs.active_idx[row] : -1;
+        slot_sh[tid] = (p * 128 + tid < TM && row < M) ? rs.active_idx[row] : -1;
       }
       __syncthreads();
       if (sec < 2) {
@@ -495,26 +517,60 @@ static int launch_ring(hipStream_t s, const void* A, int a_tiled, const void* Wp
   return SL_OK;
 }
 
-// Tile height of a launch.  Cost model in units of one full tile's time on 256 CUs: a full round
-// of workgroups costs 1, a last partial round 0.9 whatever its fill (measured: the busy CUs of a
-// partial round run at a higher clock), a half-height tile 0.565 of a full one (1.13 per FLOP:
-// LM head 823 -> 925 us when forced).  The half-height tile is taken when it is ahead by more
-// than 5 % (measured where it is: gate|up at 1024 rows 188 -> 176 us, at 768 rows 175 -> 167 us,
-// Q|K|V at 2048 rows 180 -> 169 us).
-#ifndef SL_TM_FORCE
-#define SL_TM_FORCE 0
-#endif
+// ---- tile heights of a launch ------------------------------------------------------------------
+// Cost model in units of one full-height tile's time on 256 CUs: a full round of workgroups costs 1, a
+// last partial round 0.9 whatever its fill (measured: the busy CUs of a partial round run at a higher
+// clock), a tile of TM rows kTileCost[TM / 32] of a full one.
+// A launch runs either uniform tiles of one height (any multiple of 32 from 64 to 256: the smallest
+// number of row tiles that covers the rows, or more and shorter ones where that saves a round of
+// workgroups), or, for many rows, full-height tiles plus ONE half-height tile for a row tail of at
+// most 128 rows.  Fewer, taller tiles win near-ties (less operand traffic per flop).
 static double ring_rounds_cost(int workgroups) {
   return workgroups / 256 + (workgroups % 256 ? 0.9 : 0.0);
 }
-#ifndef SL_TAIL_TILE
-#define SL_TAIL_TILE 1
-#endif
+// measured on the LM head (one row tile of TM rows) and on the layer projections: a k-tile step has a
+// floor of about 0.4 us however short the tile (barrier, LDS latency, the 16 KiB of weights per step)
+static const double kTileCost[9] = {0, 0, 0.51, 0.55, 0.565, 0.70, 0.78, 0.86, 1.0};   // by TM / 32
+
+struct RingChoice {
+  int tail;        // 1: full-height tiles + one half-height tail tile
+  int tm;          // rows per tile (uniform launches)
+  double cost;     // in full-tile rounds
+};
+static RingChoice ring_choice(int mu, int n, int splits) {
+  const int tn = sl_cdiv(n, TILE) * splits;
+  RingChoice best{0, 256, 1e30};
+  const int t_min = sl_cdiv(mu, 256), t_max = sl_cdiv(mu, 64);
+  for (int t = t_min; t <= t_max; ++t) {
+    int tm = (int)sl_align_up((size_t)sl_cdiv(mu, t), 32);
+    if (tm < 64) tm = 64;
+    if (sl_cdiv(mu, tm) != t) continue;              // the same height with fewer tiles was already priced
+    const double c = ring_rounds_cost(t * tn) * kTileCost[tm / 32];
+    if (c < 0.97 * best.cost) best = RingChoice{0, tm, c};
+  }
+  const int t_full = sl_cdiv(mu, 256);
+  const int tail = mu - (t_full - 1) * 256;          // rows of the last full-height tile
+  if (t_full > 1 && tail <= 128) {
+    // work in units of full tiles, spread over 256 CUs like any other launch
+    const double mixed = ring_rounds_cost((int)ceil(((t_full - 1) + kTileCost[4]) * tn));
+    if (mixed < 0.95 * best.cost) best = RingChoice{1, 256, mixed};
+  }
+  return best;
+}
+
+// cost of the cheapest ring launch for (mu rows, n columns, `splits` k-splits), in full-tile rounds
+double slk_ring_cost(int mu, int n, int splits) { return ring_choice(mu, n, splits).cost; }
+void slk_ring_describe(int mu, int n, int splits, int* rows, int* tail) {
+  const RingChoice c = ring_choice(mu, n, splits);
+  *rows = c.tm;
+  *tail = c.tail;
+}
+
 template <int OUT>
 static int launch_ring_tail(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
                             int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc, const RopeScatter& rs) {
   const int tiles_m = sl_cdiv(mu, TILE), tiles_n = sl_cdiv(n, TILE);
-  const size_t sh = (size_t)TileCfg<256>::NS * TileCfg<256>::STAGE * 16;       // the larger of the two rings
+  const size_t sh = 160 * 1024;                                                // the larger of the two rings
   auto kern = gemm_mfma256_tail_kernel<OUT>;
   static unsigned long long lds_ok = 0;
   SL_ALLOW_DYNAMIC_LDS(lds_ok, kern, sh);
@@ -525,32 +581,19 @@ static int launch_ring_tail(hipStream_t s, const void* A, int a_tiled, const voi
   return SL_OK;
 }
 
-// 0: full-height tiles, 1: half-height tiles, 2: full-height tiles + one half-height tail tile
-static int ring_tile_mode(int mu, int n, int splits) {
-  if (SL_TM_FORCE == 128) return 1;
-  if (SL_TM_FORCE == 256) return 0;
-  const int tn = sl_cdiv(n, TILE) * splits;
-  const int t_full = sl_cdiv(mu, 256);
-  const double full = ring_rounds_cost(t_full * tn);
-  const double half = 0.565 * ring_rounds_cost(sl_cdiv(mu, 128) * tn);
-  int mode = half < 0.95 * full ? 1 : 0;
-  const double best = mode ? half : full;
-  const int tail = mu - (t_full - 1) * 256;          // rows of the last full-height tile
-  if (SL_TAIL_TILE && t_full > 1 && tail <= 128) {
-    // work in units of full tiles, spread over 256 CUs like any other launch
-    const double mixed = ring_rounds_cost((int)ceil(((t_full - 1) + 0.565) * tn));
-    if (mixed < 0.95 * best) mode = 2;
-  }
-  return mode;
-}
-
 template <int OUT>
 static int launch256(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                      int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc,
                      const RopeScatter& rs = RopeScatter{}) {
-  switch (ring_tile_mode(mu, n, splits)) {
-    case 1: return launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
-    case 2: return launch_ring_tail<OUT>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+  const RingChoice c = ring_choice(mu, n, splits);
+  if (c.tail) return launch_ring_tail<OUT>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+  switch (c.tm) {
+    case 64: return launch_ring<OUT, 64>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 96: return launch_ring<OUT, 96>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 128: return launch_ring<OUT, 128>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 160: return launch_ring<OUT, 160>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 192: return launch_ring<OUT, 192>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
+    case 224: return launch_ring<OUT, 224>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
     default: return launch_ring<OUT, 256>(s, A, a_tiled, Wp, m_dev, mu, n, k, splits, Cf, Cb, row_map, ldc, rs);
   }
 }

@@ -178,24 +178,6 @@ __global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
 // consecutive columns, so loads and stores are 8 or 16 bytes wide (also in the fragment-tiled
 // layout, where the eight columns starting at a multiple of eight are contiguous) and all loads
 // of a thread are in flight together.  Used when shapes and pointers allow, else the kernels above.
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-
-__device__ inline void ld8(const bf16_t* p, float (&v)[8]) {
-  const bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(p);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = (float)u[e];
-}
-__device__ inline void st8(bf16_t* p, const float (&v)[8]) {
-  bf16x8_t u;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) u[e] = (bf16_t)v[e];
-  *reinterpret_cast<bf16x8_t*>(p) = u;
-}
-__device__ inline void ld8f(const float* p, float (&v)[8]) {
-  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-
 constexpr int kMaxChunks = 4;             // chunks of 8 columns per thread: rows up to 8192 columns
 
 template <bool TILED>
@@ -237,23 +219,11 @@ __global__ __launch_bounds__(kRowThreads) void embed_rmsnorm_vec_kernel(
   }
 }
 
-typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 __device__ inline void ld4(const bf16_t* p, float (&v)[4]) {
   const bf16x4_t u = *reinterpret_cast<const bf16x4_t*>(p);
 #pragma unroll
   for (int e = 0; e < 4; ++e) v[e] = (float)u[e];
 }
-__device__ inline void st4(bf16_t* p, const float (&v)[4]) {
-  bf16x4_t u;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) u[e] = (bf16_t)v[e];
-  *reinterpret_cast<bf16x4_t*>(p) = u;
-}
-__device__ inline void ld4f(const float* p, float (&v)[4]) {
-  const float4 a = *reinterpret_cast<const float4*>(p);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-}
-
 template <bool ADD, bool TILED>
 __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_vec_kernel(bf16_t* x, const float* __restrict__ delta, int S,
                                                                       size_t sstride,

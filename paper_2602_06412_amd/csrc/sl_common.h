@@ -90,6 +90,65 @@ __device__ inline float block_max(float v, float* sh) {
   return r;
 }
 
+// ---- 8- and 16-byte accesses of the row-wise code (bf16 rows, fp32 partial planes) --------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+__device__ inline void ld8(const bf16_t* p, float (&v)[8]) {
+  const bf16x8_t u = *reinterpret_cast<const bf16x8_t*>(p);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)u[e];
+}
+__device__ inline void st8(bf16_t* p, const float (&v)[8]) {
+  bf16x8_t u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) u[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x8_t*>(p) = u;
+}
+__device__ inline void ld8f(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ inline void st4(bf16_t* p, const float (&v)[4]) {
+  bf16x4_t u;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) u[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x4_t*>(p) = u;
+}
+__device__ inline void ld4f(const float* p, float (&v)[4]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+}
+
+// ---- k-split join inside a projection launch ----------------------------------------------------------
+// A projection split over k leaves fp32 partial planes [split][row][col].  Instead of a second kernel that
+// adds the planes and applies the consumer (RoPE + cache scatter, SwiGLU, residual add, RMSNorm), the
+// workgroups of one output tile take a ticket (device-scope atomic after a release fence) when their plane
+// is written; the one that draws the last ticket reads all planes of its tile, in split order (so the sum
+// does not depend on arrival order), and applies the consumer itself.  For launches of at most 32 rows the
+// RMSNorm that follows a residual add runs the same way one level up: the tile whose join finishes last
+// normalises the rows.  Tickets are zero on entry and every launch leaves them zero.
+enum { SL_JOIN_NONE = 0, SL_JOIN_ROPE = 1, SL_JOIN_SWIGLU = 2, SL_JOIN_RESIDUAL = 3, SL_JOIN_RESIDUAL_NORM = 4 };
+struct sl_join {
+  int kind;
+  int32_t* tickets;            // [tiles + 1] device ints, zero on entry
+  // residual add into the packed rows x [m, d] (+ RMSNorm by `gain` into h, fragment-tiled)
+  bf16_t* x;
+  const bf16_t* gain;
+  float eps;
+  bf16_t* h;
+  // SwiGLU of the interleaved gate|up pair into a [m, dff], fragment-tiled
+  bf16_t* a;
+  int dff;
+  // RoPE + scatter of the [q | k | v] sums into q [m, H*128] and the layer's caches (null: queries only)
+  const int32_t* active_idx;
+  const float2* rope_tab;
+  bf16_t* q;
+  bf16_t* kc;
+  bf16_t* vc;
+  int N, n_pad, H;
+};
+constexpr int kJoinTickets = 4096;     // ints in the ticket buffer (tiles of any launch that joins + 1)
+
 // ---- host side -------------------------------------------------------------------------
 extern thread_local int g_sl_last_hip_error;
 #define SL_HIP(call)                                   \
@@ -248,6 +307,7 @@ int slk_gemm_mfma256_probe(hipStream_t s, const void* A, int a_tiled, const void
 int slk_gemm_mfma256_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
                             void* a);
 int slk_gemm_splits(int mu, int n, int k);
+int slk_gemm_describe(int mu, int n, int k, int* kind, int* splits, int* rows, int* cols, int* tail);
 // a_tiled: A is in the fragment-tiled layout (rows padded to 32) instead of row-major
 int slk_gemm_mfma(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n, int k,
                   int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc);

@@ -28,6 +28,28 @@ CASES = [
     (4096, 4096, 16, 13),         # thin launches with few column tiles: the 128-column weight-stream tiles
     (4096, 12288, 32, 32),
     (4160, 2048, 24, 20),         # ... with a column tail
+    # the ring kernel's fitted tile heights (64 .. 256 rows in steps of 32), ragged row counts
+    (4160, 1024, 64, 50),
+    (4160, 1024, 96, 90),
+    (8192, 2048, 160, 150),
+    (8192, 2048, 192, 161),
+    (8192, 2048, 224, 224),
+    (8192, 2048, 256, 255),
+    (12288, 4096, 320, 320),      # two tiles of 160 rows (the LLaDA Q|K|V shape)
+    (24576, 4096, 416, 400),
+    (4096, 12288, 416, 390),
+    (126464, 4096, 160, 131),     # the LM head: 494 column tiles
+    (126464, 4096, 224, 224),
+    # forms the LLaDA-8B projections reach that the cases above do not (tests/test_linear_plan_cpu.py lists them)
+    (12288, 4096, 16, 16),        # weight stream, 128-column tiles, two k-splits
+    (126464, 4096, 16, 16),       # weight stream, 256-column tiles, unsplit (the LM head)
+    (126464, 4096, 40, 40),       # ring, 64-row tile, unsplit
+    (126464, 4096, 96, 80),       # ring, 96-row tile, unsplit
+    (12288, 4096, 170, 165),      # ring, 192-row tile, split
+    (12288, 4096, 390, 387),      # ring, 224-row tiles, split
+    (12288, 4096, 810, 805),      # ring, 192-row tiles, unsplit
+    (12288, 4096, 1140, 1140),    # ring, 256-row tiles, unsplit
+    (12288, 4096, 2578, 2570),    # ring, full-height tiles + half-height tail tile, unsplit
 ]
 
 
@@ -51,6 +73,7 @@ def test_linear_fp32_partials(n, k, m_upper, m, x_tiled):
     B.sl_linear_pack(wd, packed)
     S = B.sl_linear_splits(m_upper, n, k)
     assert S >= 1 and k % (16 * S) == 0
+    print("plan (kernel, splits, tile_rows, tile_cols, tail):", B.sl_linear_plan(m_upper, n, k), flush=True)
     y = torch.full((S, m_upper, n), float("nan"), device=DEV)
     m_dev = torch.tensor([m], dtype=torch.int32, device=DEV)
     xin = B.tile_activations(xd) if x_tiled else xd
@@ -64,7 +87,7 @@ def test_linear_fp32_partials(n, k, m_upper, m, x_tiled):
     assert np.all(np.abs(got - ref) <= _bound(x64, w64, k))
 
 
-@pytest.mark.parametrize("n,k,m_upper,m", CASES[1:9])
+@pytest.mark.parametrize("n,k,m_upper,m", CASES[1:9] + CASES[13:])
 def test_linear_bf16_row_map(n, k, m_upper, m):
     w, x = _inputs(7 * n + k + m, n, k, m_upper)
     wd, xd = w.to(DEV), x.to(DEV)
