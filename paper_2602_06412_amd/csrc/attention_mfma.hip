@@ -534,6 +534,197 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
   }
 }
 
+// Third form, for launches of few rows (late steps of a schedule, where the whole product is a few
+// MFLOP and its time is launches and memory latency): one workgroup = ONE head and 32 queries of one
+// sequence; its four waves split the key tiles (wave w takes tiles w, w + 4, ..), each with the full
+// flash recurrence on its own tiles, and merge their (O, max, sum) through LDS, so there is no
+// partial-result buffer and no merge launch.  K and V fragments go global -> registers directly (the
+// cache layouts make every MFMA fragment of a tile one contiguous 1 KiB block: no LDS staging, no
+// barrier in the loop), the next tile's fragments are requested before the current tile is computed.
+// Same fragment layouts and the same arithmetic per tile as the kernels above (P = bf16 hi + lo),
+// with the exact running max as the reference of the exponentials.
+constexpr int QTT = 32;          // queries per workgroup of the thin kernel
+__global__ __launch_bounds__(256, 1) void attention_thin_kernel(const bf16_t* __restrict__ q,
+                                                                const bf16_t* __restrict__ kc,
+                                                                const bf16_t* __restrict__ vc,
+                                                                const int32_t* __restrict__ active_idx,
+                                                                const int32_t* __restrict__ m_dev, int m_upper, int B,
+                                                                int H, int N, int n_pad, bf16_t* __restrict__ o) {
+  extern __shared__ FragA lds[];             // reused as float: partial O [4 waves][64 lanes][64] | (m, l) [4][64][2]
+  __shared__ int cu[kMaxBatch + 2];
+  constexpr int TILE_F = KT * DH / 8;
+  const int M = min(*m_dev, m_upper);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hh = blockIdx.x;
+  if (B == 1) {
+    if (tid <= 1) cu[tid] = tid ? M : 0;
+  } else if (tid <= B) {
+    int lo = 0, hi = M;
+    const long long key = (long long)tid * N;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if ((long long)active_idx[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    cu[tid] = lo;
+  }
+  __syncthreads();
+  int b = 0, tile = blockIdx.y, row0 = -1, row_end = 0;
+  for (; b < B; ++b) {
+    const int cnt = cu[b + 1] - cu[b];
+    const int nt = (cnt + QTT - 1) / QTT;
+    if (tile < nt) { row0 = cu[b] + tile * QTT; row_end = cu[b + 1]; break; }
+    tile -= nt;
+  }
+  if (row0 < 0) return;                       // uniform across the workgroup
+
+  const size_t head_base = ((size_t)b * H + hh) * n_pad * DH;
+  const FragA* kg = reinterpret_cast<const FragA*>(kc + head_base) + lane;
+  const FragA* vg = reinterpret_cast<const FragA*>(vc + head_base) + (lane >> 5) * DH + (lane & 31);
+  const int n_tiles = n_pad / KT;
+
+  // every wave holds the same 32 queries: lane = query (lane & 31), dims ks*16 + (lane>>5)*8 .. +7
+  const int my_row = row0 + (lane & 31);
+  const int ld_row = my_row < row_end ? my_row : row_end - 1;
+  FragA qf[8];
+  {
+    const bf16_t* qp = q + ((size_t)ld_row * H + hh) * DH + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const FragA*>(qp + ks * 16);
+  }
+  f32x16 acc_o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc_o[i][v] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = 1.4426950408889634f / sqrtf((float)DH);   // log2(e) / sqrt(d_h)
+
+  // fragments of tile t: K block (kb, ks) at (kb*8 + ks)*64 + lane, V^T block (st, mb) at (2*st + lane>>5)*DH + mb*32 + lane&31
+  auto load_kv = [&](int t, FragA (&kf)[16], FragA (&vf)[16]) {
+    const FragA* kt = kg + (size_t)t * TILE_F;
+    const FragA* vt = vg + (size_t)t * TILE_F;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) kf[j] = kt[j * 64];
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) vf[st * 4 + mb] = vt[(2 * st) * DH + mb * 32];
+  };
+  auto tile_step = [&](int t, const FragA (&kf)[16], const FragA (&vf)[16]) {
+    f32x16 sv[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sv[kb][v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) sv[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kb * 8 + ks], qf[ks], sv[kb], 0, 0, 0);
+    }
+    if ((t + 1) * KT > N) {                  // register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
+      const int kbase = t * KT + 4 * (lane >> 5);
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) sv[kb][v] = -INFINITY;
+    }
+    float mx = sv[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sv[kb][v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);     // finite: every tile holds at least one real key
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+    const float mb_ = m_new * sc;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
+    PFrag ph[4], pl[4];
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) {
+        const float pa = __builtin_amdgcn_exp2f(fmaf(sv[kb][v], sc, -mb_));
+        const float pb = __builtin_amdgcn_exp2f(fmaf(sv[kb][v + 1], sc, -mb_));
+        psum += pa + pb;
+        const f32x2 pp = {pa, pb};
+        const uint32_t hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
+        const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
+        const uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
+        ph[2 * kb + (v >> 3)][(v & 7) >> 1] = hw;
+        pl[2 * kb + (v >> 3)][(v & 7) >> 1] = lw;
+      }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st * 4 + mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st * 4 + mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+    }
+  };
+  // this wave's tiles: wave, wave + 4, ..; two register sets, the next tile is requested before the current one is used
+  {
+    FragA k0[16], v0[16], k1[16], v1[16];
+    int t = wave;
+    if (t < n_tiles) load_kv(t, k0, v0);
+    while (t < n_tiles) {
+      if (t + 4 < n_tiles) load_kv(t + 4, k1, v1);
+      tile_step(t, k0, v0);
+      t += 4;
+      if (t >= n_tiles) break;
+      if (t + 4 < n_tiles) load_kv(t + 4, k0, v0);
+      tile_step(t, k1, v1);
+      t += 4;
+    }
+  }
+  // merge the four waves' partial results: wave w finishes dims 32 w .. 32 w + 31
+  float* part_o = reinterpret_cast<float*>(lds);          // [4][64][64]
+  float* part_ml = part_o + 4 * 64 * 64;                  // [4][64][2]
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  {
+    float* po = part_o + ((size_t)wave * 64 + lane) * 64;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<float4*>(po + mb * 16 + 4 * g) =
+            make_float4(acc_o[mb][4 * g], acc_o[mb][4 * g + 1], acc_o[mb][4 * g + 2], acc_o[mb][4 * g + 3]);
+    part_ml[(wave * 64 + lane) * 2] = m_run * sc;           // running max in the exp2 domain (-inf: no tile)
+    part_ml[(wave * 64 + lane) * 2 + 1] = l_tot;
+  }
+  __syncthreads();
+  float mz[4], mx = -INFINITY;
+#pragma unroll
+  for (int z = 0; z < 4; ++z) { mz[z] = part_ml[(z * 64 + lane) * 2]; mx = fmaxf(mx, mz[z]); }
+  float num[16], den = 0.f;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) num[v] = 0.f;
+#pragma unroll
+  for (int z = 0; z < 4; ++z) {
+    const float w = __builtin_amdgcn_exp2f(mz[z] - mx);
+    den = fmaf(w, part_ml[(z * 64 + lane) * 2 + 1], den);
+    const float* pz = part_o + ((size_t)z * 64 + lane) * 64 + wave * 16;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) num[v] = fmaf(w, pz[v], num[v]);
+  }
+  const float inv = 1.0f / den;
+  if (my_row < row_end) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 w4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w4[e] = (__bf16)(num[4 * g + e] * inv);
+      *reinterpret_cast<bf16x4*>(o + afrag_index(my_row, hh * DH + wave * 32 + 8 * g + 4 * (lane >> 5), H * DH)) = w4;
+    }
+  }
+}
+
 // o[row, h, :] = sum_z 2^(m_z - m) O_z / sum_z 2^(m_z - m) l_z over the key splits z
 __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __restrict__ part_o,
                                                               const float* __restrict__ part_ml,
@@ -559,6 +750,13 @@ __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __res
 // ms per step at 512 workgroups, 3.1 -> 2.5 ms at 288), the pipelined one otherwise (34 vs 51 us
 // at 256 workgroups, where the paired kernel would need a key split and a merge to fill the CUs).
 static bool attention_use_pair(int blocks) { return blocks > 256; }
+
+// The thin kernel (32 queries and one head per workgroup, key tiles split over its waves) while its
+// workgroups fit the chip in one round and a wave's share of the keys stays short.
+static bool attention_use_thin(int m_upper, int B, int H, int n_pad) {
+  const int blocks = (sl_cdiv(m_upper, QTT) + B - 1) * H;
+  return blocks <= 512 && n_pad / KT <= 16;
+}
 
 // Key-split plan for a launch bounded by m_upper rows: the keys are split just far enough to
 // give every CU one workgroup of the pipelined kernel (LDS rings, 390 registers per lane: one per
@@ -590,6 +788,15 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
                        const int32_t* m_dev, int m_upper, int B, int H, int N, int n_pad, void* o, float* scratch) {
   if (m_upper <= 0) return SL_OK;
   if (B > kMaxBatch || n_pad % KT) return SL_EINVAL;
+  if (attention_use_thin(m_upper, B, H, n_pad)) {
+    const size_t sh_thin = (size_t)(4 * 64 * 64 + 4 * 64 * 2) * sizeof(float);
+    static unsigned long long lds_thin = 0;
+    SL_ALLOW_DYNAMIC_LDS(lds_thin, attention_thin_kernel, sh_thin);
+    hipLaunchKernelGGL(attention_thin_kernel, dim3(H, sl_cdiv(m_upper, QTT) + B - 1), dim3(256), sh_thin, s, (const bf16_t*)q,
+                       (const bf16_t*)kc, (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad, (bf16_t*)o);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   int tps;
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
   dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
