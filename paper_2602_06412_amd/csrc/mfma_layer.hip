@@ -82,12 +82,6 @@ static inline char* kv_k(const sl_ctx* ctx, int l) {
 }
 static inline char* kv_v(const sl_ctx* ctx, int l) { return kv_k(ctx, ctx->cfg.n_layers) + (size_t)l * ctx->kv_layer_elems * 2; }
 
-#ifndef SL_FUSE_QKV_ROPE
-#define SL_FUSE_QKV_ROPE 1
-#endif
-#ifndef SL_FUSE_RESIDUAL
-#define SL_FUSE_RESIDUAL 1
-#endif
 int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, void* o, void* a, float* f32,
                   float* attn_scratch, const int32_t* active_idx, const int32_t* m_dev, int mu, const void* next_gain) {
   const sl_config& c = ctx->cfg;
@@ -96,7 +90,7 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   const sl_layer_weights& L = ctx->layers[l];
   void* kc_w = ctx->probe_read_only ? nullptr : kv_k(ctx, l);      // read-only probe: queries only
   void* vc_w = ctx->probe_read_only ? nullptr : kv_v(ctx, l);
-  if (SL_FUSE_QKV_ROPE && H % 2 == 0 && slk_gemm_unsplit_thick(mu, 3 * hd, d)) {
+  if (H % 2 == 0 && slk_gemm_unsplit_thick(mu, 3 * hd, d)) {
     // thick launches: Q | K | V projection, RoPE and the scatter into q and the caches in one kernel
     SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma256_qkv_rope(s, h, P.wqkv, m_dev, mu, H, d, active_idx, ctx->n_seq, ctx->n_pad,
                                                              ctx->kv, q, kc_w, vc_w));
@@ -110,7 +104,7 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
                             ctx->n_pad, o, attn_scratch));
   int S = 1;
-  if (SL_FUSE_RESIDUAL && slk_gemm_unsplit_thick(mu, d, hd)) {
+  if (slk_gemm_unsplit_thick(mu, d, hd)) {
     // thick launches: the residual add runs in the projection's epilogue, the norm reads the new x
     SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_mfma256_residual(s, o, P.wo, m_dev, mu, d, hd, x));
     SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_rmsnorm(s, SL_BF16, x, m_dev, mu, d, L.ffn_norm, c.rms_eps, h, 1));
@@ -126,7 +120,7 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));
     SL_RUN(ctx, s, SL_PROF_SWIGLU, slk_swiglu(s, SL_BF16, f32, S, (size_t)mu * 2 * dff, m_dev, mu, dff, a, 1, 1));
   }
-  if (SL_FUSE_RESIDUAL && slk_gemm_unsplit_thick(mu, d, dff)) {
+  if (slk_gemm_unsplit_thick(mu, d, dff)) {
     SL_RUN(ctx, s, SL_PROF_GEMM_DOWN, slk_gemm_mfma256_residual(s, a, P.wdown, m_dev, mu, d, dff, x));
     SL_RUN(ctx, s, SL_PROF_ADD_NORM, slk_rmsnorm(s, SL_BF16, x, m_dev, mu, d, next_gain, c.rms_eps, h, 1));
   } else {

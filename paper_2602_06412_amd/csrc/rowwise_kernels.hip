@@ -178,6 +178,32 @@ __global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
 // consecutive columns, so loads and stores are 8 or 16 bytes wide (also in the fragment-tiled
 // layout, where the eight columns starting at a multiple of eight are contiguous) and all loads
 // of a thread are in flight together.  Used when shapes and pointers allow, else the kernels above.
+// bf16, fragment-tiled output, gate/up interleaved by 32-column blocks: a thread owns eight consecutive
+// output columns (32-byte loads of the gate and the up sums per plane, one 16-byte store); same arithmetic.
+__global__ __launch_bounds__(256) void swiglu_vec_kernel(const float* __restrict__ gu, int S, size_t sstride,
+                                                         const int32_t* __restrict__ m_dev, int m_upper, int dff,
+                                                         bf16_t* __restrict__ a) {
+  const int M = min(*m_dev, m_upper);
+  const int r = blockIdx.y;
+  if (r >= M) return;
+  const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (c >= dff) return;
+  const float* gp = gu + (size_t)r * 2 * dff + (c >> 5) * 64 + (c & 31);
+  float g[8], u[8], o[8];
+  ld8f(gp, g);
+  ld8f(gp + 32, u);
+  for (int sp = 1; sp < S; ++sp) {
+    float t[8], v[8];
+    ld8f(gp + sp * sstride, t);
+    ld8f(gp + sp * sstride + 32, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { g[e] += t[e]; u[e] += v[e]; }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+  st8(a + afrag_index(r, c, dff), o);
+}
+
 constexpr int kMaxChunks = 4;             // chunks of 8 columns per thread: rows up to 8192 columns
 
 template <bool TILED>
@@ -362,7 +388,9 @@ __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __r
   const int b = g / N, i = g - b * N;
   const int half = dh >> 1, hd = H * dh, per_head = half >> 2;
   const float* row = qkv + (size_t)r * 3 * hd;
-  for (int t = threadIdx.x; t < H * per_head; t += blockDim.x) {
+  // gridDim.y workgroups share a row (a launch of few rows would otherwise leave most CUs without a workgroup)
+  const int per_wg = (H * per_head + gridDim.y - 1) / gridDim.y, t_end = min(H * per_head, (int)(blockIdx.y + 1) * per_wg);
+  for (int t = blockIdx.y * per_wg + threadIdx.x; t < t_end; t += blockDim.x) {
     const int hh = t / per_head, j = (t - hh * per_head) * 4;
     const int c0 = hh * dh + j, c1 = c0 + half;
     float q0[4], q1[4], k0[4], k1[4], v0[4], v1[4], cs0[4], cs1[4];
@@ -552,13 +580,11 @@ int slk_embed_rmsnorm(hipStream_t s, int dtype, const void* emb, const int32_t* 
   return SL_OK;
 }
 
-#ifndef SL_WAVE_ROWS_MIN
-#define SL_WAVE_ROWS_MIN 2048
-#endif
+constexpr int kWaveRowsMin = 2048;     // the wave-per-row norm kernel from this many rows on (see add_rmsnorm_wave_kernel)
 int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S, size_t sstride,
                     const int32_t* m_dev, int m_upper, int d, const void* gain, float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
-  if (dtype == SL_BF16 && d == 4096 && m_upper >= SL_WAVE_ROWS_MIN && sstride % 4 == 0 && al16(x) && al16(delta) && al16(gain) &&
+  if (dtype == SL_BF16 && d == 4096 && m_upper >= kWaveRowsMin && sstride % 4 == 0 && al16(x) && al16(delta) && al16(gain) &&
       al16(h)) {
     DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_wave_kernel<true, TL, 8>), dim3(sl_cdiv(m_upper, 4)), dim3(256), 0, s,
                                              (bf16_t*)x, delta, S, sstride, m_dev, m_upper, (const bf16_t*)gain, eps,
@@ -584,7 +610,7 @@ int slk_add_rmsnorm(hipStream_t s, int dtype, void* x, const float* delta, int S
 int slk_rmsnorm(hipStream_t s, int dtype, const void* x, const int32_t* m_dev, int m_upper, int d, const void* gain,
                 float eps, void* h, int tiled) {
   if (m_upper <= 0) return SL_OK;
-  if (dtype == SL_BF16 && d == 4096 && m_upper >= SL_WAVE_ROWS_MIN && al16(x) && al16(gain) && al16(h)) {
+  if (dtype == SL_BF16 && d == 4096 && m_upper >= kWaveRowsMin && al16(x) && al16(gain) && al16(h)) {
     DISPATCH_TILED(tiled, hipLaunchKernelGGL((add_rmsnorm_wave_kernel<false, TL, 8>), dim3(sl_cdiv(m_upper, 4)), dim3(256), 0,
                                              s, (bf16_t*)const_cast<void*>(x), (const float*)nullptr, 1, (size_t)0, m_dev,
                                              m_upper, (const bf16_t*)gain, eps, (bf16_t*)h));
@@ -623,7 +649,8 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
   // thin launches are latency-bound (wide accesses, few instructions win); thick ones are bound by the
   // scattered 2-byte V stores, where the element-wise kernel's many threads per row do better
   if ((m_upper <= 256 || kc == nullptr) && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
-    hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
+    const int per_row = H * (dh / 8), wgs = per_row >= 512 && m_upper <= 256 ? 2 : 1;   // (head, four pairs) items per row
+    hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper, wgs), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
                        m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
     SL_LAUNCH_CHECK();
     return SL_OK;
@@ -647,6 +674,12 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
                int dff, void* a, int tiled, int interleaved) {
   if (m_upper <= 0) return SL_OK;
+  if (dtype == SL_BF16 && tiled && interleaved && dff % 32 == 0 && sstride % 4 == 0 && al16(gu) && al16(a)) {
+    hipLaunchKernelGGL(swiglu_vec_kernel, dim3(sl_cdiv(dff / 8, 256), m_upper), dim3(256), 0, s, gu, S, sstride, m_dev, m_upper,
+                       dff, (bf16_t*)a);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
   DISPATCH_T(dtype, DISPATCH_TILED(tiled, hipLaunchKernelGGL((swiglu_kernel<T, TL>), dim3(sl_cdiv(dff, 256), m_upper),
                                                              dim3(256), 0, s, gu, S, sstride, m_dev, m_upper, dff,
                                                              interleaved, (T*)a)));
