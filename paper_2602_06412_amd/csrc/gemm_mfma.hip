@@ -221,142 +221,6 @@ __device__ __forceinline__ void stream_landed(Frag (&b)[NBW], Frag (&a)[MB]) {
     asm volatile("s_waitcnt vmcnt(%3)" : "+v"(b[0]), "+v"(a[0]), "+v"(a[MB - 1]) : "n"(N));
 }
 
-// ---- consumers run by the workgroup that completes a tile of a k-split launch (see sl_join) ---------
-// All work on the fp32 planes [S][m_upper][ldc] restricted to rows [0, M) and columns [n0, n0 + bn) of the
-// tile, with every thread of the workgroup; plane sums are taken in split order.
-__device__ inline void join_sum8(const float* p, int S, size_t sstride, float (&v)[8]) {
-  ld8f(p, v);
-  for (int sp = 1; sp < S; ++sp) {
-    float t[8];
-    ld8f(p + sp * sstride, t);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += t[e];
-  }
-}
-__device__ inline void join_sum4(const float* p, int S, size_t sstride, float (&v)[4]) {
-  ld4f(p, v);
-  for (int sp = 1; sp < S; ++sp) {
-    float t[4];
-    ld4f(p + sp * sstride, t);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += t[e];
-  }
-}
-
-// x[r, c] <- rnd(x[r, c] + sum); x is [m, n] row-major
-__device__ inline void join_residual(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
-                                     int bn, int n) {
-  const int chunks = bn >> 3;
-  for (int it = threadIdx.x; it < M * chunks; it += blockDim.x) {
-    const int r = it / chunks, c = n0 + (it - r * chunks) * 8;
-    if (c >= n) continue;
-    float dl[8], v[8];
-    join_sum8(planes + (size_t)r * ldc + c, S, sstride, dl);
-    ld8(ja.x + (size_t)r * n + c, v);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = st<bf16_t>::rnd(v[e] + dl[e]);
-    st8(ja.x + (size_t)r * n + c, v);
-  }
-}
-
-// columns are gate / up interleaved by 32-column blocks; a[r, c] = silu(gate) * up, fragment-tiled
-__device__ inline void join_swiglu(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
-                                   int bn, int n) {
-  const int per_row = (bn >> 6) * 4;                     // (gate, up) pairs of the tile x four 8-column chunks
-  for (int it = threadIdx.x; it < M * per_row; it += blockDim.x) {
-    const int r = it / per_row, rem = it - r * per_row, pr = rem >> 2, ch = rem & 3;
-    const int gcol = n0 + 64 * pr + 8 * ch;
-    if (gcol + 32 >= n) continue;
-    float g[8], u[8], o[8];
-    join_sum8(planes + (size_t)r * ldc + gcol, S, sstride, g);
-    join_sum8(planes + (size_t)r * ldc + gcol + 32, S, sstride, u);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
-    st8(ja.a + afrag_index(r, (n0 >> 1) + 32 * pr + 8 * ch, ja.dff), o);
-  }
-}
-
-// columns are [q | k | v], H heads of 128 each; the tile lies inside one of the three (H * 128 is a multiple
-// of the tile width).  RoPE on the unrounded sums (pairs (j, j + 64) of a head, angle from the slot's table
-// row), q to the packed query rows, K and V to the slot's place in the cache layouts.
-__device__ inline void join_rope(const sl_join& ja, const float* planes, int S, size_t sstride, size_t ldc, int M, int n0,
-                                 int bn) {
-  const int hd = ja.H * 128, sec = n0 / hd, head0 = (n0 - sec * hd) >> 7;
-  const int per_row = (bn >> 7) * 16;                    // heads of the tile x sixteen chunks of four rotation pairs
-  if (sec > 0 && ja.kc == nullptr) return;               // read-only probe: queries only
-  for (int it = threadIdx.x; it < M * per_row; it += blockDim.x) {
-    const int r = it / per_row, rem = it - r * per_row, hh = rem >> 4, j = (rem & 15) * 4;
-    const int c0 = n0 + hh * 128 + j;
-    float a0[4], a1[4];
-    join_sum4(planes + (size_t)r * ldc + c0, S, sstride, a0);
-    join_sum4(planes + (size_t)r * ldc + c0 + 64, S, sstride, a1);
-    const int g = ja.active_idx[r];
-    const int b = g / ja.N, i = g - b * ja.N;
-    const int head = head0 + hh;
-    const size_t head_base = ((size_t)b * ja.H + head) * ja.n_pad * 128;
-    if (sec == 2) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        ja.vc[head_base + vc_index(i, j + e, 128)] = (bf16_t)a0[e];
-        ja.vc[head_base + vc_index(i, j + 64 + e, 128)] = (bf16_t)a1[e];
-      }
-      continue;
-    }
-    float cs0[4], cs1[4], oa[4], ob[4];
-    const float* tab = reinterpret_cast<const float*>(ja.rope_tab + (size_t)i * 64 + j);   // (cos, sin) x 4
-    ld4f(tab, cs0);
-    ld4f(tab + 4, cs1);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)], sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
-      oa[e] = a0[e] * c - a1[e] * sn;
-      ob[e] = a1[e] * c + a0[e] * sn;
-    }
-    if (sec == 0) {
-      st4(ja.q + (size_t)r * hd + head * 128 + j, oa);
-      st4(ja.q + (size_t)r * hd + head * 128 + j + 64, ob);
-    } else {
-      st4(ja.kc + head_base + kc_index(i, j, 128), oa);
-      st4(ja.kc + head_base + kc_index(i, j + 64, 128), ob);
-    }
-  }
-}
-
-// h[r, :] = x[r, :] / rms(x[r, :]) * gain, fragment-tiled, one wave per row, d = 512 CH.  The sum of squares is
-// taken in the order of the row-wise norm kernels (thread t of 256 sums chunks t and t + 256, wave totals
-// are added in wave order), so that a row's result does not depend on which path normalised it.
-template <int CH>
-__device__ inline void join_norm_rows(const sl_join& ja, int M) {
-  constexpr int d = 512 * CH;
-  const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
-  for (int r = threadIdx.x >> 6; r < M; r += nwaves) {
-    const bf16_t* xr = ja.x + (size_t)r * d;
-    float v[CH][8];
-#pragma unroll
-    for (int j = 0; j < CH; ++j) ld8(xr + (lane + j * 64) * 8, v[j]);
-    float ssq = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      float part = 0.f;
-#pragma unroll
-      for (int jj = w; jj < CH; jj += 4)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) part += v[jj][e] * v[jj][e];
-      ssq += wave_sum(part);
-    }
-    const float rstd = 1.0f / sqrtf(ssq / (float)d + ja.eps);
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-      const int c8 = lane + j * 64;
-      float g[8], o[8];
-      ld8(ja.gain + c8 * 8, g);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = v[j][e] * rstd * g[e];
-      st8(ja.h + afrag_index(r, c8 * 8, d), o);
-    }
-  }
-}
-
 // ---- thin launches (at most 32 MB rows, MB = 1 or 2): a pure weight stream ---------------------
 // Below ~300 rows the projection is bound by reading the weights once (2 n k bytes), so the only
 // thing that matters is keeping enough loads in flight.  Here every wave streams its own 64
@@ -368,12 +232,11 @@ __device__ inline void join_norm_rows(const sl_join& ja, int M) {
 // NBW = 32-column blocks per wave: 2 (workgroup tile 256 columns, 8 k-steps in flight) or 1 (128 columns, 16
 // k-steps in flight: the same bytes in flight per wave over twice as many workgroups, for launches whose
 // 256-column tiles would leave CUs without a workgroup).
-// JOIN: the launch also consumes its planes (sl_join; OUT = 0, MB = 1).
-template <int MB, int OUT, int NBW, bool JOIN = false>
+template <int MB, int OUT, int NBW>
 __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
     const bf16_t* __restrict__ A, int a_tiled, const bf16_t* __restrict__ Wp, int n, int k, int k_per_split,
     const int32_t* __restrict__ m_dev, int m_upper, float* __restrict__ Cf, bf16_t* __restrict__ Cb,
-    const int32_t* __restrict__ row_map, size_t ldc, int tiles_n, sl_join ja) {
+    const int32_t* __restrict__ row_map, size_t ldc, int tiles_n) {
   constexpr int DEPTH = 16 / NBW;
   const int M = min(*m_dev, m_upper);
   const int tn = blockIdx.x;
@@ -505,48 +368,15 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
       }
     }
   }
-  if constexpr (JOIN) {
-    static_assert(OUT == 0 && MB == 1, "the join consumes fp32 planes of a one-block launch");
-    __shared__ int ticket_sh;
-    const int S = gridDim.y;
-    // this workgroup's plane is complete: publish it, take a ticket; the last of the tile's S workgroups goes on
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) ticket_sh = atomicAdd(&ja.tickets[tn], 1);
-    __syncthreads();
-    if (ticket_sh != S - 1) return;
-    __threadfence();
-    const size_t sstride = (size_t)m_upper * ldc;
-    constexpr int BN = 128 * NBW;
-    if (ja.kind == SL_JOIN_ROPE) join_rope(ja, Cf, S, sstride, ldc, M, n0, BN);
-    else if (ja.kind == SL_JOIN_SWIGLU) join_swiglu(ja, Cf, S, sstride, ldc, M, n0, BN, n);
-    else join_residual(ja, Cf, S, sstride, ldc, M, n0, BN, n);
-    if (threadIdx.x == 0) ja.tickets[tn] = 0;
-    if (ja.kind != SL_JOIN_RESIDUAL_NORM) return;
-    // the residual stream's tile is updated: the tile that finishes last normalises the rows
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) ticket_sh = atomicAdd(&ja.tickets[tiles_n], 1);
-    __syncthreads();
-    if (ticket_sh != tiles_n - 1) return;
-    __threadfence();
-    if (n == 4096) join_norm_rows<8>(ja, M);
-    else if (n == 2048) join_norm_rows<4>(ja, M);
-    else if (n == 1024) join_norm_rows<2>(ja, M);
-    else join_norm_rows<1>(ja, M);
-    if (threadIdx.x == 0) ja.tickets[tiles_n] = 0;
-  }
 }
 
-template <int MB, int OUT, int NBW = 2, bool JOIN = false>
+template <int MB, int OUT, int NBW = 2>
 static int launch_stream(hipStream_t s, const void* A, int a_tiled, const void* Wp, const int32_t* m_dev, int mu, int n,
-                         int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc,
-                         const sl_join& ja = sl_join{}) {
+                         int k, int splits, float* Cf, void* Cb, const int32_t* row_map, size_t ldc) {
   const int tiles_n = sl_cdiv(n, 128 * NBW);
   if ((k / splits) % (16 * (16 / NBW))) return SL_EINVAL;        // whole trips of the register ring
-  if (JOIN && (tiles_n + 1 > kJoinTickets || !ja.tickets)) return SL_EINVAL;
-  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT, NBW, JOIN>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A,
-                     a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n, ja);
+  hipLaunchKernelGGL((gemm_stream_kernel<MB, OUT, NBW>), dim3(tiles_n, splits), dim3(256), 0, s, (const bf16_t*)A,
+                     a_tiled, (const bf16_t*)Wp, n, k, k / splits, m_dev, mu, Cf, (bf16_t*)Cb, row_map, ldc, tiles_n);
   SL_LAUNCH_CHECK();
   return SL_OK;
 }

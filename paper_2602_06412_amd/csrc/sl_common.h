@@ -119,36 +119,6 @@ __device__ inline void ld4f(const float* p, float (&v)[4]) {
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
 }
 
-// ---- k-split join inside a projection launch ----------------------------------------------------------
-// A projection split over k leaves fp32 partial planes [split][row][col].  Instead of a second kernel that
-// adds the planes and applies the consumer (RoPE + cache scatter, SwiGLU, residual add, RMSNorm), the
-// workgroups of one output tile take a ticket (device-scope atomic after a release fence) when their plane
-// is written; the one that draws the last ticket reads all planes of its tile, in split order (so the sum
-// does not depend on arrival order), and applies the consumer itself.  For launches of at most 32 rows the
-// RMSNorm that follows a residual add runs the same way one level up: the tile whose join finishes last
-// normalises the rows.  Tickets are zero on entry and every launch leaves them zero.
-enum { SL_JOIN_NONE = 0, SL_JOIN_ROPE = 1, SL_JOIN_SWIGLU = 2, SL_JOIN_RESIDUAL = 3, SL_JOIN_RESIDUAL_NORM = 4 };
-struct sl_join {
-  int kind;
-  int32_t* tickets;            // [tiles + 1] device ints, zero on entry
-  // residual add into the packed rows x [m, d] (+ RMSNorm by `gain` into h, fragment-tiled)
-  bf16_t* x;
-  const bf16_t* gain;
-  float eps;
-  bf16_t* h;
-  // SwiGLU of the interleaved gate|up pair into a [m, dff], fragment-tiled
-  bf16_t* a;
-  int dff;
-  // RoPE + scatter of the [q | k | v] sums into q [m, H*128] and the layer's caches (null: queries only)
-  const int32_t* active_idx;
-  const float2* rope_tab;
-  bf16_t* q;
-  bf16_t* kc;
-  bf16_t* vc;
-  int N, n_pad, H;
-};
-constexpr int kJoinTickets = 4096;     // ints in the ticket buffer (tiles of any launch that joins + 1)
-
 // ---- host side -------------------------------------------------------------------------
 extern thread_local int g_sl_last_hip_error;
 #define SL_HIP(call)                                   \
