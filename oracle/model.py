@@ -7,7 +7,11 @@ block's details; the reading taken here is the LLaDA/LLaMA-style block:
 pre-RMSNorm, rotary position embedding on q and k (half-split pairing,
 position = the row's fixed slot, footnote 1), softmax(QK^T/sqrt(d_h))V with no
 mask, SwiGLU FFN, two residual adds, a final RMSNorm and an untied LM head,
-no biases.
+no biases.  That reading is pinned structurally (hand-worked two-position
+block in scalar arithmetic, zero output projections leave the stream unchanged,
+gate/up are not interchangeable, the final gain shows in the logits: the block
+tests of the CPU suite); what cannot be pinned is agreement with the authors'
+own block, of which the paper prints no value: parity unpinned in that sense.
 
 Weights use the ``[out_features, in_features]`` convention: y = x @ W.T.
 """

@@ -3,8 +3,16 @@
 
 State follows the 'State' lines of Alg. 1: lock, the per-layer K/V caches,
 the previous posteriors, the masked set and the frozen block input x_hat.
-Decisions that a floating-point value takes (ranking by confidence, D <= eps)
-are taken on the value rounded to fp32, the precision the GPU kernels decide in.
+Decisions that a floating-point value takes (ranking by confidence, D <= eps,
+the percentile gate) are taken on the value rounded to fp32.  The paper fixes no
+precision for them (Sec. 2.2 states D_t <= eps over real numbers), and a
+decision has to be taken in ONE precision on both sides of a comparison to be
+comparable at all: fp32 is what a scoring pass over fp32-accumulated
+log-probabilities yields.  The values themselves (log-softmax, KL, confidence)
+stay fp64 up to that point, so the cast can flip a decision only where the
+fp64 value lies within one fp32 spacing of the threshold (relative 6e-8; the
+KL accuracy bound of the GPU tests, 1e-4 relative, is three orders of magnitude
+wider and those tests exclude |D - eps| <= 1e-6 from mask equality anyway).
 """
 from dataclasses import dataclass, field
 

@@ -34,6 +34,31 @@ f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
 CHECK_LAYERS = (0, 1, 13, 31)
 
 
+def _kv_candidates(cfg, w64, x_row, pos):
+    """The K/V cache rows the precision contract admits for one block input row.
+
+    The normalised input h = rnd(rmsnorm(x)) is x times ONE factor r per row, and x holds bf16 values (8-bit
+    mantissas): for some r a whole group of elements (all with the same mantissa) lands on bf16 rounding
+    boundaries at once, and an fp32 evaluation of r (relative error up to ~3e-7) rounds that group the other
+    way.  About one row in a thousand is affected (measured on the CPU: fp32 against fp64 RMSNorm of bf16 rows at
+    d = 4096, ~45 elements flip together), and then every element of the row's K and V moves by about
+    spacing x |w| x sqrt(45) ~ 1e-3, far beyond one spacing of the small ones.  Both roundings are correct
+    evaluations of the contract, so for such a row the K/V of either side of the boundary is accepted; for all
+    other rows this is the single oracle row."""
+    rnd, H, dh = cfg.rnd, cfg.n_heads, cfg.d_head
+    hn = model.rmsnorm(x_row[None], w64["attn_norm"], cfg.rms_eps)
+    out, seen = [], []
+    for f in (1.0, 1.0 - 3e-7, 1.0 + 3e-7):
+        h = rnd(hn * f)
+        if any(np.array_equal(h, s_) for s_ in seen):
+            continue
+        seen.append(h)
+        k = rnd(model.rope((h @ w64["wk"].T).reshape(1, H, dh), np.array([pos]), cfg.rope_theta))[0]
+        v = rnd((h @ w64["wv"].T).reshape(1, H, dh))[0]
+        out.append((k, v))
+    return out
+
+
 def _run_case(Bn, N, prompts, n_prompt, eps_list, schedule, block, seed, n_masked=None):
     """schedule: per step a list of per-sequence active counts (nested forced locks; a count below the
     number of lockable, i.e. unmasked, positions is met as far as those go).
@@ -86,14 +111,24 @@ def _run_case(Bn, N, prompts, n_prompt, eps_list, schedule, block, seed, n_maske
                         Kc, Vc = f64(kg[b]), f64(vg[b])
                         k_gpu, v_gpu = Kc[i].copy(), Vc[i].copy()
                         want = model.layer_active(cfg, wl64, x_in[j:j + 1], np.array([i]), Kc, Vc)[0]
-                        for got, ref, what in ((k_gpu, Kc[i], "K"), (v_gpu, Vc[i], "V")):
+                        cands = _kv_candidates(cfg, wl64, x_in[j], i)
+                        if len(cands) > 1:
+                            print(f"layer {l} row {r}: normalised input sits on bf16 rounding boundaries, "
+                                  f"{len(cands)} admissible K/V rows", flush=True)
+                        for got, c, what in ((k_gpu, 0, "K"), (v_gpu, 1, "V")):
+                            # one bf16 spacing, plus the fp32 accumulation noise of a 4096-term dot product
+                            # that cancels to nearly zero (2^-24 x sum |h w| ~ 3e-6), against any admissible row
+                            bad = []
+                            for cand in cands:
+                                ref = cand[c]
+                                e = np.abs(got - ref)
+                                bad.append(int((e > bf16_ulp(ref) + 1e-5).sum()))
+                            ref = cands[0][c]
                             e = np.abs(got - ref)
                             a = np.unravel_index(int(np.argmax(e / bf16_ulp(ref))), e.shape)
-                            # one bf16 spacing, plus the fp32 accumulation noise of a 4096-term dot product
-                            # that cancels to nearly zero (2^-24 x sum |h w| ~ 3e-6)
-                            assert np.all(e <= bf16_ulp(ref) + 1e-5), (
+                            assert min(bad) == 0, (
                                 f"layer {l} row {r}: cached {what} {a}: got {got[a]!r} want {ref[a]!r}, "
-                                f"{int((e > bf16_ulp(ref) + 1e-5).sum())} of {e.size} beyond one spacing")
+                                f"{bad} of {e.size} beyond one spacing (per admissible row)")
                         err, rms = np.abs(x_out[j] - want), np.sqrt(np.mean(want ** 2))
                         tol = bf16_ulp(want) + 1.5e-2 * rms
                         assert np.all(err <= tol), f"layer {l} row {r}: block output off by {np.max(err / tol):.2f} x tolerance"
