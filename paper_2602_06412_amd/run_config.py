@@ -72,6 +72,10 @@ def slot_work(shape, N, M):
         "lm_head": {"flops": 2.0 * M * d * V, "bytes": 2.0 * (V * d) + 2.0 * M * (d + V)},
         "attention": {"flops": 4.0 * M * N * hd, "bytes": None},
         "score": {"flops": None, "bytes": 4.0 * M * V},
+        # row-wise kernels, lower bounds: token row in, x and h out; x in, h out (the launch that also adds
+        # k-split partial planes moves 4 bytes per element and plane more)
+        "embed_norm": {"flops": None, "bytes": 6.0 * M * d},
+        "add_norm": {"flops": None, "bytes": 4.0 * M * d},
     }
 
 

@@ -8,7 +8,7 @@ logits of sampled rows are compared directly: no re-synchronisation between laye
 Three steps on a shrinking active set (512 rows, then 288 = one full row tile + a ragged 32-row
 tail, then 72): steps 2 and 3 attend to K/V that earlier steps cached, on both sides.
 
-What is asserted, and why (derivation in the design doc, 'Tolerances'): both sides round the same tensors
+What is asserted, and why: both sides round the same tensors
 to bf16 but sum in fp64 / fp32, so a value near a rounding boundary lands on one or the other
 neighbouring bf16 number, a whole spacing apart; such differences feed the next operator and
 multiply until the two computations differ by the bf16 rounding noise itself
