@@ -568,6 +568,12 @@ static int step_impl(sl_ctx* ctx, void* stream, int32_t* tokens, uint8_t* masked
                                                      block_lo, block_hi, c.temperature, c.seed, t, argmax, drawn, parts));
     write_id = drawn;
   }
+  // the plain rule in Alg. 1's order shares UpdateMASK's launch (one workgroup per sequence does both)
+  if (!c.candidates_pre_update && !(c.gate_percentile > 0.f) && compute_mask == nullptr && block_hi > block_lo && k > 0) {
+    SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_lock(s, tokens, masked, active_idx, cu_active, conf, write_id, B, N, block_lo,
+                                                   block_hi, k, m_upper, lock, kl, eps, t == 1, new_lock));
+    return SL_OK;
+  }
   SL_RUN(ctx, s, SL_PROF_UNMASK, slk_unmask_topk(s, tokens, masked, active_idx, cu_active, conf, write_id, B, N, block_lo, block_hi, k, m_upper));
   if (!c.candidates_pre_update) SL_RUN(ctx, s, SL_PROF_LOCK_RULE, lock_rule());
   return SL_OK;

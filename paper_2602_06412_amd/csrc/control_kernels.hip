@@ -62,12 +62,12 @@ int slk_compact_active(hipStream_t s, const uint8_t* lock, int B, int N, int cap
 // found by an 8-bit-per-pass radix select over LDS histograms; rows whose key reaches it are
 // unmasked.  Confidences are probabilities
 // (non-negative floats), whose bit patterns order like the values.
-__global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ tokens, uint8_t* __restrict__ masked,
-                                                          const int32_t* __restrict__ active_idx,
-                                                          const int32_t* __restrict__ cu_active,
-                                                          const float* __restrict__ conf,
-                                                          const int32_t* __restrict__ argmax, int N, int lo, int hi,
-                                                          int k, int m_upper) {
+__device__ __forceinline__ void unmask_topk_body(int32_t* __restrict__ tokens, uint8_t* masked,
+                                                 const int32_t* __restrict__ active_idx,
+                                                 const int32_t* __restrict__ cu_active,
+                                                 const float* __restrict__ conf,
+                                                 const int32_t* __restrict__ argmax, int N, int lo, int hi,
+                                                 int k, int m_upper) {
   extern __shared__ unsigned long long keys[];     // [hi - lo]
   __shared__ int count;
   __shared__ int hist[256];
@@ -140,6 +140,55 @@ __global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ 
       masked[g] = 0;
     }
   }
+}
+
+__global__ __launch_bounds__(256) void unmask_topk_kernel(int32_t* __restrict__ tokens, uint8_t* __restrict__ masked,
+                                                          const int32_t* __restrict__ active_idx,
+                                                          const int32_t* __restrict__ cu_active,
+                                                          const float* __restrict__ conf,
+                                                          const int32_t* __restrict__ argmax, int N, int lo, int hi,
+                                                          int k, int m_upper) {
+  unmask_topk_body(tokens, masked, active_idx, cu_active, conf, argmax, N, lo, hi, k, m_upper);
+}
+
+// UpdateMASK followed by the candidates + lock rule of the same sequence in one launch (the order of Alg. 1):
+// one workgroup per sequence unmasks its top k, then decides its own active rows on the updated flags and
+// carries its already-locked positions over.  A sequence's rule reads only that sequence's flags, which
+// this workgroup itself has just written (visible after the barrier).  Same decisions as
+// unmask_topk_kernel + lock_rule_kernel; new_lock may alias lock.
+__global__ __launch_bounds__(256) void unmask_lock_kernel(int32_t* __restrict__ tokens, uint8_t* masked,
+                                                          const int32_t* __restrict__ active_idx,
+                                                          const int32_t* __restrict__ cu_active,
+                                                          const float* __restrict__ conf,
+                                                          const int32_t* __restrict__ argmax, int N, int lo, int hi,
+                                                          int k, int m_upper, const uint8_t* lock,
+                                                          const float* __restrict__ kl, const float* __restrict__ eps,
+                                                          int first_step, uint8_t* new_lock) {
+  unmask_topk_body(tokens, masked, active_idx, cu_active, conf, argmax, N, lo, hi, k, m_upper);
+  __threadfence_block();
+  __syncthreads();
+  const int b = blockIdx.x, tid = threadIdx.x;
+  for (int i = tid; i < N; i += 256)
+    if (lock[(size_t)b * N + i]) new_lock[(size_t)b * N + i] = 1;
+  const int r0 = min(cu_active[b], m_upper), r1 = min(cu_active[b + 1], m_upper);
+  const float e = eps[b];
+  for (int r = r0 + tid; r < r1; r += 256) {
+    const int g = active_idx[r];
+    const bool F = !first_step && masked[g] == 0 && kl[r] <= e;
+    new_lock[g] = F ? 1 : 0;
+  }
+}
+
+int slk_unmask_lock(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
+                    const int32_t* cu_active, const float* conf, const int32_t* argmax, int B, int N, int lo, int hi,
+                    int k, int m_upper, const uint8_t* lock, const float* kl, const float* eps, int first_step,
+                    uint8_t* new_lock) {
+  if (hi <= lo || k <= 0 || m_upper <= 0) return SL_EINVAL;      // nothing to unmask: the caller runs the rule alone
+  const size_t sh = (size_t)(hi - lo) * 8;
+  hipLaunchKernelGGL(unmask_lock_kernel, dim3(B), dim3(256), sh, s, tokens, masked, active_idx, cu_active, conf,
+                     argmax, N, lo, hi, k, m_upper, lock, kl, eps, first_step, new_lock);
+  SL_LAUNCH_CHECK();
+  return SL_OK;
 }
 
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,

@@ -226,6 +226,10 @@ int slk_posterior_carry(hipStream_t s, void* store, size_t buf_bytes, size_t row
 int slk_unmask_topk(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
                     const int32_t* cu_active, const float* conf, const int32_t* argmax,
                     int B, int N, int lo, int hi, int k, int m_upper);
+int slk_unmask_lock(hipStream_t s, int32_t* tokens, uint8_t* masked, const int32_t* active_idx,
+                    const int32_t* cu_active, const float* conf, const int32_t* argmax, int B, int N, int lo, int hi,
+                    int k, int m_upper, const uint8_t* lock, const float* kl, const float* eps, int first_step,
+                    uint8_t* new_lock);
 int slk_lock_rule(hipStream_t s, const uint8_t* lock, const uint8_t* masked, const int32_t* active_idx,
                   const int32_t* m_dev, int m_upper, const float* kl, const float* eps, int B, int N,
                   int first_step, uint8_t* new_lock);
