@@ -1,21 +1,23 @@
-// Thick-M variant of the projection GEMM: one 256 x 256 output tile per CU, fed through a
-// deep ring of LDS stages.
+// The ring kernel of the projection GEMM (launches bounded by more than 32 rows): one TM x 256 output tile
+// per workgroup and CU, TM any multiple of 32 from 64 to 256, fed through a ring of LDS stages.
 //
-// Why a second kernel.  Measured on the 128-row-tile kernel: with loads switched off the
-// MFMA loop runs at ~75% of peak, with them at ~45%, although neither HBM nor L2 bandwidth is
+// Why a ring.  Measured on the older 128-row-tile kernel (gemm_mfma.hip): with loads switched off
+// the MFMA loop runs at ~75% of peak, with them at ~45%, although neither HBM nor L2 bandwidth is
 // near its limit.  Every weight byte is touched for the first time exactly once (an L2 miss
 // served from HBM, ~2 us under load), all row tiles sharing the slab wait on that same miss,
 // and with a prefetch distance of one k-tile (~0.4-0.9 us of MFMA work) the latency is exposed
 // on every tile.  This kernel therefore keeps NS-1 k-tiles in flight:
-//  * eight waves (two per SIMD) own 128 x 64 sub-tiles of a 256 x 256 tile;
+//  * eight waves (two per SIMD) own (TM/2) x 64 sub-tiles of the TM x 256 tile;
 //  * BOTH operands are staged in LDS by direct-to-LDS loads (no registers are tied up by
 //    loads in flight; each byte crosses the vector L1 once per CU: 32 B/clk at full MFMA
-//    rate, half of what the 128-row kernel needs);
-//  * k-tiles are 32 deep (32 KiB per stage), five stages fill the 160 KiB LDS, so four tiles
-//    (128 KiB per CU, 32 MiB chip-wide) are in flight while one is multiplied;
-//  * one barrier per k-tile, placed between the two halves of its MFMAs (rows 0..63 / 64..127 of
-//    a wave's sub-tile), so the LDS reads on either side of it are covered by MFMAs; fragments
-//    are read half a tile ahead.
+//    rate for the full-height tile, half of what the 128-row kernel needs);
+//  * k-tiles are 32 deep ((TM + 256) * 64 bytes per stage) and the stages fill the 160 KiB LDS: five
+//    of 32 KiB at TM = 256 (four tiles = 128 KiB per CU in flight while one is multiplied), up to
+//    eight at TM = 64 (for the short tiles a depth beyond four measured no different: their k-tile
+//    step is held at ~0.4 us by the CU's miss path whatever is in flight);
+//  * one barrier per k-tile, placed between the two halves of its MFMAs (the first and the last 16-row
+//    blocks of a wave's sub-tile), so the LDS reads on either side of it are covered by MFMAs;
+//    fragments are read half a tile ahead.
 // Operands land in LDS as 32 x 16 blocks of 1 KiB (activation rows gathered 32 x 16 per
 // instruction, pre-tiled weights copied linearly): element (r, k) of a block sits in the 16-byte
 // slot (r % 32) + 32 * ((k % 16) / 8).
