@@ -374,6 +374,26 @@ def cpu_baseline(shape, w, seed):
             dt, c = one(64)
         chk += c
         single = {"M": 64, "ms": round(dt * 1e3, 1), "rows_per_s": round(64 / dt, 1), "threads": 1}
+    # config 1 (the tiny fp32 model: 2 layers, d = 256, V = 1024, N = 32 + 96, T = 32, three tokens per step): the
+    # oracle's whole run, with the lock rule (eps = 1e-3) and without (eps < 0 = the plain sampler), in seconds
+    c1 = wl.C1
+    cfg1 = Config(c1.n_layers, c1.d_model, c1.n_heads, c1.d_head, c1.d_ff, c1.vocab, c1.mask_id, c1.rms_eps,
+                  c1.rope_theta, c1.storage)
+    w1 = wl.make_weights(c1, seed)
+    w1_64 = {"emb": f64(w1["emb"]), "final_norm": f64(w1["final_norm"]), "lm_head": f64(w1["lm_head"]),
+             "layers": [{k_: f64(v) for k_, v in L.items()} for L in w1["layers"]]}
+    from oracle import sampler
+    prompt1 = wl.prompt_uniform(seed + 1, 32, c1.vocab, c1.mask_id)
+    c1_run = {}
+    for label, eps1 in (("surelock_eps_1e-3", 1e-3), ("plain_sampler", -1.0)):
+        st = sampler.init_state(cfg1, w1_64, prompt1, 96)
+        t0 = time.perf_counter()
+        rows = 0
+        for lo, hi, k_ in sampler.block_schedule(32, 96, 96, 32):
+            rows += int((st.lock == 0).sum())
+            sampler.surelock_step(cfg1, w1_64, st, eps1, lo, hi, k_)
+        c1_run[label] = {"s": round(time.perf_counter() - t0, 3), "active_rows_summed": rows}
+        chk += float(st.lock.sum())
     top = samples[0]
     # one layer + LM head of one sequence -> 32 layers + LM head of eight sequences (labelled: an extrapolation)
     layer_share = 436.2 / (436.2 + 1036.0)            # of the sample's matrix work that is the layer (MFLOP per row)
@@ -382,6 +402,7 @@ def cpu_baseline(shape, w, seed):
             "sample": "one of config 5's eight sequences (N=1024) through one of the 32 layers + LM head + KL/conf/argmax "
                       "scoring, NumPy fp64, all host cores, at M=1024 (value), 544 and 64 active rows; M=64 again on one thread",
             "rows_per_s": top["rows_per_s"], "samples": samples, "single_thread": single,
+            "config1_full_run": c1_run,
             "extrapolated_full_step_ms": round(full_step_ms, 1),
             "extrapolation": "value x 8 sequences x (32 layers + LM head) / (1 layer + LM head) by matrix work; not measured",
             "host_cores": int(cores), "checksum": chk}
