@@ -31,8 +31,9 @@ def test_c2_full_size_sampled_rows():
         rng = np.random.default_rng(0)
         prev_rows = {}
         active = np.arange(N)
-        # 820 and 300 rows: a ragged last row tile (full-height tiles + one half-height tail tile in the LM head)
-        for t, M in ((1, 1024), (2, 820), (3, 300), (4, 16)):
+        # 820 and 300 rows: a ragged last row tile (full-height tiles + one half-height tail tile in the LM head);
+        # 420 and 213 rows: fitted tile heights of 224 and 128 rows under the fused SwiGLU and RoPE epilogues
+        for t, M in ((1, 1024), (2, 820), (3, 420), (4, 300), (5, 213), (6, 16)):
             # the active set only ever shrinks (locks are permanent): nested subsets
             active = active if M == len(active) else active[wl.active_positions(50 + M, len(active), M)]
             lock = dev(wl.lock_mask_from_active(N, active))
