@@ -349,6 +349,34 @@ __global__ __launch_bounds__(256, 2) void gemm_stream_kernel(
   static_assert(DEPTH <= 16, "last trip is written out for 16 slots");
 
   const int col_in = lane & 31, row_in = 4 * (lane >> 5);
+  if constexpr (OUT == 2) {
+    // SwiGLU of an unsplit gate|up launch in the epilogue (columns interleaved by 32-column blocks: gate
+    // c .. c+31, then up c .. c+31; n = 2 d_ff, ldc = d_ff, Cb = the fragment-tiled activation matrix a).
+    // With two blocks per wave a lane holds gate and up of its column; with one, waves 0/1 and 2/3 of the
+    // workgroup hold the gate and the up block of a pair, and the up values cross through LDS.
+    static_assert(MB == 1, "thin launches only");
+    __shared__ float up_sh[NBW == 1 ? 2 * 16 * 64 : 1];
+    if constexpr (NBW == 1) {
+      if (wave & 1) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) up_sh[((wave >> 1) * 16 + v) * 64 + lane] = acc[0][0][v];
+      }
+      __syncthreads();
+      if (wave & 1) return;
+    }
+    const int pair = NBW == 1 ? (n0 >> 6) + (wave >> 1) : (n0 >> 6) + wave;      // which 32 output columns
+    const int c = pair * 32 + col_in;
+    if (c >= (n >> 1)) return;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = 8 * (v / 4) + row_in + (v % 4);
+      if (row >= M) continue;
+      const float g = acc[0][0][v];
+      const float u = NBW == 1 ? up_sh[((wave >> 1) * 16 + v) * 64 + lane] : acc[0][NBW - 1][v];
+      Cb[afrag_index(row, c, (int)ldc)] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+    }
+    return;
+  }
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
@@ -504,6 +532,29 @@ static KernelPick pick_kernel(int mu, int n, int k, int splits, bool f32_out) {
   if (mu <= 32 && (k / splits) % 128 == 0) return KernelPick{0, 32, 256, 0};
   if (mu <= 64 && (k / splits) % 128 == 0) return KernelPick{0, 64, 256, 0};
   return KernelPick{2, pick_bm(mu), 256, 0};
+}
+
+// Thin unsplit gate|up projection with SwiGLU in its epilogue: a [mu <= 32 rows, dff] bf16, fragment-tiled.
+// Returns SL_EINVAL when the plan for this launch is not the unsplit weight-stream kernel (the caller then
+// runs the projection into fp32 planes and the SwiGLU kernel).
+int slk_gemm_stream_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
+                           void* a) {
+  const int n = 2 * dff;
+  if (mu <= 0 || mu > kThinMax || dff % 32 || k % (2 * BK)) return SL_EINVAL;
+  if ((size_t)n * k >= ((size_t)1 << 31) * 8 || (size_t)mu * k >= ((size_t)1 << 32)) return SL_EINVAL;
+  if (gemm_plan(mu, n, k, true).splits != 1) return SL_EINVAL;
+  const KernelPick p = pick_kernel(mu, n, k, 1, true);
+  if (p.kind != 0 || p.rows != 32) return SL_EINVAL;
+  if (p.cols == 128) return launch_stream<1, 2, 1>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
+  return launch_stream<1, 2, 2>(s, A, 1, Wp, m_dev, mu, n, k, 1, nullptr, a, nullptr, (size_t)dff);
+}
+// 1 if slk_gemm_stream_swiglu takes this launch
+int slk_gemm_stream_swiglu_ok(int mu, int dff, int k) {
+  const int n = 2 * dff;
+  if (mu <= 0 || mu > kThinMax || dff % 32 || k % (2 * BK)) return 0;
+  if (gemm_plan(mu, n, k, true).splits != 1) return 0;
+  const KernelPick p = pick_kernel(mu, n, k, 1, true);
+  return p.kind == 0 && p.rows == 32;
 }
 
 // kind / splits / rows / cols / tail of the launch sl_linear_forward(.., splits = 0, y_f32) would make

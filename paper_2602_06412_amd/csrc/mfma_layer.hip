@@ -115,6 +115,9 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
   }
   if (slk_gemm_unsplit_thick(mu, 2 * dff, d)) {
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma256_swiglu(s, h, P.wgu, m_dev, mu, dff, d, a));
+  } else if (slk_gemm_stream_swiglu_ok(mu, dff, d)) {
+    // thin launches whose gate|up projection runs unsplit: SwiGLU in the weight-stream kernel's epilogue
+    SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_stream_swiglu(s, h, P.wgu, m_dev, mu, dff, d, a));
   } else {
     S = slk_gemm_splits_gate_up(mu, 2 * dff, d);
     SL_RUN(ctx, s, SL_PROF_GEMM_GATE_UP, slk_gemm_mfma(s, h, 1, P.wgu, m_dev, mu, 2 * dff, d, S, f32, nullptr, nullptr, 2 * (size_t)dff));

@@ -273,6 +273,9 @@ int slk_attention_generic(hipStream_t s, int dtype, const void* q, const void* k
 // gemm_mfma.hip
 int slk_pack_weight(hipStream_t s, const void* W, int n, int k, void* P, int nb_off, int nb_stride);
 int slk_gemm_unsplit_thick(int mu, int n, int k);
+int slk_gemm_stream_swiglu_ok(int mu, int dff, int k);
+int slk_gemm_stream_swiglu(hipStream_t s, const void* A, const void* Wp, const int32_t* m_dev, int mu, int dff, int k,
+                           void* a);
 int slk_gemm_splits_gate_up(int mu, int n, int k);
 // gate|up projection with interleaved 32-column blocks (gate j, up j, gate j+1, ..) and SwiGLU in the
 // epilogue: a[row, c] = silu(g) * u as bf16 in the fragment-tiled layout; no k-split

@@ -44,6 +44,8 @@ C3 = Shape("C3-llada8b-32layer", 32, 4096, 32, 128, 12288, 126464, "bf16")
 # Reduced shapes for parity tests the oracle finishes in seconds (several tiles + ragged tails).
 S_BF16 = Shape("small-bf16", 2, 512, 4, 128, 1536, 4160, "bf16")
 S_BF16_WIDE = Shape("small-bf16-wide", 1, 1024, 8, 128, 2816, 8256, "bf16")
+# a very wide FFN (2 d_ff = 41472 columns): thin gate|up launches take the 256-column form of the weight-stream kernel
+S_BF16_FFN = Shape("small-bf16-wide-ffn", 1, 256, 2, 128, 20736, 1056, "bf16")
 # bf16 with 64-wide heads: runs on the shape-generic kernels instead of the MFMA ones
 S_BF16_H64 = Shape("small-bf16-h64", 2, 256, 4, 64, 688, 1024, "bf16")
 
