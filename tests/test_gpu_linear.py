@@ -50,6 +50,10 @@ CASES = [
     (12288, 4096, 810, 805),      # ring, 192-row tiles, unsplit
     (12288, 4096, 1140, 1140),    # ring, 256-row tiles, unsplit
     (12288, 4096, 2578, 2570),    # ring, full-height tiles + half-height tail tile, unsplit
+    # 16 row tiles and more: an XCD walks its column tiles in bands of four (25 column tiles: one whole band,
+    # seven of the eight XCDs with a tile short; 49: a whole band and a ragged one of three)
+    (6400, 512, 4200, 4190),
+    (12544, 512, 4100, 4099),
 ]
 
 
