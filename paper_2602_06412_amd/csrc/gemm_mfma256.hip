@@ -582,8 +582,14 @@ static RingChoice ring_choice(int mu, int n, int splits) {
   const int t_full = sl_cdiv(mu, 256);
   const int tail = mu - (t_full - 1) * 256;          // rows of the last full-height tile
   if (t_full > 1 && tail <= 128) {
-    // work in units of full tiles, spread over 256 CUs like any other launch
-    const double mixed = ring_rounds_cost((int)ceil(((t_full - 1) + kTileCost[4]) * tn));
+    // Every workgroup takes a CU's one slot whatever its tile height, so the rounds are those of the
+    // workgroup COUNT; a CU's share is a mix of full tiles and half tiles in the launch's proportion.
+    // (Pricing the launch by its work alone, as if the short tiles packed into the gaps, chose this form
+    // for 640 rows x 96 column tiles, 288 workgroups in two rounds: 145 us where five 128-row tiles per
+    // column tile take 117 us.)
+    // (one round: the launch lasts as long as its full tiles do)
+    const double half_share = t_full * tn > 256 ? 1.0 / t_full : 0.0;
+    const double mixed = ring_rounds_cost(t_full * tn) * (1.0 - half_share * (1.0 - kTileCost[4]));
     if (mixed < 0.95 * best.cost) best = RingChoice{1, 256, mixed};
   }
   return best;

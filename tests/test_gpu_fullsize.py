@@ -102,14 +102,16 @@ def test_c2_probe_of_all_rows_reproduces_the_step():
         sess.close()
 
 
-def test_c2_tail_tile_launches_agree_with_plain_ones():
-    """2600 active rows of 3 x 1024 slots: with m_upper = 2600 the Q|K|V (fused RoPE + scatter) and
-    gate|up (fused SwiGLU) launches run full-height row tiles plus one half-height tail tile, with
-    m_upper = 3072 (same true M) plain full-height tiles.  An output element accumulates its k-tiles in
-    the same order whatever the tile, so the K/V cache must agree bit for bit.  The down projection
-    is split over k at 2600 rows and not at 3072 (another fp32 summation order), so the logits may
-    differ by a rounding here and there, not more.  The values themselves are anchored by the oracle
-    in the tests above.  A launch repeated with the same bound must reproduce itself exactly."""
+@pytest.mark.parametrize("M", [2600, 1140])
+def test_c2_fitted_tile_launches_agree_with_full_height_ones(M):
+    """M active rows of 3 x 1024 slots: with m_upper = M the Q|K|V (fused RoPE + scatter) and gate|up (fused
+    SwiGLU) launches run row tiles fitted to M rows (2600: twelve tiles of 224 rows; 1140: gate|up as four
+    full-height tiles plus one half-height tail tile, Q|K|V as five full-height ones), with m_upper = 3072
+    (same true M) twelve full-height tiles.  An output element accumulates its k-tiles in the same order
+    whatever the tile, so the K/V cache must agree bit for bit.  The Out and down projections are split over
+    k differently under the two bounds (another fp32 summation order), so the logits may differ by a rounding
+    here and there, not more.  The values themselves are anchored by the oracle in the tests above.  A launch
+    repeated with the same bound must reproduce itself exactly."""
     shape, N, Bn = wl.C2, 1024, 3
     w = wl.make_weights(shape, seed=0, device="cuda", emb_std=1.0)
     sess = B.Session(shape, w, Bn, N)
@@ -119,22 +121,23 @@ def test_c2_tail_tile_launches_agree_with_plain_ones():
         eps = dev(np.full(Bn, 1e-3, dtype=np.float32))
         zero = torch.zeros(R, dtype=torch.uint8, device=DEV)
         sess.step(tokens, zero.clone(), zero, eps, 1, 0, N, 0, m_upper=R, new_lock=torch.zeros_like(zero))
-        active = wl.active_positions(77, R, 2600)
+        active = wl.active_positions(77, R, M)
         lock = dev(wl.lock_mask_from_active(R, active))
         rows = torch.as_tensor(active, device=DEV, dtype=torch.long)
         out = []
-        for m_upper in (2600, 2600, R):
+        for m_upper in (M, M, R):
             sess.step(tokens, zero.clone(), lock, eps, 2, 0, N, 0, m_upper=m_upper, new_lock=torch.zeros_like(zero))
             torch.cuda.synchronize()
-            assert int(sess.cu_active[-1].item()) == 2600
-            out.append((sess.logits_view(2)[rows].clone(), sess.kl[:2600].clone(), sess.conf[:2600].clone(),
-                        sess.argmax[:2600].clone(), sess.kv.clone()))
+            assert int(sess.cu_active[-1].item()) == M
+            out.append((sess.logits_view(2)[rows].clone(), sess.kl[:M].clone(), sess.conf[:M].clone(),
+                        sess.argmax[:M].clone(), sess.kv.clone()))
         a, a2, b = out
         assert torch.equal(a[0].view(torch.int16), a2[0].view(torch.int16)) and torch.equal(a[4], a2[4])
         assert torch.equal(a[1], a2[1]) and torch.equal(a[2], a2[2]) and torch.equal(a[3], a2[3])
         assert torch.equal(a[4], b[4]), "K/V cache must not depend on the tile heights"
         dz = (a[0].float() - b[0].float()).abs()
-        assert float(dz.max()) <= 0.0625 and float((dz > 0).float().mean()) < 0.05
+        # measured: 3-5 % of the logits land on a neighbouring bf16 value, none further than one spacing at |z| < 8
+        assert float(dz.max()) <= 0.0625 and float((dz > 0).float().mean()) < 0.10
         assert torch.allclose(a[2], b[2], rtol=0.1)              # a one-spacing change of the top logit moves max p by a few %
         assert float(a[0].float().abs().mean()) > 0.1
     finally:

@@ -21,7 +21,7 @@ CASES = [
     (4160, 512, 96, 70),
     (4160, 1024, 320, 300),       # one full 256-row tile and a ragged one
     (2048, 2048, 384, 200),       # the second row tile lies wholly beyond the device-side row count
-    (32768, 512, 300, 290),       # 128 column tiles: one full-height row tile + a half-height tail tile
+    (32768, 512, 300, 290),       # 128 column tiles, two row tiles
     (12288, 1536, 704, 700),
     (8192, 4096, 1024, 1000),
     (4096, 12288, 1024, 1024),
@@ -49,7 +49,8 @@ CASES = [
     (12288, 4096, 390, 387),      # ring, 224-row tiles, split
     (12288, 4096, 810, 805),      # ring, 192-row tiles, unsplit
     (12288, 4096, 1140, 1140),    # ring, 256-row tiles, unsplit
-    (12288, 4096, 2578, 2570),    # ring, full-height tiles + half-height tail tile, unsplit
+    (12288, 4096, 2578, 2570),    # ring, eleven row tiles, unsplit
+    (24576, 4096, 1140, 1135),    # ring, full-height tiles + half-height tail tile, unsplit (480 workgroups)
     # 16 row tiles and more: an XCD walks its column tiles in bands of four (25 column tiles: one whole band,
     # seven of the eight XCDs with a tile short; 49: a whole band and a ragged one of three)
     (6400, 512, 4200, 4190),
