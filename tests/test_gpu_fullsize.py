@@ -39,8 +39,15 @@ def test_c2_full_size_sampled_rows():
             lock = dev(wl.lock_mask_from_active(N, active))
             tokens = dev(tokens_np, torch.int32)
             print(f"C2 full-size step t={t} M={M}", flush=True)
+            k_before, v_before = (x.clone() for x in sess.kv_read(0))
             sess.step(tokens, zero.clone(), lock, eps, t, 0, N, 0, m_upper=M, new_lock=torch.zeros_like(lock))
             torch.cuda.synchronize()
+            # the cache rows of locked slots are never written: byte-identical across the step, although the
+            # scatter of the active rows' V writes whole 16-byte units that hold locked slots too
+            locked = torch.as_tensor(np.setdiff1d(np.arange(N), active), device=DEV, dtype=torch.long)
+            k_after, v_after = sess.kv_read(0)
+            assert torch.equal(k_after[0, locked].view(torch.int16), k_before[0, locked].view(torch.int16))
+            assert torch.equal(v_after[0, locked].view(torch.int16), v_before[0, locked].view(torch.int16))
             assert int(sess.cu_active[-1].item()) == M
             assert np.array_equal(sess.active_idx[:M].cpu().numpy(), active)
             # oracle: block output of the active rows (tokens index w64['emb'] by position)
