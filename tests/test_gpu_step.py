@@ -360,3 +360,58 @@ def test_m_upper_too_small_is_contained():
         assert len(changed) > 0 and set(changed) <= set(idx_ok[:mu].tolist())
     finally:
         sess.close()
+
+
+@pytest.mark.parametrize("shape", [wl.C1, wl.S_BF16])
+def test_sequences_without_active_rows(shape):
+    """Degenerate batches: a sequence whose positions are all locked contributes no row (its neighbour's
+    logits are bit for bit those of the same sequence stepped alone, with the same row bound), and a step
+    in which nothing is active at all computes nothing, unmasks nothing and returns the lock mask unchanged."""
+    w = weights_to_device(wl.make_weights(shape, seed=2))
+    N, mu = 96, 48
+    eps2, eps1 = dev(np.array([1e-3, 1e-3], dtype=np.float32)), dev(np.array([1e-3], dtype=np.float32))
+    tok = np.stack([wl.prompt_uniform(5 + b, N, shape.vocab, shape.mask_id) for b in range(2)])
+    lock = np.ones((2, N), dtype=np.uint8)
+    act = np.sort(np.random.default_rng(1).choice(N, size=37, replace=False))
+    lock[1, act] = 0                                              # sequence 0: nothing active; sequence 1: 37 rows
+    masked = np.zeros((2, N), dtype=np.uint8); masked[1, act[-5:]] = 1
+    s2, s1 = B.Session(shape, w, 2, N), B.Session(shape, w, 1, N)
+    try:
+        # step 1: all of sequence 1 (its K/V and first posteriors), nothing of sequence 0, under the same row bound
+        # in both sessions, so that both run the same launches
+        z8 = torch.zeros(2 * N, dtype=torch.uint8, device=DEV)
+        lock_first = torch.cat([torch.ones(N, dtype=torch.uint8, device=DEV), z8[:N]])
+        s2.step(dev(tok.reshape(-1), torch.int32), z8.clone(), lock_first, eps2, 1, 0, N, 0, m_upper=N)
+        s1.step(dev(tok[1], torch.int32), z8[:N].clone(), z8[:N].clone(), eps1, 1, 0, N, 0, m_upper=N)
+        torch.cuda.synchronize()
+        assert s2.cu_active.cpu().tolist() == [0, 0, N]
+        assert torch.equal(s2.logits_view(1)[N:], s1.logits_view(1))
+        t2, m2 = dev(tok.reshape(-1), torch.int32), dev(masked.reshape(-1))
+        t1, m1 = dev(tok[1], torch.int32), dev(masked[1])
+        nl2 = torch.full((2 * N,), 9, dtype=torch.uint8, device=DEV)
+        nl1 = torch.full((N,), 9, dtype=torch.uint8, device=DEV)
+        s2.step(t2, m2, dev(lock.reshape(-1)), eps2, 2, 0, N, 2, m_upper=mu, new_lock=nl2)
+        s1.step(t1, m1, dev(lock[1]), eps1, 2, 0, N, 2, m_upper=mu, new_lock=nl1)
+        torch.cuda.synchronize()
+        assert s2.cu_active.cpu().tolist() == [0, 0, 37] and s1.cu_active.cpu().tolist() == [0, 37]
+        assert np.array_equal(s2.active_idx[:37].cpu().numpy(), N + act)
+        rows2 = torch.as_tensor(N + act, device=DEV, dtype=torch.long)
+        rows1 = torch.as_tensor(act, device=DEV, dtype=torch.long)
+        assert torch.equal(s2.logits_view(2)[rows2], s1.logits_view(2)[rows1])
+        assert torch.equal(s2.kl[:37], s1.kl[:37]) and torch.equal(s2.argmax[:37], s1.argmax[:37])
+        assert torch.equal(nl2[N:], nl1) and torch.all(nl2[:N] == 1)
+        assert torch.equal(t2[N:], t1) and torch.equal(m2[N:], m1) and torch.equal(t2[:N].cpu(), torch.as_tensor(tok[0], dtype=torch.int32))
+        assert int(m1.sum().item()) == 3                          # two of the five masked slots were unmasked
+        # nothing active at all
+        all_locked = torch.ones(2 * N, dtype=torch.uint8, device=DEV)
+        kv_before, post_before = s2.kv.clone(), s2.post.clone()
+        t3, m3 = t2.clone(), m2.clone()
+        nl3 = torch.full((2 * N,), 9, dtype=torch.uint8, device=DEV)
+        s2.step(t3, m3, all_locked, eps2, 3, 0, N, 2, m_upper=mu, new_lock=nl3)
+        torch.cuda.synchronize()
+        assert s2.cu_active.cpu().tolist() == [0, 0, 0]
+        assert torch.all(nl3 == 1) and torch.equal(t3, t2) and torch.equal(m3, m2)
+        assert torch.equal(s2.kv, kv_before) and torch.equal(s2.post, post_before)
+    finally:
+        s2.close()
+        s1.close()
