@@ -48,6 +48,11 @@ typedef enum sl_status {
 
 enum { SL_F32 = 0, SL_BF16 = 1 };
 
+/* Largest batch (sequences stepped together): the attention kernels keep the row range of every sequence in
+ * LDS.  sl_kv_cache_bytes / sl_kv_cache_bind and the stand-alone calls that take a batch return SL_EINVAL
+ * beyond it. */
+enum { SL_MAX_BATCH = 255 };
+
 /* Model shape.  The block is the pre-RMSNorm / RoPE / SwiGLU block with multi-head
  * attention (H_kv = H), the one whose GEMMs the paper's algorithmic-FLOP count
  * lists (Sec. 2.4): Q, K, V, Out projections and a three-matrix FFN. */

@@ -143,7 +143,7 @@ static size_t rope_tab_bytes(const sl_config& c, int n_pad) {
 }
 
 extern "C" int sl_kv_cache_bytes(const sl_ctx* ctx, int32_t batch, int32_t n_seq, size_t* out) {
-  if (!ctx || !out || batch < 1 || n_seq < 1) return SL_EINVAL;
+  if (!ctx || !out || batch < 1 || batch > SL_MAX_BATCH || n_seq < 1) return SL_EINVAL;
   const sl_config& c = ctx->cfg;
   const int n_pad = (int)sl_align_up(n_seq, 64);
   const size_t layer = (size_t)batch * c.n_heads * n_pad * c.d_head;

@@ -25,7 +25,7 @@ typedef bf16x8 FragA;       // one lane's 16-byte share of an MFMA operand fragm
 constexpr int QT = 128;          // queries per workgroup
 constexpr int KT = 64;           // slots per K/V tile
 constexpr int DH = 128;
-constexpr int kMaxBatch = 255;
+constexpr int kMaxBatch = SL_MAX_BATCH;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

@@ -57,6 +57,9 @@ def test_size_queries_and_call_order_without_gpu():
         out = C.c_size_t()
         assert lib.sl_kv_cache_bytes(ctx, 0, 512, C.byref(out)) == B.SL_EINVAL
         assert lib.sl_kv_cache_bytes(ctx, 1, 512, None) == B.SL_EINVAL
+        assert lib.sl_kv_cache_bytes(ctx, 255, 64, C.byref(out)) == B.SL_OK              # SL_MAX_BATCH
+        assert lib.sl_kv_cache_bytes(ctx, 256, 64, C.byref(out)) == B.SL_EINVAL
+        assert lib.sl_kv_cache_bind(ctx, None, 256, 1 << 40, 256, 64) == B.SL_EINVAL
         assert lib.sl_kv_cache_bind(ctx, None, None, 1 << 30, 1, 512) == B.SL_EINVAL
         assert lib.sl_kv_cache_bind(ctx, None, 256, 16, 1, 512) == B.SL_ENOSPC
         assert lib.sl_kv_cache_bind(ctx, None, 257, 1 << 40, 1, 512) == B.SL_EINVAL      # misaligned

@@ -415,3 +415,44 @@ def test_sequences_without_active_rows(shape):
     finally:
         s2.close()
         s1.close()
+
+
+def test_largest_batch():
+    """SL_MAX_BATCH = 255 sequences of 64 slots in one step (16320 packed rows, then a ragged step in which
+    every sequence keeps a different number of active rows, some none): sampled sequences against the oracle's
+    full forward of that sequence alone, the packed row ranges against the definition."""
+    from oracle import model
+    shape, Bn, N = wl.S_BF16, 255, 64
+    w = wl.make_weights(shape, seed=7, norm_gain_jitter=0.05)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    tok = np.stack([wl.prompt_uniform(100 + b, N, shape.vocab, shape.mask_id) for b in range(Bn)])
+    sess = B.Session(shape, weights_to_device(w), Bn, N)
+    try:
+        eps = dev(np.full(Bn, 1e-3, dtype=np.float32))
+        z8 = torch.zeros(Bn * N, dtype=torch.uint8, device=DEV)
+        tokens = dev(tok.reshape(-1), torch.int32)
+        sess.step(tokens, z8.clone(), z8.clone(), eps, 1, 0, N, 0, m_upper=Bn * N, new_lock=torch.zeros_like(z8))
+        torch.cuda.synchronize()
+        assert sess.cu_active.cpu().tolist() == [b * N for b in range(Bn + 1)]
+        for b in (0, 127, 254):
+            z, _, _ = model.forward_full(cfg, w64, tok[b])
+            z_gpu = sess.logits_view(1)[b * N:(b + 1) * N].double().cpu().numpy()
+            check_logits(z_gpu, z, "bf16", f"B=255 step 1, sequence {b}")
+        # ragged: sequence b keeps b % 9 of its rows active (every ninth sequence none)
+        lock = np.ones((Bn, N), dtype=np.uint8)
+        rng = np.random.default_rng(3)
+        for b in range(Bn):
+            lock[b, rng.choice(N, size=b % 9, replace=False)] = 0
+        active, cu = control.compact_active(lock)
+        M = len(active)
+        sess.step(tokens, z8.clone(), dev(lock.reshape(-1)), eps, 2, 0, N, 0, m_upper=M, new_lock=torch.zeros_like(z8))
+        torch.cuda.synchronize()
+        assert np.array_equal(sess.cu_active.cpu().numpy(), cu)
+        assert np.array_equal(sess.active_idx[:M].cpu().numpy(), active)
+        # unchanged tokens and a cache that already holds this forward's K/V: the restricted rows reproduce step 1
+        rows = torch.as_tensor(active, device=DEV, dtype=torch.long)
+        d = (sess.logits_view(2)[rows].float() - sess.logits_view(1)[rows].float()).abs()
+        assert float(d.max()) <= 0.0625 and float((d > 0).float().mean()) < 0.25
+        assert torch.all(sess.kl[:M] < 1e-3)
+    finally:
+        sess.close()
