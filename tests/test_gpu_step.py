@@ -209,7 +209,7 @@ def test_c1_lock_disabled_is_full_recompute():
     (wl.S_BF16, 3, 40, 96, 12, 96, [16, 50, 136]),   # batch with different M per sequence
     (wl.S_BF16_WIDE, 2, 64, 64, 8, 32, [20, 70]),
     (wl.S_BF16_H64, 2, 30, 70, 10, 70, [10, 33]),     # bf16 on the shape-generic kernels
-    (wl.S_BF16, 2, 1000, 100, 5, 100, [40, 300]),     # N = 1100: 18 key tiles (4 or 5 per wave of the thin attention kernel), last one ragged
+    (wl.S_BF16, 2, 1000, 100, 5, 100, [40, 300]),     # N = 1100: 18 key tiles, the last one ragged: beyond the thin attention kernel's 16, so the keys are split over workgroups (+ merge)
     (wl.S_BF16_FFN, 1, 40, 56, 8, 56, [12]),          # thin steps whose gate|up + SwiGLU launch is the 256-column weight stream
 ])
 def test_bf16_small_forced_schedule(shape, Bn, n_p, n_gen, T, block, M_end):
