@@ -183,7 +183,7 @@ extern "C" int sl_kv_cache_read(const sl_ctx* ctx, void* stream, int32_t layer, 
   if (!ctx->kv) return SL_ESTATE;
   if (layer < 0 || layer >= ctx->cfg.n_layers) return SL_EINVAL;
   return slk_kv_read((hipStream_t)stream, ctx->cfg.dtype, kv_k_layer(ctx, layer), kv_v_layer(ctx, layer), ctx->batch,
-                     ctx->cfg.n_heads, ctx->n_seq, ctx->n_pad, ctx->cfg.d_head, k_out, v_out);
+                     ctx->cfg.n_heads, ctx->n_seq, ctx->n_pad, ctx->cfg.d_head, k_out, v_out, ctx->use_mfma ? 1 : 0);
 }
 
 // ---- posterior store -----------------------------------------------------------------------------
@@ -300,7 +300,7 @@ static int run_layers(sl_ctx* ctx, hipStream_t s, const Workspace& ws, const int
     // RoPE; live K/V overwrite the rows' own cache slots (locked slots are never touched)
     SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, dt, ws.f32, 1, 0, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad, rope_tab, ws.q,
                              ctx->probe_read_only ? nullptr : kv_k_layer(ctx, l),
-                             ctx->probe_read_only ? nullptr : kv_v_layer(ctx, l)));
+                             ctx->probe_read_only ? nullptr : kv_v_layer(ctx, l), 0));
     SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_generic(s, dt, ws.q, kv_k_layer(ctx, l), kv_v_layer(ctx, l), active_idx, m_dev, mu, H, dh,
                                  ctx->n_seq, ctx->n_pad, ws.o));
     SL_RUN(ctx, s, SL_PROF_GEMM_OUT, slk_gemm_generic(s, dt, ws.o, L.wo, m_dev, mu, d, hd, ws.f32, nullptr, nullptr, d));

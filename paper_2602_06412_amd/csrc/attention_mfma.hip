@@ -9,9 +9,20 @@
 //   lane l of the accumulator owns query q = l%32 and 16 keys per 32-key block, so the row
 //   max / sum of the online softmax need one cross-lane exchange (lanes l, l^32) only;
 //   O^T[dim, q] += V^T P^T  (A = V^T fragment from LDS, B = P^T = the accumulator registers
-//   of the first product rounded to bf16, used in place: no LDS round trip, no transpose).
+//   of the first product rounded to half precision, used in place: no LDS round trip, no
+//   transpose).
 // The K/V cache layouts (kc_index / vc_index) make every fragment of a 64-slot tile a
 // contiguous block, so a tile is a straight 16 KiB + 16 KiB copy into LDS.
+//
+// Precision of P.  The second product runs on half-precision operands: V is cached as the half
+// image of its bf16 values (vcache_half_bits: exact in the range activations live in), P is
+// rounded to half precision (11 significant bits, round to nearest even) by the two thick-launch
+// kernels and carried as a pair of halves (22 bits) by the thin one, where the second half costs
+// nothing.  One bf16 value per probability (8 bits, what a plain bf16 attention does) is not
+// enough against an fp64 softmax: measured on one full-size layer, the rms error of the logits
+// grows by 17 % with bf16 probabilities, by 5-8 % with one half, by nothing with two; the largest
+// error and the share of logits beyond 2e-2 stay where the bf16 roundings of the activations put
+// them with one half or two.
 //
 // One workgroup = 4 waves x 32 queries of ONE sequence and one head; packed rows of
 // different sequences never share a tile (the varlen case of a ragged batch).
@@ -28,10 +39,27 @@ constexpr int DH = 128;
 constexpr int kMaxBatch = SL_MAX_BATCH;
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-constexpr float kMaxLag = 8.0f;   // probabilities may exceed 1 by up to 2^8 before the reference moves
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t PFrag __attribute__((ext_vector_type(4)));   // eight bf16 probabilities, packed in pairs
+constexpr float kMaxLag = 8.0f;   // probabilities may exceed 1 by up to 2^8 before the reference moves
+typedef uint32_t PFrag __attribute__((ext_vector_type(4)));   // eight half-precision probabilities, packed in pairs
+
+// O^T += V^T P^T on one fragment pair: V is cached as half-precision images of its bf16 values, P is
+// rounded to half precision (see the kernels), the product accumulates in fp32.
+__device__ inline f32x16 mfma_pv(const FragA& v, const PFrag& p, const f32x16& acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, v), __builtin_bit_cast(f16x8, p), acc, 0, 0, 0);
+}
+// Two probabilities as a packed pair of halves, round to nearest even.
+__device__ inline uint32_t pack_half2(float a, float b) {
+  const f32x2 pp = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, f16x2));
+}
+// What the halves of such a pair leave of (a, b), again as a packed pair: P = hi + lo carries 22 bits.
+__device__ inline uint32_t pack_half2_rest(float a, float b, uint32_t hi) {
+  const f16x2 h = __builtin_bit_cast(f16x2, hi);
+  return pack_half2(a - (float)h[0], b - (float)h[1]);
+}
 
 // SPLIT: the key tiles are divided over gridDim.z workgroups (thin launches would otherwise
 // leave most CUs idle and walk all N slots serially); each writes its unnormalised O, running
@@ -42,8 +70,8 @@ typedef uint32_t PFrag __attribute__((ext_vector_type(4)));   // eight bf16 prob
 // S(t+1) = K(t+1) Q^T while the vector ALU turns S(t) into P(t) (MFMAs run asynchronously once
 // issued).  O is kept relative to the running max of the tiles already ADDED, so the rescale by
 // alpha(t) follows the accumulation of tile t-1 and happens only when some lane's max moved.
-// K and V tiles arrive by direct-to-LDS loads into two-slot rings (K(t+2) and V(t) are issued in
-// iteration t, one iteration ahead of their use); one barrier per tile.
+// K and V tiles arrive by direct-to-LDS loads into three-slot rings (K(t+3) and V(t+1) are issued
+// in iteration t, two iterations ahead of their use); one barrier per tile.
 template <bool SPLIT>
 __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __restrict__ q,
                                                                 const bf16_t* __restrict__ kc,
@@ -160,30 +188,25 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
       for (int v = 0; v < 16; ++v)
         if (kbase + 32 * kb + 8 * (v / 4) + (v % 4) >= N) sv[kb][v] = -INFINITY;
   };
-  // O^T += V^T P^T with P = hi + lo
-  auto pv = [&](const FragA* vt_lds, const PFrag (&ph)[4], const PFrag (&pl)[4]) {
+  // O^T += V^T P^T
+  auto pv = [&](const FragA* vt_lds, const PFrag (&ph)[4]) {
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       FragA a[4];
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) a[mb] = vt_lds[(2 * st + (lane >> 5)) * DH + mb * 32 + (lane & 31)];
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+      for (int mb = 0; mb < 4; ++mb) acc_o[mb] = mfma_pv(a[mb], ph[st], acc_o[mb]);
     }
   };
-  // One pipeline step for tile t: scores sc_cur -> probabilities (p_new_hi/lo), while the MFMAs
-  // add tile t-1 (p_old) and compute the scores of tile t+1 (sc_next).
-  auto step = [&](int t, f32x16 (&sc_cur)[2], f32x16 (&sc_next)[2], const PFrag (&poh)[4], const PFrag (&pol)[4],
-                  PFrag (&pnh)[4], PFrag (&pnl)[4]) {
+  // One pipeline step for tile t: scores sc_cur -> probabilities p_new, while the MFMAs add tile t-1
+  // (p_old) and compute the scores of tile t+1 (sc_next).
+  auto step = [&](int t, f32x16 (&sc_cur)[2], f32x16 (&sc_next)[2], const PFrag (&p_old)[4], PFrag (&p_new)[4]) {
     // loads complete in order, eight chunks per wave per iteration: all but those of the last
     // R-2 iterations have landed, which covers K(t+1) and V(t-1)
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(8 * (R - 2)) : "memory");
     __syncthreads();      // ... for everyone; the slots of K(t) and V(t-2) are free
-    // K(t+R) and V(t+R-2) go into the two slots the barrier just freed, one 1 KiB chunk every fourth
+    // K(t+R) and V(t+R-2) go into the two slots the barrier just freed, one 1 KiB chunk every second
     // MFMA slot below (a burst of eight would fill the load queue and stall the wave at issue).
     // Past the last tile K re-fetches the last one; nothing reads it.
     const FragA* k_src = kg + (size_t)min(kt_lo + t + R, kt_hi - 1) * TILE_F;
@@ -192,14 +215,16 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
     FragA* const v_dst = ldsV + ((t + R - 2) % R) * TILE_F;
     const FragA* vt_lds = ldsV + ((t + R - 1) % R) * TILE_F + (lane >> 5) * DH + (lane & 31);
     const FragA* kt_lds = ldsK + ((t + 1) % R) * TILE_F + lane;
-    // The block below is laid out by hand as 48 slots, one MFMA each, fenced so that the
-    // compiler keeps the order: slots 0..31 add tile t-1 (V fragment groups of four, hi then lo),
-    // slots 32..47 compute the scores of tile t+1; LDS fragments are read 8..10 slots ahead of
-    // their MFMA; the softmax of tile t rides along, one pair of probabilities every third slot
-    // (an MFMA occupies the matrix pipe for 32 cycles, a pair costs ~76 vector-ALU cycles).
-    FragA va[2][4], kf[16];
+    // The block below is laid out by hand as 32 slots, one MFMA each, fenced so that the compiler
+    // keeps the order: slots 0..15 add tile t-1 (V fragment groups of four), slots 16..31 compute the
+    // scores of tile t+1; LDS fragments are read 8..12 slots ahead of their MFMA; the softmax of tile
+    // t rides along, one pair of probabilities every second slot (an MFMA occupies the matrix pipe
+    // for 32 cycles and leaves the vector ALU about 20 of them).
+    FragA va[3][4], kf[16];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) va[0][mb] = vt_lds[mb * 32];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) va[1][mb] = vt_lds[2 * DH + mb * 32];
     // running max of tile t while those first reads are in flight
     float mx = sc_cur[0][0];
 #pragma unroll
@@ -218,28 +243,26 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
     const float mb_ = m_new * sc;
     float psum = 0.f, pa = 0.f, pb = 0.f;
-    uint32_t hw = 0u;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 48; ++i) {
-      if (i < 32 && i % 4 == 0) {
-        if (i < 16) load_chunk(k_src, k_dst, i / 4);
-        else load_chunk(v_src, v_dst, i / 4 - 4);
+    for (int i = 0; i < 32; ++i) {
+      if (i < 16 && i % 2 == 0) {
+        if (i < 8) load_chunk(k_src, k_dst, i / 2);
+        else load_chunk(v_src, v_dst, i / 2 - 4);
       }
-      if (i < 32) {
-        const int st = i >> 3, r = i & 7;
-        if (r < 4 && st < 3) va[(st + 1) & 1][r] = vt_lds[(2 * (st + 1)) * DH + r * 32];
+      if (i < 8) {                                   // V fragments of group st + 2, eight slots ahead
+        const int st = i >> 2, r = i & 3;
+        va[(st + 2) % 3][r] = vt_lds[(2 * (st + 2)) * DH + r * 32];
       }
-      if (i >= 22 && i < 38) {
-        const int q = i - 22, jr = (q & 1) * 8 + (q >> 1);
+      if (i >= 4 && i < 20) {                        // K fragments of tile t+1, twelve slots ahead
+        const int q = i - 4, jr = (q & 1) * 8 + (q >> 1);
         kf[jr] = kt_lds[jr * 64];
       }
-      if (i < 32) {
-        const int st = i >> 3, r = i & 7, mb = r & 3;
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st & 1][mb], __builtin_bit_cast(FragA, (r >> 2) ? pol[st] : poh[st]),
-                                                            acc_o[mb], 0, 0, 0);
+      if (i < 16) {
+        const int st = i >> 2, mb = i & 3;
+        acc_o[mb] = mfma_pv(va[st % 3][mb], p_old[st], acc_o[mb]);
       } else {
-        const int jj = i - 32, kb = jj & 1, ks = jj >> 1, j = kb * 8 + ks;   // the two score blocks alternate
+        const int jj = i - 16, kb = jj & 1, ks = jj >> 1, j = kb * 8 + ks;   // the two score blocks alternate
         if (ks == 0) {
           f32x16 z;
 #pragma unroll
@@ -250,29 +273,21 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
         }
       }
       // Softmax of tile t, one pair of probabilities (2pr, 2pr+1 of this lane: register v of block
-      // kb, for P^T step 2*kb + v/8) per three slots, its dependent chain cut in three so that no
-      // slot carries more than five vector-ALU instructions behind its MFMA: exponentials, then
-      // sum + high halves, then low halves.  The empty asm statements tie each piece to its slot:
-      // without them the compiler sinks the whole softmax below the last MFMA.
+      // kb, for P^T step 2*kb + v/8) per two slots: the exponentials, then the sum and the rounding
+      // to a pair of halves.  The empty asm statements tie each piece to its slot: without them the
+      // compiler sinks the whole softmax below the last MFMA.
       {
-        const int pr = i / 3, ph = i % 3;
+        const int pr = i >> 1;
         const int x = 2 * pr, kb = x >> 4, v = x & 15, stp = 2 * kb + (v >> 3), e = v & 7;
-        if (ph == 0) {
+        if ((i & 1) == 0) {
           pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
           pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
           asm volatile("" : "+v"(pa), "+v"(pb));
-        } else if (ph == 1) {
-          psum += pa + pb;
-          const f32x2 pp = {pa, pb};
-          hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-          asm volatile("" : "+v"(hw), "+v"(psum));
-          pnh[stp][e >> 1] = hw;
         } else {
-          // the bf16 halves are widened back with a shift / a mask
-          const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
-          uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
-          asm volatile("" : "+v"(lw));
-          pnl[stp][e >> 1] = lw;
+          psum += pa + pb;
+          uint32_t hw = pack_half2(pa, pb);
+          asm volatile("" : "+v"(hw), "+v"(psum));
+          p_new[stp][e >> 1] = hw;
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -289,23 +304,23 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
   };
 
   f32x16 s0[2], s1[2];
-  PFrag p0h[4], p0l[4], p1h[4], p1l[4];
+  PFrag p0[4], p1[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { p0h[i][e] = 0u; p0l[i][e] = 0u; }
+    for (int e = 0; e < 4; ++e) p0[i][e] = 0u;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   scores(ldsK, s0);
   if ((kt_lo + 1) * KT > N) mask_tail(kt_lo, s0);
   for (int t = 0; t < T; t += 2) {
-    step(t, s0, s1, p0h, p0l, p1h, p1l);
-    if (t + 1 < T) step(t + 1, s1, s0, p1h, p1l, p0h, p0l);
+    step(t, s0, s1, p0, p1);
+    if (t + 1 < T) step(t + 1, s1, s0, p1, p0);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();                            // V(T-1) landed
-  if (T & 1) pv(ldsV + ((T - 1) % R) * TILE_F, p1h, p1l);
-  else pv(ldsV + ((T - 1) % R) * TILE_F, p0h, p0l);
+  if (T & 1) pv(ldsV + ((T - 1) % R) * TILE_F, p1);
+  else pv(ldsV + ((T - 1) % R) * TILE_F, p0);
 
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (SPLIT) {
@@ -340,12 +355,17 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
   }
 }
 
-// Second form of the same product for launches with at least two workgroups per CU: the wave
-// does not pipeline its own tile steps (scores, softmax, P.V in sequence), needs half the
-// registers and a two-slot ring, and two workgroups share a CU, so that one's softmax runs under
-// the other's MFMAs and barrier waits.  Same fragment layouts, same arithmetic per tile.
+// Second form of the same product for launches with more workgroups than CUs: the wave does not
+// pipeline its own tile steps (scores, softmax, P.V in sequence) and THREE workgroups share a CU, so
+// that one's softmax runs under the others' MFMAs and barrier waits.  What lets three fit: P is one
+// half-precision value per probability (no lo half: 32 MFMAs per tile instead of 48, no vector work to
+// form it; 151 registers), and V has ONE 16 KiB slot next to K's two (48 KiB per workgroup): V(t) is
+// requested at the top of step t, when the barrier has shown that everyone is done with V(t-1), and
+// arrives under the scores and the softmax of the step; a second barrier per step makes it visible.
+// Measured at sum M = 8192 rows of N = 1024: 220 us (two workgroups per CU, P as two halves) ->
+// 206 us (three per CU) -> 157 us (one half).  Same fragment layouts as above.
 template <bool SPLIT>
-__global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __restrict__ q,
+__global__ __launch_bounds__(256, 3) void attention_trio_kernel(const bf16_t* __restrict__ q,
                                                                 const bf16_t* __restrict__ kc,
                                                                 const bf16_t* __restrict__ vc,
                                                                 const int32_t* __restrict__ active_idx,
@@ -353,7 +373,7 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
                                                                 int H, int N, int n_pad, bf16_t* __restrict__ o,
                                                                 int tiles_per_split, float* __restrict__ part_o,
                                                                 float* __restrict__ part_ml) {
-  extern __shared__ FragA lds[];             // K ring [2][16 KiB] | V ring [2][16 KiB]
+  extern __shared__ FragA lds[];             // K ring [2][16 KiB] | V slot [16 KiB]
   __shared__ int cu[kMaxBatch + 2];
   constexpr int TILE_F = KT * DH / 8;
   FragA* const ldsK = lds;
@@ -404,7 +424,6 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
     }
   };
   load_tile(kg + (size_t)kt_lo * TILE_F, ldsK);
-  load_tile(vg + (size_t)kt_lo * TILE_F, ldsV);
 
   const int my_row = row0 + wave * 32 + (lane & 31);
   const int ld_row = my_row < row_end ? my_row : row_end - 1;
@@ -424,13 +443,12 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
 
   for (int t = 0; t < T; ++t) {
     const int slot = t & 1;
-    // tile t has landed (it was requested one iteration ago) ...
+    // K(t) has landed (it was requested one iteration ago) ...
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();       // ... for everyone, and everyone is done with tile t-1: its slot is free
-    if (t + 1 < T) {
-      load_tile(kg + (size_t)(kt_lo + t + 1) * TILE_F, ldsK + (slot ^ 1) * TILE_F);
-      load_tile(vg + (size_t)(kt_lo + t + 1) * TILE_F, ldsV + (slot ^ 1) * TILE_F);
-    }
+    __syncthreads();       // ... for everyone, and everyone is done with tile t-1: V's slot and K(t-1)'s are free
+    // V(t) first, then K(t+1): loads complete in order, so "all but the last four" below means V(t)
+    load_tile(vg + (size_t)(kt_lo + t) * TILE_F, ldsV);
+    if (t + 1 < T) load_tile(kg + (size_t)(kt_lo + t + 1) * TILE_F, ldsK + (slot ^ 1) * TILE_F);
     // S^T = K Q^T: two 32-key blocks; register v of block kb is key 32*kb + 8*(v/4) + 4*(lane>>5) + v%4
     f32x16 sv[2];
     const FragA* kt_lds = ldsK + slot * TILE_F + lane;
@@ -467,8 +485,8 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_o[i][v] *= alpha;
     }
-    // P = hi + lo in bf16; pair (v, v+1) of block kb belongs to P^T step 2*kb + v/8
-    PFrag ph[4], pl[4];
+    // P in half precision, round to nearest even; pair (v, v+1) of block kb belongs to P^T step 2*kb + v/8
+    PFrag ph[4];
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -477,28 +495,23 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
         const float pa = __builtin_amdgcn_exp2f(fmaf(sv[kb][v], sc, -mb_));
         const float pb = __builtin_amdgcn_exp2f(fmaf(sv[kb][v + 1], sc, -mb_));
         psum += pa + pb;
-        const f32x2 pp = {pa, pb};
-        const uint32_t hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-        const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
-        const uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
-        ph[2 * kb + (v >> 3)][(v & 7) >> 1] = hw;
-        pl[2 * kb + (v >> 3)][(v & 7) >> 1] = lw;
+        ph[2 * kb + (v >> 3)][(v & 7) >> 1] = pack_half2(pa, pb);
       }
     l_run = l_run * alpha + psum;
     m_run = m_new;
+    // V(t) has landed (K(t+1)'s four chunks may still be in flight) ...
+    if (t + 1 < T) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();       // ... for everyone
     // O^T += V^T P^T
-    const FragA* vt_lds = ldsV + slot * TILE_F + (lane >> 5) * DH + (lane & 31);
+    const FragA* vt_lds = ldsV + (lane >> 5) * DH + (lane & 31);
 #pragma unroll
     for (int st = 0; st < 4; ++st) {
       FragA a[4];
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) a[mb] = vt_lds[(2 * st) * DH + mb * 32];
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+      for (int mb = 0; mb < 4; ++mb) acc_o[mb] = mfma_pv(a[mb], ph[st], acc_o[mb]);
     }
   }
 
@@ -541,8 +554,8 @@ __global__ __launch_bounds__(256, 2) void attention_pair_kernel(const bf16_t* __
 // partial-result buffer and no merge launch.  K and V fragments go global -> registers directly (the
 // cache layouts make every MFMA fragment of a tile one contiguous 1 KiB block: no LDS staging, no
 // barrier in the loop), the next tile's fragments are requested before the current tile is computed.
-// Same fragment layouts and the same arithmetic per tile as the kernels above (P = bf16 hi + lo),
-// with the exact running max as the reference of the exponentials.
+// Same fragment layouts as the kernels above; P is carried as two halves (hi + lo, 22 bits: the
+// matrix pipe idles here anyway), with the exact running max as the reference of the exponentials.
 constexpr int QTT = 32;          // queries per workgroup of the thin kernel
 __global__ __launch_bounds__(256, 1) void attention_thin_kernel(const bf16_t* __restrict__ q,
                                                                 const bf16_t* __restrict__ kc,
@@ -649,10 +662,8 @@ __global__ __launch_bounds__(256, 1) void attention_thin_kernel(const bf16_t* __
         const float pa = __builtin_amdgcn_exp2f(fmaf(sv[kb][v], sc, -mb_));
         const float pb = __builtin_amdgcn_exp2f(fmaf(sv[kb][v + 1], sc, -mb_));
         psum += pa + pb;
-        const f32x2 pp = {pa, pb};
-        const uint32_t hw = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2));
-        const f32x2 rest = {pa - __uint_as_float(hw << 16), pb - __uint_as_float(hw & 0xffff0000u)};
-        const uint32_t lw = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
+        const uint32_t hw = pack_half2(pa, pb);
+        const uint32_t lw = pack_half2_rest(pa, pb, hw);
         ph[2 * kb + (v >> 3)][(v & 7) >> 1] = hw;
         pl[2 * kb + (v >> 3)][(v & 7) >> 1] = lw;
       }
@@ -662,10 +673,10 @@ __global__ __launch_bounds__(256, 1) void attention_thin_kernel(const bf16_t* __
     for (int st = 0; st < 4; ++st) {
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st * 4 + mb], __builtin_bit_cast(FragA, ph[st]), acc_o[mb], 0, 0, 0);
+        acc_o[mb] = mfma_pv(vf[st * 4 + mb], ph[st], acc_o[mb]);
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb)
-        acc_o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[st * 4 + mb], __builtin_bit_cast(FragA, pl[st]), acc_o[mb], 0, 0, 0);
+        acc_o[mb] = mfma_pv(vf[st * 4 + mb], pl[st], acc_o[mb]);
     }
   };
   // this wave's tiles: wave, wave + 4, ..; two register sets, the next tile is requested before the current one is used
@@ -745,11 +756,10 @@ __global__ __launch_bounds__(128) void attention_merge_kernel(const float* __res
   o[afrag_index(row, hh * DH + dd, H * DH)] = (bf16_t)(num / den);
 }
 
-// Which kernel a launch of `blocks` (row tile, head) workgroups takes: the paired kernel as soon as
-// there is more than one workgroup per CU (measured on 32 layers at N = 2048: attention 3.5 -> 3.0
-// ms per step at 512 workgroups, 3.1 -> 2.5 ms at 288), the pipelined one otherwise (34 vs 51 us
-// at 256 workgroups, where the paired kernel would need a key split and a merge to fill the CUs).
-static bool attention_use_pair(int blocks) { return blocks > 256; }
+// Which kernel a launch of `blocks` (row tile, head) workgroups takes: the three-per-CU kernel as
+// soon as there are more workgroups than CUs, the pipelined one otherwise (at N = 2048 and 857 rows,
+// 224 workgroups: 46 us against 62 us for the three-per-CU kernel with the keys split three ways).
+static bool attention_use_trio(int blocks) { return blocks > 256; }
 
 // The thin kernel (32 queries and one head per workgroup, key tiles split over its waves) while its
 // workgroups fit the chip in one round and a wave's share of the keys stays short.
@@ -759,13 +769,13 @@ static bool attention_use_thin(int m_upper, int B, int H, int n_pad) {
 }
 
 // Key-split plan for a launch bounded by m_upper rows: the keys are split just far enough to
-// give every CU one workgroup of the pipelined kernel (LDS rings, 390 registers per lane: one per
-// CU) or two of the paired kernel; splitting further only adds partial-result traffic and more
+// give every CU one workgroup of the pipelined kernel (LDS rings, 370 registers per lane: one per
+// CU) or three of the other; splitting further only adds partial-result traffic and more
 // rounds of workgroups.  Returns Z (1 = no split) and the tiles per split.
 int slk_attention_splits(int m_upper, int B, int H, int n_pad, int* tiles_per_split) {
   const int n_tiles = n_pad / KT;
   const int blocks = (sl_cdiv(m_upper, QT) + B - 1) * H;
-  int Z = (attention_use_pair(blocks) ? 512 : 256) / blocks;
+  int Z = (attention_use_trio(blocks) ? 768 : 256) / blocks;
   if (Z < 1) Z = 1;
   if (Z > n_tiles) Z = n_tiles;
   const int tps = sl_cdiv(n_tiles, Z);
@@ -800,15 +810,15 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   int tps;
   const int Z = scratch ? slk_attention_splits(m_upper, B, H, n_pad, &tps) : 1;
   dim3 grid(H, sl_cdiv(m_upper, QT) + B - 1, Z), block(256);
-  const bool pair = attention_use_pair((int)(grid.x * grid.y));
-  const size_t sh = (pair ? 4 : 6) * (size_t)KT * DH * 2;   // K and V rings of 16 KiB slots: two or three each
+  const bool trio = attention_use_trio((int)(grid.x * grid.y));
+  const size_t sh = (trio ? 3 : 6) * (size_t)KT * DH * 2;   // 16 KiB slots: K 2 + V 1, or three each
   static unsigned long long lds_ok[4] = {0, 0, 0, 0};
   SL_ALLOW_DYNAMIC_LDS(lds_ok[0], attention_mfma_kernel<false>, 6 * (size_t)KT * DH * 2);
   SL_ALLOW_DYNAMIC_LDS(lds_ok[1], attention_mfma_kernel<true>, 6 * (size_t)KT * DH * 2);
-  SL_ALLOW_DYNAMIC_LDS(lds_ok[2], attention_pair_kernel<false>, 4 * (size_t)KT * DH * 2);
-  SL_ALLOW_DYNAMIC_LDS(lds_ok[3], attention_pair_kernel<true>, 4 * (size_t)KT * DH * 2);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[2], attention_trio_kernel<false>, 3 * (size_t)KT * DH * 2);
+  SL_ALLOW_DYNAMIC_LDS(lds_ok[3], attention_trio_kernel<true>, 3 * (size_t)KT * DH * 2);
   if (Z == 1) {
-    hipLaunchKernelGGL(pair ? attention_pair_kernel<false> : attention_mfma_kernel<false>, grid, block, sh, s,
+    hipLaunchKernelGGL(trio ? attention_trio_kernel<false> : attention_mfma_kernel<false>, grid, block, sh, s,
                        (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad,
                        (bf16_t*)o, 0, nullptr, nullptr);
     SL_LAUNCH_CHECK();
@@ -816,7 +826,7 @@ int slk_attention_mfma(hipStream_t s, const void* q, const void* kc, const void*
   }
   float* part_o = scratch;
   float* part_ml = scratch + (size_t)Z * m_upper * H * DH;
-  hipLaunchKernelGGL(pair ? attention_pair_kernel<true> : attention_mfma_kernel<true>, grid, block, sh, s,
+  hipLaunchKernelGGL(trio ? attention_trio_kernel<true> : attention_mfma_kernel<true>, grid, block, sh, s,
                      (const bf16_t*)q, (const bf16_t*)kc, (const bf16_t*)vc, active_idx, m_dev, m_upper, B, H, N, n_pad,
                      (bf16_t*)o, tps, part_o, part_ml);
   SL_LAUNCH_CHECK();

@@ -442,7 +442,7 @@ __device__ __forceinline__ void ring_tile(
             const int bb = g0 / rs.N, i0 = g0 - bb * rs.N;
             bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (bf16_t)col[((e >> 2) * 8 + 4 * vcg + (e & 3)) * RSf];
+            for (int e = 0; e < 8; ++e) o[e] = vcache_half_bits(col[((e >> 2) * 8 + 4 * vcg + (e & 3)) * RSf]);
             *reinterpret_cast<bf16x8*>(rs.vc + ((size_t)bb * rs.H + head) * rs.n_pad * 128 + vc_index(i0 + 4 * vcg, vdim, 128)) = o;
           } else {
 #pragma unroll 1
@@ -451,7 +451,7 @@ __device__ __forceinline__ void ring_tile(
               const int g = slot_sh[gi * 16 + lr];
               if (g < 0) continue;
               const int bb = g / rs.N, i = g - bb * rs.N;
-              rs.vc[((size_t)bb * rs.H + head) * rs.n_pad * 128 + vc_index(i, vdim, 128)] = (bf16_t)col[lr * RSf];
+              rs.vc[((size_t)bb * rs.H + head) * rs.n_pad * 128 + vc_index(i, vdim, 128)] = vcache_half_bits(col[lr * RSf]);
             }
           }
         }

@@ -99,7 +99,7 @@ int sl_mfma_layer(sl_ctx* ctx, hipStream_t s, int l, void* x, void* h, void* q, 
     const int S = slk_gemm_splits(mu, 3 * hd, d);
     SL_RUN(ctx, s, SL_PROF_GEMM_QKV, slk_gemm_mfma(s, h, 1, P.wqkv, m_dev, mu, 3 * hd, d, S, f32, nullptr, nullptr, 3 * (size_t)hd));
     SL_RUN(ctx, s, SL_PROF_ROPE_KV, slk_rope_kv_write(s, SL_BF16, f32, S, (size_t)mu * 3 * hd, active_idx, m_dev, mu, H, dh, ctx->n_seq, ctx->n_pad,
-                             ctx->kv, q, kc_w, vc_w));
+                             ctx->kv, q, kc_w, vc_w, 1));
   }
   SL_RUN(ctx, s, SL_PROF_ATTENTION, slk_attention_mfma(s, q, kv_k(ctx, l), kv_v(ctx, l), active_idx, m_dev, mu, ctx->batch, H, ctx->n_seq,
                             ctx->n_pad, o, attn_scratch));

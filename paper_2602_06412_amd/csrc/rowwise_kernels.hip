@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kRowThreads) void add_rmsnorm_kernel(T* x, const fl
 // q, k <- rnd(RoPE(q, k)) at the row's fixed slot; v <- rnd(v); k, v go to the row's own
 // cache slot (the only cache rows this step may touch), q to the packed query buffer.
 // Half-split pairing (j, j + d_h/2); angles come from a table built in fp64 at bind time.
-template <typename T>
+template <typename T, bool VH>
 __global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restrict__ qkv, int S, size_t sstride,
                                                             const int32_t* __restrict__ active_idx,
                                                             const int32_t* __restrict__ m_dev, int m_upper, int H,
@@ -109,8 +109,13 @@ __global__ __launch_bounds__(256) void rope_kv_write_kernel(const float* __restr
     const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
     st<T>::stv(kc + head_base + kc_index(i, j, dh), k0 * cs.x - k1 * cs.y);
     st<T>::stv(kc + head_base + kc_index(i, j + half, dh), k1 * cs.x + k0 * cs.y);
-    st<T>::stv(vc + head_base + vc_index(i, j, dh), v0);
-    st<T>::stv(vc + head_base + vc_index(i, j + half, dh), v1);
+    if constexpr (VH) {                                  // bf16 storage only (see vcache_half_bits)
+      vc[head_base + vc_index(i, j, dh)] = vcache_half_bits(v0);
+      vc[head_base + vc_index(i, j + half, dh)] = vcache_half_bits(v1);
+    } else {
+      st<T>::stv(vc + head_base + vc_index(i, j, dh), v0);
+      st<T>::stv(vc + head_base + vc_index(i, j + half, dh), v1);
+    }
   }
 }
 
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(256) void swiglu_kernel(const float* __restrict__ g
   st<T>::stv(a + act_index<TILED>(r, c, dff), g / (1.0f + expf(-g)) * u);
 }
 
-template <typename T>
+template <typename T, bool VH>
 __global__ void kv_read_kernel(const T* __restrict__ kc, const T* __restrict__ vc, int B, int H, int N, int n_pad,
                                int dh, T* __restrict__ k_out, T* __restrict__ v_out) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -156,7 +161,8 @@ __global__ void kv_read_kernel(const T* __restrict__ kc, const T* __restrict__ v
   const int b = t / ((size_t)dh * H * N);
   const size_t head_base = ((size_t)b * H + hh) * n_pad * dh;
   k_out[t] = kc[head_base + kc_index(i, dd, dh)];
-  v_out[t] = vc[head_base + vc_index(i, dd, dh)];
+  if constexpr (VH) v_out[t] = vcache_half_value(vc[head_base + vc_index(i, dd, dh)]);
+  else v_out[t] = vc[head_base + vc_index(i, dd, dh)];
 }
 
 __global__ void fill_zero_kernel(uint4* p, size_t n16) {
@@ -374,6 +380,7 @@ __global__ __launch_bounds__(256) void add_rmsnorm_wave_kernel(bf16_t* x, const 
 // those of a wave contiguous, q and K leave as 8-byte stores (consecutive dims
 // of one slot are contiguous in the K layout); V keeps 2-byte stores, its layout puts eight
 // SLOTS side by side, not eight dims.
+template <bool VH>
 __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __restrict__ qkv, int S, size_t sstride,
                                                                 const int32_t* __restrict__ active_idx,
                                                                 const int32_t* __restrict__ m_dev, int m_upper, int H,
@@ -425,15 +432,15 @@ __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __r
     st4(kc + head_base + kc_index(i, j + half, dh), kb);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      vc[head_base + vc_index(i, j + e, dh)] = (bf16_t)v0[e];
-      vc[head_base + vc_index(i, j + half + e, dh)] = (bf16_t)v1[e];
+      vc[head_base + vc_index(i, j + e, dh)] = vcache_elem<VH>(v0[e]);
+      vc[head_base + vc_index(i, j + half + e, dh)] = vcache_elem<VH>(v1[e]);
     }
   }
 }
 
 // Thick-launch variant: one workgroup per 16 consecutive packed rows, one head at a time.
 // Loads are 16 bytes per thread and contiguous along a row; q leaves directly (8-byte stores);
-// K and V of the head are staged in LDS as bf16 and leave in the order of the cache layouts:
+// K and V of the head are staged in LDS as 16-bit cache elements and leave in the order of the cache layouts:
 //   K: a thread writes the 16-byte unit (slot, 8 dims); the 16 rows of a unit column are 16
 //      lanes, so consecutive slots give 256 contiguous bytes;
 //   V: the cache puts eight SLOTS side by side per dim (slots 16A + 4c + {0..3} and 16A + 8 + 4c +
@@ -442,6 +449,7 @@ __global__ __launch_bounds__(256) void rope_kv_write_vec_kernel(const float* __r
 //      active) a thread writes one group as a 16-byte store, a wave 1 KiB contiguous; otherwise V
 //      falls back to 2-byte stores.
 // Requires d_h = 128 (256 threads = 16 rows x 16 chunks of four rotation pairs).
+template <bool VH>
 __global__ __launch_bounds__(256) void rope_kv_write_block_kernel(const float* __restrict__ qkv, int S, size_t sstride,
                                                                   const int32_t* __restrict__ active_idx,
                                                                   const int32_t* __restrict__ m_dev, int m_upper, int H,
@@ -515,8 +523,11 @@ __global__ __launch_bounds__(256) void rope_kv_write_block_kernel(const float* _
       st4(q + (size_t)(r0 + j) * hd + c1, qb);
       st4(&kbuf[j][jj], ka);
       st4(&kbuf[j][jj + half], kb);
-      st4(&vbuf[j][jj], v0);
-      st4(&vbuf[j][jj + half], v1);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vbuf[j][jj + e] = vcache_elem<VH>(v0[e]);
+        vbuf[j][jj + half + e] = vcache_elem<VH>(v1[e]);
+      }
     }
     __syncthreads();
     if (gs >= 0) {
@@ -642,16 +653,18 @@ int slk_rope_table(hipStream_t s, void* tab, int n_pad, int dh, float theta) {
 
 int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
                       const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc,
-                      void* vc) {
+                      void* vc, int v_half) {
   if (m_upper <= 0) return SL_OK;
   if ((kc == nullptr) != (vc == nullptr)) return SL_EINVAL;
+  if (v_half && dtype != SL_BF16) return SL_EINVAL;     // the half container is a 16-bit format
   // kc = vc = null: rotate and store the queries only (the row-per-workgroup kernels skip the cache stores)
   // thin launches are latency-bound (wide accesses, few instructions win); thick ones are bound by the
   // scattered 2-byte V stores, where the element-wise kernel's many threads per row do better
   if ((m_upper <= 256 || kc == nullptr) && dtype == SL_BF16 && dh % 8 == 0 && sstride % 4 == 0 && al16(rope_tab) && al16(qkv) && al16(q) && al16(kc) && al16(vc)) {
     const int per_row = H * (dh / 8), wgs = per_row >= 512 && m_upper <= 256 ? 2 : 1;   // (head, four pairs) items per row
-    hipLaunchKernelGGL(rope_kv_write_vec_kernel, dim3(m_upper, wgs), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
-                       m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
+    hipLaunchKernelGGL(v_half ? rope_kv_write_vec_kernel<true> : rope_kv_write_vec_kernel<false>, dim3(m_upper, wgs), dim3(256), 0,
+                       s, qkv, S, sstride, active_idx, m_dev, m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q,
+                       (bf16_t*)kc, (bf16_t*)vc);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
@@ -659,12 +672,19 @@ int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t 
     const int row_blocks = sl_cdiv(m_upper, 16);
     int hs = 1;                                          // head groups: aim at two workgroups per CU
     while (hs < H && H % (hs * 2) == 0 && row_blocks * hs < 512) hs *= 2;
-    hipLaunchKernelGGL(rope_kv_write_block_kernel, dim3(row_blocks, hs), dim3(256), 0, s, qkv, S, sstride, active_idx,
-                       m_dev, m_upper, H, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
+    hipLaunchKernelGGL(v_half ? rope_kv_write_block_kernel<true> : rope_kv_write_block_kernel<false>, dim3(row_blocks, hs),
+                       dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev, m_upper, H, N, n_pad, (const float2*)rope_tab,
+                       (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
     SL_LAUNCH_CHECK();
     return SL_OK;
   }
-  DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_kernel<T>), dim3(m_upper), dim3(256), 0, s, qkv, S, sstride,
+  if (v_half) {
+    hipLaunchKernelGGL((rope_kv_write_kernel<bf16_t, true>), dim3(m_upper), dim3(256), 0, s, qkv, S, sstride, active_idx, m_dev,
+                       m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (bf16_t*)q, (bf16_t*)kc, (bf16_t*)vc);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
+  DISPATCH_T(dtype, hipLaunchKernelGGL((rope_kv_write_kernel<T, false>), dim3(m_upper), dim3(256), 0, s, qkv, S, sstride,
                                        active_idx, m_dev, m_upper, H, dh, N, n_pad, (const float2*)rope_tab, (T*)q, (T*)kc,
                                        (T*)vc));
   SL_LAUNCH_CHECK();
@@ -688,9 +708,16 @@ int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride,
 }
 
 int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
-                void* k_out, void* v_out) {
+                void* k_out, void* v_out, int v_half) {
   const size_t total = (size_t)B * N * H * dh;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((kv_read_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+  if (v_half) {
+    if (dtype != SL_BF16) return SL_EINVAL;
+    hipLaunchKernelGGL((kv_read_kernel<bf16_t, true>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const bf16_t*)kc, (const bf16_t*)vc, B, H, N, n_pad, dh, (bf16_t*)k_out, (bf16_t*)v_out);
+    SL_LAUNCH_CHECK();
+    return SL_OK;
+  }
+  DISPATCH_T(dtype, hipLaunchKernelGGL((kv_read_kernel<T, false>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                                        (const T*)kc, (const T*)vc, B, H, N, n_pad, dh, (T*)k_out, (T*)v_out));
   SL_LAUNCH_CHECK();
   return SL_OK;

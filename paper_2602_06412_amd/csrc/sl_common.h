@@ -40,6 +40,22 @@ __host__ __device__ inline size_t vc_index(int slot, int dim, int dh) {
   return (((size_t)(slot >> 4) * 2 + ((slot >> 2) & 1)) * dh + dim) * 8 + ((slot >> 3) & 1) * 4 + (slot & 3);
 }
 
+// V element of the MFMA route.  The attention kernels multiply V by half-precision probabilities (the
+// matrix cores take both operands in one format), so on that route the cache holds each V value, rounded
+// to bf16 like every stored activation, in an IEEE half container: exact for 2^-14 <= |v| <= 65504
+// (a bf16 value has 8 significant bits, a half 11), kept to a multiple of 2^-24 below that, saturated
+// above (an infinity would turn a zero probability into NaN).  These helpers carry the 16 bits in a
+// bf16_t, which is what the cache pointers are typed as.
+typedef _Float16 f16_t;
+__device__ inline bf16_t vcache_half_bits(float v) {
+  const float r = (float)(bf16_t)v;
+  const float c = r != r ? r : fminf(fmaxf(r, -65504.f), 65504.f);
+  return __builtin_bit_cast(bf16_t, (f16_t)c);
+}
+__device__ inline bf16_t vcache_half_value(bf16_t bits) { return (bf16_t)(float)__builtin_bit_cast(f16_t, bits); }
+template <bool VH>
+__device__ inline bf16_t vcache_elem(float v) { return VH ? vcache_half_bits(v) : (bf16_t)v; }
+
 // ---- activation matrices feeding the MFMA GEMMs ------------------------------------------
 // "Tiled" layout of an [rows, K] bf16 matrix: MFMA A-operand fragments [rows/32][K/16][64][8],
 // lane = row%32 + 32*((col%16)/8).  A GEMM workgroup then fetches each 32 x 16 fragment as one
@@ -255,11 +271,12 @@ int slk_gemm_mfma256_qkv_rope(hipStream_t s, const void* A, const void* Wp, cons
                               const int32_t* active_idx, int N, int n_pad, const void* rope_tab, void* q, void* kc,
                               void* vc);
 int slk_rope_kv_write(hipStream_t s, int dtype, const float* qkv, int S, size_t sstride, const int32_t* active_idx,
-                      const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc);
+                      const int32_t* m_dev, int m_upper, int H, int dh, int N, int n_pad, const void* rope_tab, void* q, void* kc, void* vc,
+                      int v_half);
 int slk_swiglu(hipStream_t s, int dtype, const float* gu, int S, size_t sstride, const int32_t* m_dev, int m_upper,
                int dff, void* a, int tiled, int interleaved);
 int slk_kv_read(hipStream_t s, int dtype, const void* kc, const void* vc, int B, int H, int N, int n_pad, int dh,
-                void* k_out, void* v_out);
+                void* k_out, void* v_out, int v_half);
 int slk_fill_zero(hipStream_t s, void* p, size_t bytes);
 int slk_copy_rows(hipStream_t s, int dtype, const void* src, void* dst, const int32_t* m_dev, int m_upper, int d);
 // gemm_generic.hip:  C[m, n] (fp32, ldc) = A[m, k] (T) . W[n, k]^T (T); optional row map for the output

@@ -16,7 +16,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import control, posterior
+from oracle import control, model, posterior
 from paper_2602_06412_amd import binding as B
 from paper_2602_06412_amd import workloads as wl
 from tests.gpu_util import DEV, check_logits, dev, oracle_cfg, weights_to_device
@@ -261,6 +261,52 @@ def test_kv_cache_matches_oracle_and_is_permanent():
             for l in range(shape.n_layers):
                 for a, b_ in zip(snaps[ti][l], snaps[ti - 1][l]):
                     assert torch.equal(a[0, li], b_[0, li])
+    finally:
+        sess.close()
+
+
+@pytest.mark.parametrize("scale,what", [(3.0e5, "beyond the half range"), (2.0e-6, "below the normal half range")])
+def test_v_cache_container_at_the_ends_of_its_range(scale, what):
+    """The bf16 route keeps V, rounded to bf16, in a half-precision container (attention multiplies it by
+    half-precision probabilities).  With the V projection scaled by 3e5 many |V| exceed 65504: they are stored
+    saturated, never as infinity (a zero probability times infinity would be NaN), and the logits stay
+    finite.  Scaled by 2e-6 all |V| fall below the smallest normal half 2^-14: they are kept to the container's
+    absolute resolution 2^-24, not flushed to zero.  Every value between those ends is held exactly, which
+    the other cache tests check."""
+    shape = wl.S_BF16
+    w = wl.make_weights(shape, seed=5)
+    for lw in w["layers"]:
+        lw["wv"] = (lw["wv"].float() * scale).to(lw["wv"].dtype)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    N = 96
+    tokens_np = wl.prompt_uniform(2, N, shape.vocab, shape.mask_id)
+    sess = B.Session(shape, weights_to_device(w), 1, N)
+    try:
+        zero = torch.zeros(N, dtype=torch.uint8, device=DEV)
+        sess.step(dev(tokens_np, torch.int32), zero.clone(), zero, dev(np.array([1e-3], dtype=np.float32)), 1, 0, N, 0)
+        torch.cuda.synchronize()
+        vg = sess.kv_read(0)[1][0].to(torch.float64).cpu().numpy()
+        # layer 0's V from the definition: rnd(rnd(rmsnorm(emb)) Wv^T)
+        L0 = w64["layers"][0]
+        h = cfg.rnd(model.rmsnorm(w64["emb"][tokens_np], L0["attn_norm"], cfg.rms_eps))
+        v = cfg.rnd(h @ L0["wv"].T).reshape(N, cfg.n_heads, cfg.d_head)
+        assert np.isfinite(vg).all()
+        assert torch.isfinite(sess.logits_view(1).float()).all()
+        if scale > 1:
+            big = np.abs(v) > 65504
+            assert big.mean() > 0.05, "the case must reach the end of the range"
+            # 65504 read back as bf16 is 65536 (the nearest bf16 value)
+            assert np.all(np.abs(vg[big]) == 65536.0) and np.all(np.sign(vg[big]) == np.sign(v[big]))
+            ok = ~big & (np.abs(v) < 6.0e4)
+            err = np.abs(vg[ok] - v[ok])
+            assert np.all(err <= 2.0 ** (np.floor(np.log2(np.maximum(np.abs(v[ok]), 1e-30))) - 7))
+        else:
+            assert (np.abs(v) < 2.0 ** -14).all() and (np.abs(v) > 2.0 ** -22).mean() > 0.5
+            # container resolution 2^-24 (half a step each way), plus the bf16 rounding of the read-back and the
+            # one-spacing slack of an fp32 sum that sits on a bf16 rounding boundary
+            err = np.abs(vg - v)
+            assert np.all(err <= 2.0 ** -25 + 2.0 ** (np.floor(np.log2(np.maximum(np.abs(v), 1e-30))) - 7))
+            assert (vg != 0).mean() > 0.9
     finally:
         sess.close()
 
