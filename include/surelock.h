@@ -126,6 +126,12 @@ int sl_bind_weights(sl_ctx *ctx, void *stream, const sl_weights *plain /* host s
  *                                         which one lane holds the K Q^T accumulator, so P.V
  *                                         needs no transpose
  * (sl_kv_cache_read returns the plain layout.)
+ * On the matrix-core route (bf16, d_h = 128) a V element is the value rounded to bf16, held in the
+ * 16 bits of an IEEE half: the attention kernels multiply V by half-precision probabilities and the
+ * matrix cores take both operands in one format.  Every bf16 value with 2^-14 <= |v| <= 65504 is held
+ * exactly; smaller magnitudes are kept to a multiple of 2^-24; larger ones are stored as +-65504 (never
+ * as infinity).  sl_kv_cache_read converts back to bf16.  K elements and everything on the other routes
+ * are plain values of type T.
  * sl_kv_cache_bind zero-fills the buffer (enqueued on `stream`). */
 int sl_kv_cache_bytes(const sl_ctx *ctx, int32_t batch, int32_t n_seq, size_t *out);
 int sl_kv_cache_bind(sl_ctx *ctx, void *stream, void *kv, size_t bytes, int32_t batch, int32_t n_seq);

@@ -225,23 +225,13 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
     for (int mb = 0; mb < 4; ++mb) va[0][mb] = vt_lds[mb * 32];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) va[1][mb] = vt_lds[2 * DH + mb * 32];
-    // running max of tile t while those first reads are in flight
-    float mx = sc_cur[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sc_cur[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     // The reference point of the exponentials follows the running max only in jumps of more than
     // kMaxLag (in the exp2 domain): a stale reference is exact mathematics (numerator and
     // denominator carry the same factor, at most 2^kMaxLag), and O is then rescaled on a tile only
     // when some query of the wave really jumped.  With near-uniform scores the max of 32 queries
     // creeps up on almost every tile, and rescaling 64 accumulators each time cost a quarter of
     // the kernel.  First tile: m_run = -inf, so every query jumps (alpha = 0 on a zero O).
-    const float m_cand = fmaxf(m_run, mx);    // finite: every tile holds at least one real key
-    const float m_new = (m_cand - m_run) * sc > kMaxLag ? m_cand : m_run;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
-    const float mb_ = m_new * sc;
+    float mx = sc_cur[0][0], m_new = 0.f, alpha = 1.f, mb_ = 0.f;
     float psum = 0.f, pa = 0.f, pb = 0.f;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -272,22 +262,44 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(const bf16_t* __
           sc_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], qf[ks], sc_next[kb], 0, 0, 0);
         }
       }
-      // Softmax of tile t, one pair of probabilities (2pr, 2pr+1 of this lane: register v of block
-      // kb, for P^T step 2*kb + v/8) per two slots: the exponentials, then the sum and the rounding
-      // to a pair of halves.  The empty asm statements tie each piece to its slot: without them the
-      // compiler sinks the whole softmax below the last MFMA.
-      {
-        const int pr = i >> 1;
-        const int x = 2 * pr, kb = x >> 4, v = x & 15, stp = 2 * kb + (v >> 3), e = v & 7;
-        if ((i & 1) == 0) {
-          pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
-          pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
-          asm volatile("" : "+v"(pa), "+v"(pb));
+      // Vector work of tile t, tied to its slot by the empty asm statements (without them the compiler
+      // sinks all of it below the last MFMA).  Slots 0..3: the tile's row max, a dependent chain that
+      // would otherwise hold the first MFMA back (the MFMAs of these slots add tile t-1 and do not need
+      // it); the two lanes of a query exchange their halves with a lane-half swap, a vector-ALU
+      // instruction.  Slots 4..31: the softmax, one pair of probabilities (2pr, 2pr+1 of this lane:
+      // register v of block kb, for P^T step 2*kb + v/8) at a time, exponentials in one slot, sum and
+      // rounding to a pair of halves in the next; the last four slots carry two such pieces each.
+      if (i < 4) {
+        const int kb = i >> 1, v0 = (i & 1) * 8;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) mx = fmaxf(mx, sc_cur[kb][v0 + v]);
+        if (i == 3) {
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+          mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          const float m_cand = fmaxf(m_run, mx);    // finite: every tile holds at least one real key
+          m_new = (m_cand - m_run) * sc > kMaxLag ? m_cand : m_run;
+          alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
+          mb_ = m_new * sc;
+          asm volatile("" : "+v"(m_new), "+v"(alpha), "+v"(mb_));
         } else {
-          psum += pa + pb;
-          uint32_t hw = pack_half2(pa, pb);
-          asm volatile("" : "+v"(hw), "+v"(psum));
-          p_new[stp][e >> 1] = hw;
+          asm volatile("" : "+v"(mx));
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < (i < 28 ? 1 : 2); ++u) {
+          const int piece = i < 28 ? i - 4 : 24 + 2 * (i - 28) + u;      // 32 pieces: (pair, half of its work)
+          const int pr = piece >> 1;
+          const int x = 2 * pr, kb = x >> 4, v = x & 15, stp = 2 * kb + (v >> 3), e = v & 7;
+          if ((piece & 1) == 0) {
+            pa = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v], sc, -mb_));
+            pb = __builtin_amdgcn_exp2f(fmaf(sc_cur[kb][v + 1], sc, -mb_));
+            asm volatile("" : "+v"(pa), "+v"(pb));
+          } else {
+            psum += pa + pb;
+            uint32_t hw = pack_half2(pa, pb);
+            asm volatile("" : "+v"(hw), "+v"(psum));
+            p_new[stp][e >> 1] = hw;
+          }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -473,7 +485,10 @@ __global__ __launch_bounds__(256, 3) void attention_trio_kernel(const bf16_t* __
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sv[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    {   // the two lanes of a query exchange their halves' maxima (a lane-half swap: vector ALU, no LDS trip)
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
     // the reference of the exponentials follows the running max only in jumps (see kMaxLag)
     const float m_cand = fmaxf(m_run, mx);
     const float m_new = (m_cand - m_run) * sc > kMaxLag ? m_cand : m_run;
