@@ -81,7 +81,7 @@ def test_c2_full_size_sampled_rows():
 
 
 def test_c2_two_sequences_reach_the_three_per_cu_attention():
-    """Two sequences of N = 1024 in one batch: 16 and then 14 row tiles x 32 heads are more workgroups than
+    """Two sequences of N = 1024 in one batch: 16, then 14, then 10 row tiles x 32 heads are more workgroups than
     CUs, so attention runs in its second form (three workgroups per CU, one half-precision value per
     probability where the other forms carry a second half).  Sampled rows of both sequences against the oracle,
     with the yardstick of the single-sequence test.  Measured: the single half raises the rms error of the
@@ -106,7 +106,8 @@ def test_c2_two_sequences_reach_the_three_per_cu_attention():
         rng = np.random.default_rng(1)
         tokens = dev(tokens_np, torch.int32)
         per_seq = [np.arange(N), np.arange(N)]
-        for t, counts in ((1, (1024, 1024)), (2, (900, 700))):
+        # third step: 10 row tiles x 32 heads = 320 workgroups, where the keys are split two ways (+ merge launch)
+        for t, counts in ((1, (1024, 1024)), (2, (900, 700)), (3, (600, 500))):
             per_seq = [a if m == len(a) else a[wl.active_positions(60 + m, len(a), m)] for a, m in zip(per_seq, counts)]
             active = np.concatenate([b * N + a for b, a in enumerate(per_seq)])
             M = len(active)
