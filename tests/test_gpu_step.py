@@ -311,6 +311,53 @@ def test_v_cache_container_at_the_ends_of_its_range(scale, what):
         sess.close()
 
 
+@pytest.mark.parametrize("N", [7680, 7650])
+def test_longest_sequence(N):
+    """The step at its longest sequence (7680 slots, the limit of UpdateMASK's selection; 120 key tiles; and 7650
+    slots, whose last key tile holds 34 slots and 30 masked ones): two
+    sequences of a one-layer bf16 model.  Step 1 computes every row (480 (row tile, head) workgroups: the
+    three-per-CU attention kernel walks all 120 tiles); step 2 computes 200 + 40 rows (the pipelined kernel with
+    the keys split over 64 workgroups per pair and the merge launch).  The oracle's attention costs M x N, so it
+    runs the block for sampled rows only, against the cache the GPU holds for the other slots (whose rows are
+    checked the same way when sampled): their K/V rows and their logits."""
+    shape = wl.Shape("small-bf16-1layer", 1, 512, 4, 128, 1536, 4160, "bf16")
+    Bn = 2
+    w = wl.make_weights(shape, seed=9, norm_gain_jitter=0.05)
+    cfg, w64 = oracle_cfg(shape), wl.weights_to_numpy64(w)
+    R = Bn * N
+    tokens_np = wl.prompt_zipf(31, R, shape.vocab, shape.mask_id)
+    sess = B.Session(shape, weights_to_device(w), Bn, N)
+    rng = np.random.default_rng(2)
+    try:
+        tokens = dev(tokens_np, torch.int32)
+        eps = dev(np.full(Bn, 1e-3, dtype=np.float32))
+        zero = torch.zeros(R, dtype=torch.uint8, device=DEV)
+        per_seq = [np.arange(N), np.arange(N)]
+        for t, counts in ((1, (N, N)), (2, (200, 40))):
+            per_seq = [a if m == len(a) else a[wl.active_positions(70 + m, len(a), m)] for a, m in zip(per_seq, counts)]
+            active = np.concatenate([b * N + a for b, a in enumerate(per_seq)])
+            M = len(active)
+            lock = dev(wl.lock_mask_from_active(R, active))
+            sess.step(tokens, zero.clone(), lock, eps, t, 0, N, 0, m_upper=M, new_lock=torch.zeros_like(lock))
+            torch.cuda.synchronize()
+            assert int(sess.cu_active[-1].item()) == M
+            assert np.array_equal(sess.active_idx[:M].cpu().numpy(), active)
+            kg, vg = (x.to(torch.float64).cpu().numpy() for x in sess.kv_read(0))
+            for b in range(Bn):
+                a = per_seq[b]
+                pos = np.unique(np.concatenate([rng.choice(a, size=6, replace=False), [a[0], a[-1]]]))
+                Kc, Vc = kg[b].copy(), vg[b].copy()
+                x = model.layer_active(cfg, w64["layers"][0], w64["emb"][tokens_np[b * N + pos]], pos, Kc, Vc)
+                for got, want in ((kg[b][pos], Kc[pos]), (vg[b][pos], Vc[pos])):
+                    err = np.abs(got - want)
+                    assert np.all(err <= 2.0 ** (np.floor(np.log2(np.maximum(np.abs(want), 1e-30))) - 7) + 1e-6)
+                z = model.lm_head(cfg, w64, x)
+                rows = torch.as_tensor(b * N + pos, device=DEV, dtype=torch.long)
+                check_logits(sess.logits_view(t)[rows].double().cpu().numpy(), z, shape.storage, f"N={N} t={t} sequence {b}")
+    finally:
+        sess.close()
+
+
 def test_m_upper_tight_and_errors():
     shape = wl.C1
     w = weights_to_device(wl.make_weights(shape, seed=1))
