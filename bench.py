@@ -308,7 +308,10 @@ def main():
         "config": {"workload": DESCRIBE["c5"] + "; value = whole SureLock step with every row active (sum M = %d); "
                                "`sweep` samples the lock schedule" % M0,
                    "N": r5.N, "batch": r5.Bn, "M": M0, "d_model": d, "n_heads": shape.n_heads, "d_head": shape.d_head,
-                   "d_ff": shape.d_ff, "vocab": V, "n_layers": shape.n_layers},
+                   "d_ff": shape.d_ff, "vocab": V, "n_layers": shape.n_layers,
+                   "arithmetic": "bf16 storage and MFMA operands, fp32 accumulation; attention's P.V product on half-precision "
+                                 "operands (V cached as the half image of its bf16 value, probabilities rounded to half: "
+                                 "11 significant bits where a bf16 attention keeps 8)"},
         "rows_per_s": round(M0 / ms0 * 1e3),
         "roofline": roof,
         "achievable": ach_peaks,
